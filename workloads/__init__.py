@@ -1,0 +1,116 @@
+"""Seeded synthetic inputs for the five benchmark configurations.
+
+This module serves both the CPU oracle's tests and the GPU tests / benchmark.
+It holds none of the method's arithmetic: it draws fp32 numbers from torch's
+CPU generator and lets torch convert them to bfloat16 (a library routine).
+Every tensor is a CPU torch.bfloat16 tensor; `bits()` views one as uint16.
+
+The shapes and value distributions are those of the workload definition: the
+three GEMM problems follow the paper's Section 5.1 "Benchmark problems"
+(square, batched, large-K; here in bf16 and at the sizes the workload fixes),
+the two block configurations take the layer shapes of Sections 5.2.4
+(768 -> 3072 -> 768, GELU) and 5.2.5 (4096 -> 14336 -> 4096, SwiGLU, 32 query /
+8 key-value heads of width 128).  They stand in for the benchmark-suite
+problems and the model block the paper measured, none of which is available.
+The seed is the paper's (Section 5.1: seed 42).
+"""
+import zlib
+
+import numpy as np
+import torch
+
+SEED = 42
+
+
+def _generator(name):
+    g = torch.Generator(device="cpu")
+    g.manual_seed((SEED * 1000003 + zlib.crc32(name.encode())) & 0x7FFFFFFFFFFFFFFF)
+    return g
+
+
+def uniform(shape, name):
+    """fp32 uniform on [-1, 1), converted to bf16."""
+    x = torch.rand(shape, generator=_generator(name), dtype=torch.float32) * 2.0 - 1.0
+    return x.to(torch.bfloat16)
+
+
+def normal(shape, std, name):
+    """fp32 normal with the given standard deviation, converted to bf16."""
+    x = torch.randn(shape, generator=_generator(name), dtype=torch.float32) * float(std)
+    return x.to(torch.bfloat16)
+
+
+def small_int(shape, lo, hi, name):
+    """Integers in [lo, hi], exactly representable in bf16 (|v| <= 256)."""
+    assert -256 <= lo <= hi <= 256
+    x = torch.randint(lo, hi + 1, shape, generator=_generator(name), dtype=torch.int32)
+    return x.to(torch.float32).to(torch.bfloat16)
+
+
+def permutation(n, name):
+    return torch.randperm(n, generator=_generator(name))
+
+
+def choice_rows(M, count, name, edges=()):
+    """Sorted sample of row indices: the given edge rows plus `count` random ones."""
+    g = _generator(name)
+    r = torch.randperm(M, generator=g)[: min(count, M)].tolist()
+    s = sorted(set(int(e) for e in edges if 0 <= e < M) | set(r))
+    return np.asarray(s, dtype=np.int64)
+
+
+def bits(t):
+    """uint16 numpy view of a CPU bfloat16 tensor."""
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+def from_bits(a):
+    """CPU bfloat16 tensor sharing memory with a uint16 numpy array."""
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16)
+
+
+# ---- the five configurations ------------------------------------------------
+
+def config1(n=512):
+    """Single GEMM C = A B, uniform[-1,1), no epilogue."""
+    return {"A": uniform((n, n), "c1.A"), "B": uniform((n, n), "c1.B")}
+
+
+def config2(n=8192):
+    """Square GEMM, inputs ~ N(0,1), fused bias ~ N(0,1)."""
+    return {"A": normal((n, n), 1.0, "c2.A"), "B": normal((n, n), 1.0, "c2.B"),
+            "bias": normal((n,), 1.0, "c2.bias")}
+
+
+def config3a(batch=128, n=512):
+    """Batched GEMM, uniform[-1,1)."""
+    return {"A": uniform((batch, n, n), "c3a.A"), "B": uniform((batch, n, n), "c3a.B")}
+
+
+def config3b(m=256, n=256, k=131072):
+    """Large-K GEMM, entries ~ N(0, variance 1/K)."""
+    std = float(k) ** -0.5
+    return {"A": normal((m, k), std, "c3b.A"), "B": normal((k, n), std, "c3b.B")}
+
+
+def config4(tokens=8192, d=768, dff=3072):
+    """GPT-small-shaped block GEMMs: weights and biases ~ N(0, std 0.02), activations ~ N(0,1)."""
+    return {
+        "X": normal((tokens, d), 1.0, "c4.X"),
+        "Wqkv": normal((3 * d, d), 0.02, "c4.Wqkv"), "bqkv": normal((3 * d,), 0.02, "c4.bqkv"),
+        "W1": normal((dff, d), 0.02, "c4.W1"), "b1": normal((dff,), 0.02, "c4.b1"),
+        "W2": normal((d, dff), 0.02, "c4.W2"), "b2": normal((d,), 0.02, "c4.b2"),
+        "R": normal((tokens, d), 1.0, "c4.R"),
+    }
+
+
+def config5(tokens=2048, d=4096, dff=14336, q_heads=32, kv_heads=8, head_dim=128):
+    """Llama-3-8B-shaped block GEMMs: weights ~ N(0, std 0.02), no biases."""
+    nqkv = (q_heads + 2 * kv_heads) * head_dim
+    return {
+        "X": normal((tokens, d), 1.0, "c5.X"),
+        "Wqkv": normal((nqkv, d), 0.02, "c5.Wqkv"),
+        "Wg": normal((dff, d), 0.02, "c5.Wg"), "Wu": normal((dff, d), 0.02, "c5.Wu"),
+        "Wd": normal((d, dff), 0.02, "c5.Wd"),
+        "R": normal((tokens, d), 1.0, "c5.R"),
+    }
