@@ -1,0 +1,109 @@
+"""Benchmark: bf16 GEMM + epilogue TFLOP/s and % of the MI355X bf16 MFMA peak.
+
+A step is one pass of the hot path (config lookup, tiled MFMA main loop, fused epilogue) over
+the headline workload: the square GEMM M = N = K = 8192 with fused bias add (inputs ~ N(0,1),
+seed 42), inputs resident in HBM.  Prints ONE JSON line.  `--all` adds every other
+configuration (batched, large-K split-K, the GPT- and Llama-shaped block GEMMs) under "others".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6        # 256 CU x 4096 FLOP/clk/CU x 2.4 GHz, dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def time_calls(fn, steps, warmup):
+    """Mean milliseconds per call: HIP events on the stream the kernels are launched on."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / steps
+
+
+def cpu_baseline(rows=1024, n=8192):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
+    import numpy as np
+    import workloads as wl
+    from oracle import ref
+    c = wl.config2(n)
+    sel = np.linspace(0, n - 1, rows).astype(np.int64)
+    t0 = time.perf_counter()
+    ref.gemm_epilogue(c["A"], c["B"], False, bias=c["bias"], rows=sel)
+    dt = time.perf_counter() - t0
+    return {"value": 2.0 * rows * n * n / dt / 1e12, "unit": "TFLOP/s", "cores": ref.num_threads(), "kind": "oracle",
+            "sample": f"{rows} of {n} output rows of the {n}^3 + bias workload (all columns, full K), "
+                      f"{dt:.1f} s; the oracle also forms the |A||B| bound in the same pass", "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--all", action="store_true", help="also time the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--n", type=int, default=8192, help="size of the square workload (default: the headline 8192)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists here)")
+
+    import torch
+    import paper_2604_26666_amd as fact
+    import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    fact.lib()
+
+    n = args.n
+    c = wl.config2(n)
+    A, B, bias = c["A"].cuda(), c["B"].cuda(), c["bias"].cuda()
+    C = torch.empty(n, n, dtype=torch.bfloat16, device="cuda")
+    ep = fact.Epilogue(bias=bias)
+
+    def step():
+        fact.binding.check(fact.fact_gemm(n, n, n, A, n, B, n, 0, C, n, ep))
+
+    ms = time_calls(step, args.steps, args.warmup)
+    flops = 2.0 * n * n * n
+    tflops = flops / (ms * 1e-3) / 1e12
+    rc, cfg, split = fact.fact_select_config(1, n, n, n, 0, 0)
+    tile = fact.fact_config_info(cfg)
+    alg_bytes = 2.0 * (3 * n * n + n)
+
+    out = {
+        "metric": "bf16 GEMM+epilogue TFLOP/s and % of MI355X bf16 MFMA peak per config",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"square GEMM M=N=K={n}, bf16 ~N(0,1) seed 42, fp32 accumulate, bf16 out, fused bias",
+                   "tile": f"{tile[0]}x{tile[1]}x64, {tile[2]}x{tile[3]} waves", "config_id": cfg, "split_k": split},
+        "pct_of_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": alg_bytes,
+                     "kernel_ms": round(ms, 5)},
+    }
+    if args.all:
+        from paper_2604_26666_amd import workbench
+        out["others"] = workbench.time_all(args.steps, args.warmup)
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,191 @@
+/*
+ * fact.h - C ABI of the MI355X (gfx950) bf16 GEMM + fused-epilogue library.
+ *
+ * The library computes what the paper's synthesized kernels compute: dense
+ * GEMMs (square, batched, large-K; paper Section 5.1 "Benchmark problems") and
+ * the two-GEMM feed-forward patterns with fused activation epilogues (Section
+ * 5.2.4 "MLP with GELU", Section 5.2.5 "SwiGLU MLP"), with reduced-precision
+ * inputs and an fp32 accumulator (Listing 1: reduced-precision inputs with fp32
+ * accumulator).  Here the inputs and outputs are bf16.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     allocates nothing, frees nothing and keeps no pointer after it returns.
+ *   - Matrices are row-major; every leading dimension (ld*) and batch stride is
+ *     in ELEMENTS, not bytes.
+ *   - bf16 = upper 16 bits of IEEE binary32.  Products are accumulated in fp32;
+ *     the result is rounded to bf16 once (nearest, ties to even) at the store.
+ *   - trans_b == 0: B is [K][N]  (C = A B).
+ *     trans_b == 1: B is [N][K]  (C = A B^T, the weight layout of a linear layer).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
+ *     is enqueued on it; the calls do not synchronise.
+ *   - Return value: FACT_OK or a negative fact_status.  Arguments are validated
+ *     on the host before anything is launched; on error nothing is launched.  No
+ *     exception crosses the boundary and the library never aborts.
+ *   - Aliasing: C may alias `residual` exactly (same pointer, same ld): each
+ *     element is read before it is written by the same thread.  Any other overlap
+ *     of an output with an input is undefined.
+ *   - Shapes: any positive M, N, K.  The MFMA path needs 16-byte aligned A and B
+ *     with lda, ldb and K multiples of 8 (and N a multiple of 8 when trans_b == 0);
+ *     anything else runs a slower guarded kernel with the same results contract.
+ */
+#ifndef FACT_H
+#define FACT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fact_status {
+    FACT_OK = 0,
+    FACT_ERR_NULL = -1,         /* a required pointer is NULL */
+    FACT_ERR_DIM = -2,          /* a dimension is <= 0 or a leading dimension / stride is too small */
+    FACT_ERR_ALIGN = -3,        /* a pointer is not 2-byte aligned (bf16) / workspace not 16-byte aligned */
+    FACT_ERR_LAYOUT = -4,       /* trans_b is not 0 or 1, or the layout is not allowed with the epilogue */
+    FACT_ERR_EPILOGUE = -5,     /* unknown activation, bias given with the gated epilogue, odd N with it */
+    FACT_ERR_WORKSPACE = -6,    /* workspace missing or too small */
+    FACT_ERR_UNSUPPORTED = -7,  /* unknown tile configuration id, split factor out of range */
+    FACT_ERR_HIP = -8           /* a HIP call failed; text via fact_last_error() */
+} fact_status;
+
+typedef enum fact_act {
+    FACT_ACT_NONE = 0,
+    FACT_ACT_GELU_TANH = 1,     /* 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3)))  (Section 5.2.4: GELU epilogue) */
+    FACT_ACT_SILU_GATE = 2      /* SiLU(gate) * up  (Section 5.2.5: gate projection with SiLU, times up projection) */
+} fact_act;
+
+/*
+ * Fused epilogue, applied in registers in this order:
+ *     z = acc + bias[n];  z = act(z);  z = z + residual[m][n];  C[m][n] = bf16(z)
+ * bias     : bf16[Nout] device pointer or NULL.
+ * residual : bf16[M][ldr] device pointer or NULL; ldr in elements, >= Nout.
+ * act      : a fact_act.  With FACT_ACT_SILU_GATE the GEMM's B must be given with
+ *            trans_b == 1 as [N][K] with N even: rows 0..N/2-1 are the gate
+ *            weights, rows N/2..N-1 the up weights; the output then has
+ *            Nout = N/2 columns and bias must be NULL.  Otherwise Nout = N.
+ * In the batched call the residual of batch b starts stride_r elements after
+ * that of batch b-1 (stride_r may be 0: one residual shared by all); bias is
+ * shared by all batches.
+ */
+typedef struct fact_epilogue {
+    const void *bias;
+    const void *residual;
+    int64_t ldr;
+    int64_t stride_r;
+    int32_t act;
+} fact_epilogue;
+
+/* ---- entry points --------------------------------------------------------------------- */
+
+/*
+ * C[M][Nout] = epilogue(A[M][K] x B).  One data-parallel 2-D tiled launch (the paper's
+ * "Data Parallel" grid schedule, Section 4.2 Action 2; Section 5.2.1).  ep may be NULL.
+ * The tile configuration comes from the per-shape table (the shadow of the paper's
+ * registry lookup, Section 4.2 Action 6).
+ */
+int fact_gemm(int64_t M, int64_t N, int64_t K,
+              const void *A, int64_t lda,
+              const void *B, int64_t ldb, int trans_b,
+              void *C, int64_t ldc,
+              const fact_epilogue *ep, void *stream);
+
+/*
+ * C[b] = epilogue(A[b] x B[b]) for b in [0, batch): one launch, grid.z = batch
+ * (Section 5.1, Problem 3; Section 5.2.2).  Strides are in elements and may be 0 for
+ * an operand shared by every batch (not for C).
+ */
+int fact_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
+                      const void *A, int64_t lda, int64_t stride_a,
+                      const void *B, int64_t ldb, int64_t stride_b, int trans_b,
+                      void *C, int64_t ldc, int64_t stride_c,
+                      const fact_epilogue *ep, void *stream);
+
+/*
+ * Large-K GEMM (Section 5.1, Problem 6; Section 5.2.3): K is cut into split_k
+ * contiguous ranges, each range's product is written as an fp32 partial into the
+ * workspace (fp32 because reduced precision is not enough there, Section 5.2.3), and a
+ * second kernel adds the partials in ascending range order in fp32, applies the
+ * epilogue and rounds once.  split_k == 0 lets the table choose; split_k == 1 (or a
+ * choice of 1) runs the plain kernel and needs no workspace.  Bit-reproducible: the
+ * order of additions is fixed.
+ * ws: device pointer, 16-byte aligned, at least
+ * fact_gemm_splitk_workspace_bytes(M, N, K, split_k) bytes; contents are scratch.
+ */
+int fact_gemm_splitk(int64_t M, int64_t N, int64_t K,
+                     const void *A, int64_t lda,
+                     const void *B, int64_t ldb, int trans_b,
+                     void *C, int64_t ldc,
+                     const fact_epilogue *ep,
+                     int split_k, void *ws, size_t ws_bytes, void *stream);
+
+/* Bytes of workspace fact_gemm_splitk needs for this shape and split_k (0 = the table's
+ * choice).  Returns 0 when no workspace is needed or the arguments are invalid. */
+size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k);
+
+/*
+ * Two-GEMM feed-forward block (pattern p2 of Sections 5.2.4 and 5.2.5), two launches
+ * on one stream:
+ *     H = act(X W1^T + b1)      bf16 [T][d_ff], written to the caller's H buffer
+ *     Y = H W2^T + b2 + R       bf16 [T][d_model]
+ * X  : bf16 [T][d_model].        W1 : bf16 [d_ff][d_model].
+ * W1u: with FACT_ACT_SILU_GATE, the up-projection weights bf16 [d_ff][d_model] and W1 is
+ *      the gate projection; must be NULL otherwise.
+ * b1 : bf16 [d_ff] or NULL (must be NULL with FACT_ACT_SILU_GATE).
+ * W2 : bf16 [d_model][d_ff].     b2 : bf16 [d_model] or NULL.
+ * R  : residual bf16 [T][d_model] or NULL (Y may alias R).
+ * All matrices dense (leading dimension = row length).
+ * ws : workspace for a split-K second GEMM, fact_block_mlp_workspace_bytes() bytes
+ *      (may be NULL when that returns 0).
+ */
+int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
+                   const void *X, const void *W1, const void *W1u, const void *b1, int act,
+                   const void *W2, const void *b2, const void *R,
+                   void *H, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+size_t fact_block_mlp_workspace_bytes(int64_t T, int64_t d_model, int64_t d_ff, int act);
+
+/* ---- tile configurations: the auto-tuning surface (Section 4.2 Action 5) ---------------- */
+
+/* Number of compiled tile configurations; ids are 0 .. fact_num_configs()-1. */
+int fact_num_configs(void);
+
+/* Describes configuration `id`: macro-tile rows/cols, waves along M and N, LDS bytes.
+ * Any out pointer may be NULL.  Returns FACT_ERR_UNSUPPORTED for a bad id. */
+int fact_config_info(int id, int *tile_m, int *tile_n, int *waves_m, int *waves_n, int *lds_bytes);
+
+/* The table's choice for a shape (host logic only, no GPU needed): writes the tile
+ * configuration id and the split-K factor (>= 1).  batch >= 1.  Returns FACT_OK, or an
+ * error if the shape is invalid.  config_id is -1 when the shape can only run on the
+ * guarded fallback kernel (unaligned dimensions). */
+int fact_select_config(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b, int act,
+                       int *config_id, int *split_k);
+
+/*
+ * fact_gemm_batched with the tile configuration, split factor and tile-row group size
+ * forced: the entry point the on-device sweep uses.  config_id < 0, split_k <= 0 and
+ * group_m <= 0 mean "table's choice".  split_k > 1 needs ws (see fact_gemm_splitk) and
+ * batch == 1.  A configuration whose LDS or alignment needs the shape cannot meet
+ * returns FACT_ERR_UNSUPPORTED (recorded by the sweep as a launch failure, as in
+ * Section 5.1 "Auto-tuning methodology").
+ */
+int fact_gemm_ex(int64_t batch, int64_t M, int64_t N, int64_t K,
+                 const void *A, int64_t lda, int64_t stride_a,
+                 const void *B, int64_t ldb, int64_t stride_b, int trans_b,
+                 void *C, int64_t ldc, int64_t stride_c,
+                 const fact_epilogue *ep,
+                 int config_id, int split_k, int group_m,
+                 void *ws, size_t ws_bytes, void *stream);
+
+/* ---- misc ------------------------------------------------------------------------------- */
+
+const char *fact_status_string(int status);   /* static string, never NULL */
+const char *fact_last_error(void);            /* text of the last HIP failure on this thread, "" if none */
+int fact_version(void);                       /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FACT_H */

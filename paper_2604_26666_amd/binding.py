@@ -1,0 +1,177 @@
+"""ctypes binding of include/fact.h.  Argument marshalling only.
+
+Functions carry the C names and take the C arguments in the C order.  A pointer argument
+may be an int (device address), None (NULL) or a torch tensor (its data_ptr() is passed);
+`stream` may be None (torch's current stream), an int, or a torch.cuda.Stream.
+Return codes are returned unchanged by the fact_* functions; `check()` raises on error.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfact_gemm.so")
+
+ACT_NONE = 0
+ACT_GELU_TANH = 1
+ACT_SILU_GATE = 2
+
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+_ptr = ctypes.c_void_p
+_size = ctypes.c_size_t
+
+
+class FactError(RuntimeError):
+    pass
+
+
+class _CEpilogue(ctypes.Structure):
+    _fields_ = [("bias", _ptr), ("residual", _ptr), ("ldr", _i64), ("stride_r", _i64), ("act", ctypes.c_int32)]
+
+
+class Epilogue:
+    """Mirror of the C struct fact_epilogue."""
+
+    def __init__(self, bias=None, residual=None, ldr=0, stride_r=0, act=ACT_NONE):
+        self.bias, self.residual, self.ldr, self.stride_r, self.act = bias, residual, ldr, stride_r, act
+
+    def _c(self):
+        return _CEpilogue(_addr(self.bias), _addr(self.residual), int(self.ldr), int(self.stride_r), int(self.act))
+
+
+_lib = None
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded shared library.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FactError(f"{_LIB_PATH} is missing: build it with `python -m paper_2604_26666_amd.build` "
+                            "(or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(_LIB_PATH)
+        ep = ctypes.POINTER(_CEpilogue)
+        L.fact_gemm.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _int, _ptr, _i64, ep, _ptr]
+        L.fact_gemm_batched.argtypes = [_i64, _i64, _i64, _i64, _ptr, _i64, _i64, _ptr, _i64, _i64, _int,
+                                        _ptr, _i64, _i64, ep, _ptr]
+        L.fact_gemm_splitk.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _int, _ptr, _i64, ep,
+                                       _int, _ptr, _size, _ptr]
+        L.fact_gemm_splitk_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+        L.fact_gemm_splitk_workspace_bytes.restype = _size
+        L.fact_block_mlp.argtypes = [_i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr, _int, _ptr, _ptr, _ptr,
+                                     _ptr, _ptr, _ptr, _size, _ptr]
+        L.fact_block_mlp_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+        L.fact_block_mlp_workspace_bytes.restype = _size
+        L.fact_gemm_ex.argtypes = [_i64, _i64, _i64, _i64, _ptr, _i64, _i64, _ptr, _i64, _i64, _int,
+                                   _ptr, _i64, _i64, ep, _int, _int, _int, _ptr, _size, _ptr]
+        L.fact_num_configs.argtypes = []
+        ip = ctypes.POINTER(_int)
+        L.fact_config_info.argtypes = [_int, ip, ip, ip, ip, ip]
+        L.fact_select_config.argtypes = [_i64, _i64, _i64, _i64, _int, _int, ip, ip]
+        L.fact_status_string.argtypes = [_int]
+        L.fact_status_string.restype = ctypes.c_char_p
+        L.fact_last_error.argtypes = []
+        L.fact_last_error.restype = ctypes.c_char_p
+        L.fact_version.argtypes = []
+        for name in ("fact_gemm", "fact_gemm_batched", "fact_gemm_splitk", "fact_block_mlp", "fact_gemm_ex",
+                     "fact_num_configs", "fact_config_info", "fact_select_config", "fact_version"):
+            getattr(L, name).restype = _int
+        _lib = L
+    return _lib
+
+
+def _addr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())       # torch tensor
+
+
+def _stream(s):
+    if s is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(s, int):
+        return s
+    return int(s.cuda_stream)
+
+
+def _ep(ep):
+    return None if ep is None else ctypes.byref(ep._c())
+
+
+def check(rc, what="fact call"):
+    if rc != 0:
+        raise FactError(f"{what} failed: {rc} ({fact_status_string(rc)}) {fact_last_error()}")
+    return rc
+
+
+def fact_gemm(M, N, K, A, lda, B, ldb, trans_b, C, ldc, ep=None, stream=None):
+    return lib().fact_gemm(M, N, K, _addr(A), lda, _addr(B), ldb, int(trans_b), _addr(C), ldc, _ep(ep), _stream(stream))
+
+
+def fact_gemm_batched(batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, trans_b, C, ldc, stride_c,
+                      ep=None, stream=None):
+    return lib().fact_gemm_batched(batch, M, N, K, _addr(A), lda, stride_a, _addr(B), ldb, stride_b, int(trans_b),
+                                   _addr(C), ldc, stride_c, _ep(ep), _stream(stream))
+
+
+def fact_gemm_splitk(M, N, K, A, lda, B, ldb, trans_b, C, ldc, ep, split_k, ws, ws_bytes, stream=None):
+    return lib().fact_gemm_splitk(M, N, K, _addr(A), lda, _addr(B), ldb, int(trans_b), _addr(C), ldc, _ep(ep),
+                                  int(split_k), _addr(ws), int(ws_bytes), _stream(stream))
+
+
+def fact_gemm_splitk_workspace_bytes(M, N, K, split_k):
+    return int(lib().fact_gemm_splitk_workspace_bytes(M, N, K, int(split_k)))
+
+
+def fact_block_mlp(T, d_model, d_ff, X, W1, W1u, b1, act, W2, b2, R, H, Y, ws, ws_bytes, stream=None):
+    return lib().fact_block_mlp(T, d_model, d_ff, _addr(X), _addr(W1), _addr(W1u), _addr(b1), int(act),
+                                _addr(W2), _addr(b2), _addr(R), _addr(H), _addr(Y), _addr(ws), int(ws_bytes),
+                                _stream(stream))
+
+
+def fact_block_mlp_workspace_bytes(T, d_model, d_ff, act):
+    return int(lib().fact_block_mlp_workspace_bytes(T, d_model, d_ff, int(act)))
+
+
+def fact_gemm_ex(batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, trans_b, C, ldc, stride_c, ep,
+                 config_id, split_k, group_m, ws, ws_bytes, stream=None):
+    return lib().fact_gemm_ex(batch, M, N, K, _addr(A), lda, stride_a, _addr(B), ldb, stride_b, int(trans_b),
+                              _addr(C), ldc, stride_c, _ep(ep), int(config_id), int(split_k), int(group_m),
+                              _addr(ws), int(ws_bytes), _stream(stream))
+
+
+def fact_num_configs():
+    return int(lib().fact_num_configs())
+
+
+def fact_config_info(cfg_id):
+    """Returns (tile_m, tile_n, waves_m, waves_n, lds_bytes) or raises for a bad id."""
+    v = [_int() for _ in range(5)]
+    check(lib().fact_config_info(int(cfg_id), *[ctypes.byref(x) for x in v]), "fact_config_info")
+    return tuple(x.value for x in v)
+
+
+def fact_select_config(batch, M, N, K, trans_b, act):
+    """Returns (status, config_id, split_k)."""
+    c, s = _int(-2), _int(0)
+    rc = lib().fact_select_config(batch, M, N, K, int(trans_b), int(act), ctypes.byref(c), ctypes.byref(s))
+    return rc, c.value, s.value
+
+
+def fact_status_string(rc):
+    return lib().fact_status_string(int(rc)).decode()
+
+
+def fact_last_error():
+    return lib().fact_last_error().decode()
+
+
+def fact_version():
+    return int(lib().fact_version())

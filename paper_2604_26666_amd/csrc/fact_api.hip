@@ -1,0 +1,413 @@
+// C ABI of the library: argument validation, shape -> tile-configuration lookup, launches.
+// Host code only; every step of the computation runs in the kernels of gemm_kernel.h and
+// aux_kernels.hip.
+#include "../../include/fact.h"
+#include "launch.h"
+
+#include <cstdio>
+#include <cstring>
+
+namespace fact {
+
+static const ConfigDesc g_configs[] = {
+#define FACT_CFG(id, bm, bn, wm, wn) {id, bm, bn, wm, wn, fact_launch_cfg##id},
+#include "configs.def"
+#undef FACT_CFG
+};
+static constexpr int kNumConfigs = (int)(sizeof(g_configs) / sizeof(g_configs[0]));
+
+static constexpr int kNumCU = 256;
+static constexpr int kLdsPerCU = 160 * 1024;
+static constexpr int kMaxGridZ = 65535;
+
+static thread_local char g_last_error[256] = "";
+
+static int hip_fail(hipError_t e, const char *what)
+{
+    std::snprintf(g_last_error, sizeof g_last_error, "%s: %s", what, hipGetErrorString(e));
+    return FACT_ERR_HIP;
+}
+
+// ---- the per-shape table (filled by the on-device sweep) and the model behind it -----------
+
+struct TableRow {
+    int64_t batch, M, N, K;
+    int trans_b, gated;
+    int cfg, split, group_m;
+};
+static const TableRow g_table[] = {
+#include "tile_table.inc"
+    {0, 0, 0, 0, 0, 0, -1, 0, 0}   // sentinel
+};
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Can the MFMA kernel take these operands at all?  (Dimensions only; pointer alignment is
+// checked separately at launch.)
+static bool fast_dims_ok(int64_t M, int64_t N, int64_t K, int trans_b)
+{
+    if (K % 8) return false;
+    if (!trans_b && N % 8) return false;
+    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX - 64) return false;
+    return true;
+}
+
+static int wgs_per_cu(const ConfigDesc &c)
+{
+    int by_lds = kLdsPerCU / c.lds_bytes();
+    // accumulators per lane + staging/fragment registers, out of 512 per lane at one wave per SIMD
+    int acc = (c.bm / c.wm / 32) * (c.bn / c.wn / 32) * 16;
+    int by_regs = 512 / (acc + 128);
+    int occ = by_lds < by_regs ? by_lds : by_regs;
+    return occ < 1 ? 1 : occ;
+}
+
+// Relative throughput of one CU running this configuration (larger tiles reuse operands more).
+static double tile_efficiency(const ConfigDesc &c)
+{
+    const double per_k = (double)(c.bm + c.bn) / ((double)c.bm * c.bn);   // operand bytes per MAC
+    return 1.0 / (1.0 + 48.0 * per_k);
+}
+
+struct Plan {
+    int cfg = -1;      // -1: fallback kernel
+    int split = 1;
+    int group_m = 4;
+};
+
+static double model_time(const ConfigDesc &c, int64_t batch, int64_t M, int64_t nout, int64_t K, bool gated, int split)
+{
+    const int64_t bn_out = gated ? c.bn / 2 : c.bn;
+    const int64_t tiles = ((M + c.bm - 1) / c.bm) * ((nout + bn_out - 1) / bn_out) * batch * split;
+    const int occ = wgs_per_cu(c);
+    const int64_t slots = (int64_t)kNumCU * occ;
+    const int64_t rounds = (tiles + slots - 1) / slots;
+    const double k_eff = (double)((K + split - 1) / split) + 192.0;      // fixed prologue/epilogue cost
+    return (double)rounds * occ * (double)c.bm * c.bn * k_eff / tile_efficiency(c);
+}
+
+static Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b, int act, bool allow_split)
+{
+    Plan pl;
+    const bool gated = act == FACT_ACT_SILU_GATE;
+    if (!fast_dims_ok(M, N, K, trans_b)) return pl;
+    for (const TableRow *r = g_table; r->cfg >= 0; ++r) {
+        if (r->batch == batch && r->M == M && r->N == N && r->K == K && r->trans_b == trans_b &&
+            r->gated == (int)gated && (allow_split || r->split <= 1)) {
+            pl.cfg = r->cfg; pl.split = r->split < 1 ? 1 : r->split; pl.group_m = r->group_m > 0 ? r->group_m : 4;
+            return pl;
+        }
+    }
+    const int64_t nout = gated ? N / 2 : N;
+    double best = 0;
+    for (int i = 0; i < kNumConfigs; ++i) {
+        const ConfigDesc &c = g_configs[i];
+        if (gated && !c.gate_capable()) continue;
+        int max_split = 1;
+        if (allow_split && batch == 1) {
+            max_split = (int)(K / 1024);
+            if (max_split > 256) max_split = 256;
+            if (max_split < 1) max_split = 1;
+        }
+        for (int s = 1; s <= max_split; s *= 2) {
+            double t = model_time(c, batch, M, nout, K, gated, s);
+            if (s > 1) t += 2.0 * s * (double)M * N * 24.0;     // partial write + read, in MAC-equivalents
+            if (pl.cfg < 0 || t < best) { best = t; pl.cfg = i; pl.split = s; }
+        }
+    }
+    pl.group_m = 4;
+    return pl;
+}
+
+// ---- validation -----------------------------------------------------------------------------
+
+struct Problem {
+    int64_t batch, M, N, K;
+    const void *A; int64_t lda, stride_a;
+    const void *B; int64_t ldb, stride_b; int trans_b;
+    const void *B_up;     // gated with separate weights, else nullptr
+    void *C; int64_t ldc, stride_c;
+    fact_epilogue ep;
+};
+
+static int validate(const Problem &q)
+{
+    if (!q.A || !q.B || !q.C) return FACT_ERR_NULL;
+    if (q.batch <= 0 || q.M <= 0 || q.N <= 0 || q.K <= 0) return FACT_ERR_DIM;
+    if (q.batch > kMaxGridZ) return FACT_ERR_DIM;
+    if (q.trans_b != 0 && q.trans_b != 1) return FACT_ERR_LAYOUT;
+    const int act = q.ep.act;
+    if (act != FACT_ACT_NONE && act != FACT_ACT_GELU_TANH && act != FACT_ACT_SILU_GATE) return FACT_ERR_EPILOGUE;
+    const bool gated = act == FACT_ACT_SILU_GATE;
+    if (gated) {
+        if (q.ep.bias) return FACT_ERR_EPILOGUE;
+        if (q.N % 2) return FACT_ERR_EPILOGUE;
+        if (!q.trans_b) return FACT_ERR_LAYOUT;
+    }
+    const int64_t nout = gated ? q.N / 2 : q.N;
+    if (q.lda < q.K) return FACT_ERR_DIM;
+    if (q.ldb < (q.trans_b ? q.K : q.N)) return FACT_ERR_DIM;
+    if (q.ldc < nout) return FACT_ERR_DIM;
+    if (q.ep.residual && q.ep.ldr < nout) return FACT_ERR_DIM;
+    if (q.stride_a < 0 || q.stride_b < 0 || q.stride_c < 0 || q.ep.stride_r < 0) return FACT_ERR_DIM;
+    if (q.batch > 1 && q.stride_c < (q.M - 1) * q.ldc + nout) return FACT_ERR_DIM;
+    if (q.M > INT32_MAX || q.N > INT32_MAX || q.K > INT32_MAX) return FACT_ERR_DIM;
+    const uintptr_t two = (uintptr_t)q.A | (uintptr_t)q.B | (uintptr_t)q.C | (uintptr_t)q.ep.bias |
+                          (uintptr_t)q.ep.residual | (uintptr_t)q.B_up;
+    if (two & 1u) return FACT_ERR_ALIGN;
+    return FACT_OK;
+}
+
+static size_t splitk_ws_bytes(int64_t M, int64_t N, int split)
+{
+    return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+// ---- the one launch path every entry point goes through ----------------------------------------
+
+static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_table_split,
+               void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    int rc = validate(q);
+    if (rc != FACT_OK) return rc;
+    const bool gated = q.ep.act == FACT_ACT_SILU_GATE;
+    const int64_t nout = gated ? q.N / 2 : q.N;
+
+    Plan pl = make_plan(q.batch, q.M, q.N, q.K, q.trans_b, q.ep.act, allow_table_split);
+    if (cfg_id >= 0) {
+        if (cfg_id >= kNumConfigs) return FACT_ERR_UNSUPPORTED;
+        if (!fast_dims_ok(q.M, q.N, q.K, q.trans_b)) return FACT_ERR_UNSUPPORTED;
+        if (gated && !g_configs[cfg_id].gate_capable()) return FACT_ERR_UNSUPPORTED;
+        pl.cfg = cfg_id;
+        if (split <= 0) pl.split = 1;
+    }
+    if (split > 0) pl.split = split;
+    if (group_m > 0) pl.group_m = group_m;
+    if (pl.split > 1 && q.batch != 1) return FACT_ERR_UNSUPPORTED;
+    if (pl.split > kMaxGridZ) return FACT_ERR_UNSUPPORTED;
+
+    // operands the MFMA kernel reads with 16-byte loads
+    const bool ptr_ok = aligned16(q.A) && aligned16(q.B) && (!q.B_up || aligned16(q.B_up)) &&
+                        q.lda % 8 == 0 && q.ldb % 8 == 0 && q.stride_a % 8 == 0 && q.stride_b % 8 == 0;
+    if (pl.cfg >= 0 && !ptr_ok) {
+        if (cfg_id >= 0) return FACT_ERR_UNSUPPORTED;
+        pl.cfg = -1;
+    }
+    if (pl.cfg < 0) pl.split = 1;     // the fallback never splits
+
+    GemmArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.A = (const __bf16 *)q.A;
+    a.B = (const __bf16 *)q.B;
+    a.B_up = gated ? (q.B_up ? (const __bf16 *)q.B_up : (const __bf16 *)q.B + nout * q.ldb) : nullptr;
+    a.C = (__bf16 *)q.C;
+    a.bias = (const __bf16 *)q.ep.bias;
+    a.res = (const __bf16 *)q.ep.residual;
+    a.lda = q.lda; a.ldb = q.ldb; a.ldc = q.ldc; a.ldr = q.ep.ldr;
+    a.stride_a = q.stride_a; a.stride_b = q.stride_b; a.stride_c = q.stride_c; a.stride_r = q.ep.stride_r;
+    a.M = (int)q.M; a.N = (int)q.N; a.K = (int)q.K;
+    a.act = q.ep.act;
+    a.splits = 1;
+    a.group_m = pl.group_m;
+    // 8-byte vector access to C / residual / bias in the epilogue
+    a.vec_store = (nout % 4 == 0) && q.ldc % 4 == 0 && ((uintptr_t)q.C & 7u) == 0 && q.stride_c % 4 == 0 &&
+                  (!q.ep.bias || ((uintptr_t)q.ep.bias & 7u) == 0) &&
+                  (!q.ep.residual || (((uintptr_t)q.ep.residual & 7u) == 0 && q.ep.ldr % 4 == 0 && q.ep.stride_r % 4 == 0));
+
+    hipError_t e;
+    if (pl.cfg < 0) {
+        e = launch_fallback_gemm(a, q.trans_b != 0, (int)q.batch, stream);
+        return e == hipSuccess ? FACT_OK : hip_fail(e, "fallback gemm launch");
+    }
+
+    const ConfigDesc &c = g_configs[pl.cfg];
+    const int bn_out = gated ? c.bn / 2 : c.bn;
+    const int64_t tiles_m = (q.M + c.bm - 1) / c.bm, tiles_n = (nout + bn_out - 1) / bn_out;
+    if (tiles_m * tiles_n > INT32_MAX / 2) return FACT_ERR_DIM;
+    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
+
+    if (pl.split > 1) {
+        // K ranges are multiples of the 64-element staging step
+        int64_t kps = (q.K + pl.split - 1) / pl.split;
+        kps = (kps + BK - 1) / BK * BK;
+        const int splits = (int)((q.K + kps - 1) / kps);
+        if (splits <= 1) {
+            pl.split = 1;
+        } else {
+            const size_t need = splitk_ws_bytes(q.M, q.N, pl.split);
+            if (!ws) return FACT_ERR_WORKSPACE;
+            if (!aligned16(ws)) return FACT_ERR_ALIGN;
+            if (ws_bytes < need) return FACT_ERR_WORKSPACE;
+            a.splits = splits;
+            a.k_per_split = (int)kps;
+            a.P = (float *)ws;
+        }
+    }
+    e = c.launch(a, q.trans_b != 0, a.splits > 1 ? a.splits : (int)q.batch, stream);
+    if (e != hipSuccess) return hip_fail(e, "gemm launch");
+    if (a.splits > 1) {
+        e = launch_splitk_reduce(a, stream);
+        if (e != hipSuccess) return hip_fail(e, "split-K reduce launch");
+    }
+    return FACT_OK;
+}
+
+static fact_epilogue ep_or_none(const fact_epilogue *ep)
+{
+    fact_epilogue e;
+    std::memset(&e, 0, sizeof e);
+    if (ep) e = *ep;
+    return e;
+}
+
+}  // namespace fact
+
+using namespace fact;
+
+extern "C" {
+
+int fact_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+              int trans_b, void *C, int64_t ldc, const fact_epilogue *ep, void *stream)
+{
+    Problem q{1, M, N, K, A, lda, 0, B, ldb, 0, trans_b, nullptr, C, ldc, 0, ep_or_none(ep)};
+    return run(q, -1, 1, 0, false, nullptr, 0, (hipStream_t)stream);
+}
+
+int fact_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
+                      const void *A, int64_t lda, int64_t stride_a,
+                      const void *B, int64_t ldb, int64_t stride_b, int trans_b,
+                      void *C, int64_t ldc, int64_t stride_c,
+                      const fact_epilogue *ep, void *stream)
+{
+    Problem q{batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, trans_b, nullptr, C, ldc, stride_c, ep_or_none(ep)};
+    return run(q, -1, 1, 0, false, nullptr, 0, (hipStream_t)stream);
+}
+
+int fact_gemm_splitk(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                     int trans_b, void *C, int64_t ldc, const fact_epilogue *ep,
+                     int split_k, void *ws, size_t ws_bytes, void *stream)
+{
+    if (split_k < 0) return FACT_ERR_UNSUPPORTED;
+    Problem q{1, M, N, K, A, lda, 0, B, ldb, 0, trans_b, nullptr, C, ldc, 0, ep_or_none(ep)};
+    return run(q, -1, split_k, 0, true, ws, ws_bytes, (hipStream_t)stream);
+}
+
+size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || split_k < 0) return 0;
+    int s = split_k;
+    if (s == 0) {
+        // the table's choice may depend on layout and epilogue; report the largest over them
+        for (int tb = 0; tb < 2; ++tb)
+            for (int act = 0; act < 3; ++act) {
+                if (act == FACT_ACT_SILU_GATE && (!tb || N % 2)) continue;
+                Plan pl = make_plan(1, M, N, K, tb, act, true);
+                if (pl.cfg >= 0 && pl.split > s) s = pl.split;
+            }
+    }
+    return splitk_ws_bytes(M, N, s);
+}
+
+int fact_gemm_ex(int64_t batch, int64_t M, int64_t N, int64_t K,
+                 const void *A, int64_t lda, int64_t stride_a,
+                 const void *B, int64_t ldb, int64_t stride_b, int trans_b,
+                 void *C, int64_t ldc, int64_t stride_c,
+                 const fact_epilogue *ep, int config_id, int split_k, int group_m,
+                 void *ws, size_t ws_bytes, void *stream)
+{
+    Problem q{batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, trans_b, nullptr, C, ldc, stride_c, ep_or_none(ep)};
+    return run(q, config_id, split_k, group_m, true, ws, ws_bytes, (hipStream_t)stream);
+}
+
+size_t fact_block_mlp_workspace_bytes(int64_t T, int64_t d_model, int64_t d_ff, int act)
+{
+    if (T <= 0 || d_model <= 0 || d_ff <= 0) return 0;
+    (void)act;
+    Plan pl = make_plan(1, T, d_model, d_ff, 1, FACT_ACT_NONE, true);
+    return pl.cfg >= 0 ? splitk_ws_bytes(T, d_model, pl.split) : 0;
+}
+
+int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
+                   const void *X, const void *W1, const void *W1u, const void *b1, int act,
+                   const void *W2, const void *b2, const void *R,
+                   void *H, void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!X || !W1 || !W2 || !H || !Y) return FACT_ERR_NULL;
+    if (act != FACT_ACT_NONE && act != FACT_ACT_GELU_TANH && act != FACT_ACT_SILU_GATE) return FACT_ERR_EPILOGUE;
+    const bool gated = act == FACT_ACT_SILU_GATE;
+    if (gated && !W1u) return FACT_ERR_NULL;
+    if (!gated && W1u) return FACT_ERR_EPILOGUE;
+    if (gated && b1) return FACT_ERR_EPILOGUE;
+    if (T <= 0 || d_model <= 0 || d_ff <= 0) return FACT_ERR_DIM;
+
+    // GEMM 1: H = act(X W1^T + b1); gated: contraction over 2*d_ff columns, gate then up
+    fact_epilogue e1;
+    std::memset(&e1, 0, sizeof e1);
+    e1.bias = b1;
+    e1.act = act;
+    Problem q1{1, T, gated ? 2 * d_ff : d_ff, d_model, X, d_model, 0, W1, d_model, 0, 1,
+               gated ? W1u : nullptr, H, d_ff, 0, e1};
+    int rc = run(q1, -1, 1, 0, false, nullptr, 0, (hipStream_t)stream);
+    if (rc != FACT_OK) return rc;
+
+    // GEMM 2: Y = H W2^T + b2 + R  (may split K = d_ff when the table says so and ws allows)
+    fact_epilogue e2;
+    std::memset(&e2, 0, sizeof e2);
+    e2.bias = b2;
+    e2.residual = R;
+    e2.ldr = d_model;
+    e2.act = FACT_ACT_NONE;
+    Problem q2{1, T, d_model, d_ff, H, d_ff, 0, W2, d_ff, 0, 1, nullptr, Y, d_model, 0, e2};
+    const size_t need = fact_block_mlp_workspace_bytes(T, d_model, d_ff, act);
+    if (need > 0 && (!ws || ws_bytes < need)) return FACT_ERR_WORKSPACE;
+    return run(q2, -1, 0, 0, need > 0, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int fact_num_configs(void) { return kNumConfigs; }
+
+int fact_config_info(int id, int *tile_m, int *tile_n, int *waves_m, int *waves_n, int *lds_bytes)
+{
+    if (id < 0 || id >= kNumConfigs) return FACT_ERR_UNSUPPORTED;
+    const ConfigDesc &c = g_configs[id];
+    if (tile_m) *tile_m = c.bm;
+    if (tile_n) *tile_n = c.bn;
+    if (waves_m) *waves_m = c.wm;
+    if (waves_n) *waves_n = c.wn;
+    if (lds_bytes) *lds_bytes = c.lds_bytes();
+    return FACT_OK;
+}
+
+int fact_select_config(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b, int act,
+                       int *config_id, int *split_k)
+{
+    if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return FACT_ERR_DIM;
+    if (trans_b != 0 && trans_b != 1) return FACT_ERR_LAYOUT;
+    if (act < 0 || act > 2) return FACT_ERR_EPILOGUE;
+    if (act == FACT_ACT_SILU_GATE && (N % 2 || !trans_b)) return FACT_ERR_EPILOGUE;
+    Plan pl = make_plan(batch, M, N, K, trans_b, act, true);
+    if (config_id) *config_id = pl.cfg;
+    if (split_k) *split_k = pl.split;
+    return FACT_OK;
+}
+
+const char *fact_status_string(int status)
+{
+    switch (status) {
+    case FACT_OK: return "ok";
+    case FACT_ERR_NULL: return "required pointer is NULL";
+    case FACT_ERR_DIM: return "bad dimension, leading dimension or stride";
+    case FACT_ERR_ALIGN: return "pointer alignment";
+    case FACT_ERR_LAYOUT: return "bad layout flag";
+    case FACT_ERR_EPILOGUE: return "bad epilogue";
+    case FACT_ERR_WORKSPACE: return "workspace missing or too small";
+    case FACT_ERR_UNSUPPORTED: return "unsupported configuration";
+    case FACT_ERR_HIP: return "HIP error";
+    default: return "unknown status";
+    }
+}
+
+const char *fact_last_error(void) { return g_last_error; }
+
+int fact_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// One tile configuration's kernels (both B layouts).  Built once per row of configs.def with
+// -DFACT_ID=.. -DFACT_BM=.. -DFACT_BN=.. -DFACT_WM=.. -DFACT_WN=..
+#include "launch.h"
+
+namespace fact {
+
+#define FACT_CAT2(a, b) a##b
+#define FACT_CAT(a, b) FACT_CAT2(a, b)
+
+template <bool TRANS_B>
+static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t stream)
+{
+    auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B>;
+    constexpr int lds = 2 * (FACT_BM + FACT_BN) * LDS_ROW;
+    static bool attr_set[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev]) {
+        e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    dim3 grid((unsigned)(args.tiles_m * args.tiles_n), 1, (unsigned)grid_z);
+    dim3 block(FACT_WM * FACT_WN * 64, 1, 1);
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
+    return hipGetLastError();
+}
+
+hipError_t FACT_CAT(fact_launch_cfg, FACT_ID)(const GemmArgs &args, bool trans_b, int grid_z, hipStream_t stream)
+{
+    return trans_b ? launch_one<true>(args, grid_z, stream) : launch_one<false>(args, grid_z, stream);
+}
+
+}  // namespace fact

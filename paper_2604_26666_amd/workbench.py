@@ -1,0 +1,172 @@
+"""The benchmark configurations as runnable cases, for bench.py --all and the on-device sweep.
+
+Each case names one GEMM of the five configurations (shapes from the workload definition;
+see workloads/__init__.py), allocates its seeded inputs on the GPU and launches it through
+the C ABI.  PyTorch is used for device memory and event timing only.
+"""
+import torch
+
+from . import binding as fact
+
+PEAK_BF16_TFLOPS = 2516.6
+PEAK_HBM_GBS = 8000.0
+
+
+class Case:
+    def __init__(self, name, M, N, K, trans_b, act=fact.ACT_NONE, bias=False, residual=False, batch=1,
+                 splitk=False, maker=None):
+        self.name, self.M, self.N, self.K, self.trans_b, self.act = name, M, N, K, trans_b, act
+        self.has_bias, self.has_res, self.batch, self.splitk = bias, residual, batch, splitk
+        self.maker = maker
+        self.t = None
+
+    @property
+    def nout(self):
+        return self.N // 2 if self.act == fact.ACT_SILU_GATE else self.N
+
+    @property
+    def flops(self):
+        return 2.0 * self.M * self.N * self.K * self.batch
+
+    @property
+    def min_bytes(self):
+        b = self.batch * (self.M * self.K + self.K * self.N + self.M * self.nout) * 2.0
+        if self.has_bias:
+            b += self.nout * 2.0
+        if self.has_res:
+            b += self.batch * self.M * self.nout * 2.0
+        return b
+
+    def alloc(self):
+        if self.t is None:
+            t = {k: (v.cuda() if v is not None else None) for k, v in self.maker().items()}
+            shape = (self.batch, self.M, self.nout) if self.batch > 1 else (self.M, self.nout)
+            t["C"] = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+            t["ws"] = None
+            self.t = t
+        return self.t
+
+    def free(self):
+        self.t = None
+
+    def _ws(self, nbytes):
+        t = self.t
+        if nbytes > 0 and (t["ws"] is None or t["ws"].numel() < nbytes):
+            t["ws"] = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        return t["ws"]
+
+    def run(self, cfg=-1, split=0, group_m=0):
+        """Launch once.  cfg/split/group_m <= 0 (split 0) leave the choice to the table.  Returns the status."""
+        t = self.alloc()
+        ep = fact.Epilogue(bias=t.get("bias"), residual=t.get("R"), ldr=self.nout,
+                           stride_r=self.M * self.nout if self.batch > 1 else 0, act=self.act)
+        lda = self.K
+        ldb = self.K if self.trans_b else self.N
+        if not self.splitk and split == 0:
+            split = 1
+        need = fact.fact_gemm_splitk_workspace_bytes(self.M, self.N, self.K, split) if split != 1 else 0
+        ws = self._ws(need)
+        return fact.fact_gemm_ex(self.batch, self.M, self.N, self.K, t["A"], lda, self.M * self.K,
+                                 t["B"], ldb, self.K * self.N, self.trans_b, t["C"], self.nout, self.M * self.nout,
+                                 ep, cfg, split, group_m, ws, need)
+
+
+def cases(names=None):
+    import workloads as wl
+
+    def c1():
+        c = wl.config1()
+        return {"A": c["A"], "B": c["B"]}
+
+    def c2():
+        c = wl.config2()
+        return {"A": c["A"], "B": c["B"], "bias": c["bias"]}
+
+    def c3a():
+        c = wl.config3a()
+        return {"A": c["A"], "B": c["B"]}
+
+    def c3b():
+        c = wl.config3b()
+        return {"A": c["A"], "B": c["B"]}
+
+    c4 = {}
+    c5 = {}
+
+    def g4():
+        if not c4:
+            c4.update(wl.config4())
+        return c4
+
+    def g5():
+        if not c5:
+            c5.update(wl.config5())
+        return c5
+
+    def h4():     # the down projection's input: a stand-in with the distribution of GELU outputs
+        return wl.normal((8192, 3072), 0.5, "c4.Hstandin")
+
+    def h5():
+        return wl.normal((2048, 14336), 0.3, "c5.Hstandin")
+
+    import torch as _t
+    G = fact.ACT_GELU_TANH
+    S = fact.ACT_SILU_GATE
+    allc = [
+        Case("c1.square512", 512, 512, 512, 0, maker=c1),
+        Case("c2.square8192+bias", 8192, 8192, 8192, 0, bias=True, maker=c2),
+        Case("c3a.batched128x512", 512, 512, 512, 0, batch=128, maker=c3a),
+        Case("c3b.largeK", 256, 256, 131072, 0, splitk=True, maker=c3b),
+        Case("c4.qkv+bias", 8192, 2304, 768, 1, bias=True,
+             maker=lambda: {"A": g4()["X"], "B": g4()["Wqkv"], "bias": g4()["bqkv"]}),
+        Case("c4.up+bias+gelu", 8192, 3072, 768, 1, act=G, bias=True,
+             maker=lambda: {"A": g4()["X"], "B": g4()["W1"], "bias": g4()["b1"]}),
+        Case("c4.down+bias+res", 8192, 768, 3072, 1, bias=True, residual=True,
+             maker=lambda: {"A": h4(), "B": g4()["W2"], "bias": g4()["b2"], "R": g4()["R"]}),
+        Case("c5.qkv", 2048, 6144, 4096, 1, maker=lambda: {"A": g5()["X"], "B": g5()["Wqkv"]}),
+        Case("c5.gate_up_silu", 2048, 28672, 4096, 1, act=S,
+             maker=lambda: {"A": g5()["X"], "B": _t.cat([g5()["Wg"], g5()["Wu"]])}),
+        Case("c5.down+res", 2048, 4096, 14336, 1, residual=True,
+             maker=lambda: {"A": h5(), "B": g5()["Wd"], "R": g5()["R"]}),
+    ]
+    if names:
+        allc = [c for c in allc if any(c.name.startswith(n) for n in names)]
+    return allc
+
+
+def time_case(case, steps=20, warmup=5, cfg=-1, split=0, group_m=0):
+    """Mean ms per launch with device events on the launch stream, or None if the configuration
+    is refused (recorded by the sweep as a launch failure)."""
+    case.alloc()
+    rc = case.run(cfg, split, group_m)
+    if rc != 0:
+        return None
+    for _ in range(warmup - 1):
+        case.run(cfg, split, group_m)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        case.run(cfg, split, group_m)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / steps
+
+
+def report(case, ms):
+    tf = case.flops / (ms * 1e-3) / 1e12
+    gbs = case.min_bytes / (ms * 1e-3) / 1e9
+    return {"ms": round(ms, 5), "tflops": round(tf, 2), "pct_mfma_peak": round(100 * tf / PEAK_BF16_TFLOPS, 2),
+            "min_traffic_GBs": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / PEAK_HBM_GBS, 2)}
+
+
+def time_all(steps=20, warmup=5, names=None):
+    out = {}
+    for c in cases(names):
+        ms = time_case(c, steps, warmup)
+        rc, cfg, split = fact.fact_select_config(c.batch, c.M, c.N, c.K, c.trans_b, c.act)
+        r = report(c, ms) if ms else {"error": "refused"}
+        r["config_id"], r["split_k"] = cfg, (split if c.splitk else 1)
+        out[c.name] = r
+        c.free()
+    return out

@@ -1,0 +1,277 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+
+Exact tests (identity, permutations, small integers, rounding ties) demand equal bits;
+tolerance tests demand |got - z| <= 1e-2 * bound + 1e-3 per element and a relative
+Frobenius error <= 5e-3 (the workload definition's criteria, written out in oracle/check.py).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_26666_amd as fact
+import workloads as wl
+from oracle import check, ref
+
+pytestmark = pytest.mark.gpu
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the GPU; none is visible")
+    import os
+    assert os.path.exists(fact.lib_path()), "libfact_gemm.so is not built"
+    fact.lib()
+
+
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def ncfg():
+    return fact.fact_num_configs()
+
+
+def gate_capable(cfg):
+    bm, bn, wm, wn, _ = fact.fact_config_info(cfg)
+    return (bn // wn // 32) % 2 == 0
+
+
+# ---- exact: layouts, tile mapping, every configuration -------------------------------------
+
+@pytest.mark.parametrize("trans_b", [0, 1])
+def test_permutation_matrices_every_config(trans_b):
+    n = 512
+    X = wl.uniform((n, 384), "gp.X")                  # C = P X must reproduce rows of X bit for bit
+    p = wl.permutation(n, "gp.perm")
+    P = torch.eye(n, dtype=torch.bfloat16)[p].contiguous()
+    Bmat = X if not trans_b else X.t().contiguous()
+    want = wl.bits(X[p].contiguous())
+    for cfg in range(ncfg()):
+        got = G().gemm(P, Bmat, trans_b, cfg=cfg)
+        assert np.array_equal(got, want), f"cfg {cfg}"
+    # B = I: C = A
+    A = wl.uniform((300, n), "gp.A")
+    eye = torch.eye(n, dtype=torch.bfloat16)
+    for cfg in range(ncfg()):
+        assert np.array_equal(G().gemm(A, eye, trans_b, cfg=cfg), wl.bits(A)), f"cfg {cfg}"
+
+
+@pytest.mark.parametrize("trans_b", [0, 1])
+@pytest.mark.parametrize("shape", [(300, 264, 200), (520, 776, 1096), (64, 64, 64), (1, 8, 8), (257, 520, 72)])
+def test_small_integers_bit_exact_every_config(shape, trans_b):
+    M, N, K = shape
+    A = wl.small_int((M, K), -2, 2, f"gi.A{shape}")
+    B = wl.small_int((K, N), -2, 2, f"gi.B{shape}")
+    Bs = B if not trans_b else B.t().contiguous()
+    r = ref.gemm_epilogue(A, Bs, bool(trans_b))
+    assert np.abs(r.z).max() <= 256 * 64       # exactly representable sums; bf16 rounding is the oracle's
+    for cfg in range(ncfg()):
+        got = G().gemm(A, Bs, trans_b, cfg=cfg, pad=8 if cfg % 2 else 0)
+        check.assert_bits_equal(got, r, what=f"cfg {cfg} {shape} tb {trans_b}")
+
+
+def test_rounding_ties_through_the_mfma_path_and_the_fallback():
+    a = torch.tensor([1.0078125, 1.0234375, 1.0078125, -1.0078125] * 16, dtype=torch.float32)
+    b = torch.tensor([1.5, 1.25] * 32, dtype=torch.float32)
+    for K, entry in ((1, "fallback"), (64, "mfma")):
+        A = torch.zeros(64, K)
+        A[:, 0] = a
+        B = torch.zeros(K, 64)
+        B[0, :] = b
+        A, B = A.to(torch.bfloat16), B.to(torch.bfloat16)
+        r = ref.gemm_epilogue(A, B)
+        rc, cfg, _ = fact.fact_select_config(1, 64, 64, K, 0, 0)
+        assert (cfg < 0) == (entry == "fallback")
+        got = G().gemm(A, B, 0)
+        check.assert_bits_equal(got, r, what=entry)
+        w = ref.widen(got)
+        assert w[0, 0] == 1.515625 and w[1, 0] == 1.53125 and w[0, 1] == 1.2578125 and w[3, 0] == -1.515625
+
+
+@pytest.mark.parametrize("trans_b", [0, 1])
+def test_tiny_and_unaligned_shapes_use_the_guarded_kernel(trans_b):
+    for (M, N, K) in [(1, 1, 1), (2, 3, 5), (5, 7, 3), (17, 33, 9), (33, 20, 100)]:
+        A = wl.small_int((M, K), -3, 3, f"gt.A{M}{N}{K}")
+        B = wl.small_int((K, N), -3, 3, f"gt.B{M}{N}{K}")
+        Bs = B if not trans_b else B.t().contiguous()
+        bias = wl.small_int((N,), -3, 3, "gt.bias")
+        res = wl.small_int((M, N), -3, 3, "gt.res")
+        r = ref.gemm_epilogue(A, Bs, bool(trans_b), bias=bias, residual=res)
+        got = G().gemm(A, Bs, trans_b, bias=bias, residual=res, pad=3)
+        check.assert_bits_equal(got, r, what=f"{(M, N, K)}")
+
+
+def test_all_ones_closed_form():
+    for K in (64, 256, 1024, 4096):
+        A = torch.ones(256, K, dtype=torch.bfloat16)
+        B = torch.ones(K, 256, dtype=torch.bfloat16)
+        got = ref.widen(G().gemm(A, B, 0))
+        assert (got == K).all()
+
+
+# ---- epilogues --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("trans_b", [0, 1])
+def test_epilogue_wiring_exact(trans_b):
+    # integer bias / residual keep every value exact: bits must match
+    M, N, K = 200, 328, 136
+    A = wl.small_int((M, K), -2, 2, "ge.A")
+    B = wl.small_int((K, N), -2, 2, "ge.B")
+    Bs = B if not trans_b else B.t().contiguous()
+    bias = wl.small_int((N,), -5, 5, "ge.bias")
+    res = wl.small_int((M, N), -5, 5, "ge.res")
+    for kw in (dict(bias=bias), dict(residual=res), dict(bias=bias, residual=res),
+               dict(bias=bias, residual=res, in_place=True)):
+        oracle_kw = {k: v for k, v in kw.items() if k != "in_place"}
+        r = ref.gemm_epilogue(A, Bs, bool(trans_b), **oracle_kw)
+        for cfg in (0, 3, ncfg() - 1):
+            got = G().gemm(A, Bs, trans_b, cfg=cfg, pad=4, **kw)
+            check.assert_bits_equal(got, r, what=f"{list(kw)} cfg {cfg}")
+
+
+@pytest.mark.parametrize("act", [fact.ACT_GELU_TANH, fact.ACT_SILU_GATE])
+def test_activation_epilogues_within_tolerance(act):
+    M, K, Nout = 264, 192, 328
+    X = wl.normal((M, K), 1.0, "ga.X")
+    res = wl.normal((M, Nout), 1.0, "ga.R")
+    if act == fact.ACT_SILU_GATE:
+        W = wl.normal((2 * Nout, K), 0.1, "ga.W2")
+        bias = None
+    else:
+        W = wl.normal((Nout, K), 0.1, "ga.W")
+        bias = wl.normal((Nout,), 0.5, "ga.b")
+    r = ref.gemm_epilogue(X, W, True, bias=bias, residual=res, act=act)
+    for cfg in range(ncfg()):
+        if act == fact.ACT_SILU_GATE and not gate_capable(cfg):
+            continue
+        got = G().gemm(X, W, 1, bias=bias, residual=res, act=act, cfg=cfg)
+        s = check.assert_close(got, r, what=f"act {act} cfg {cfg}")
+        assert s["max_err_ulp"] <= 1.01, s          # within one bf16 spacing of the fp64 value
+    # the table's own choice, and the split-K path with the same epilogue
+    check.assert_close(G().gemm(X, W, 1, bias=bias, residual=res, act=act), r)
+    check.assert_close(G().gemm(X, W, 1, bias=bias, residual=res, act=act, cfg=3, split=3), r)
+
+
+def test_gate_wiring_exact():
+    # gate = an integer input feature, up = 1 exactly -> out = RNE(SiLU(g)): tells the gate
+    # half from the up half (swapped, the result would be SiLU(1) * g)
+    M, K, I = 128, 64, 128
+    X = wl.small_int((M, K), -3, 3, "gg.X")
+    X[:, 0] = 1.0
+    Wg = torch.zeros(I, K)
+    Wu = torch.zeros(I, K)
+    for j in range(I):
+        Wg[j, j % K] = 1.0                        # g_j = x_{j mod K}
+    Wu[:, 0] = 1.0                                # u_j = x_0 = 1
+    W = torch.cat([Wg, Wu]).to(torch.bfloat16)
+    r = ref.gemm_epilogue(X, W, True, act=fact.ACT_SILU_GATE)
+    got = G().gemm(X, W, 1, act=fact.ACT_SILU_GATE)
+    s = check.compare(got, r)
+    assert s["ok"] and s["max_err_ulp"] <= 1.01, s
+    xs = X.to(torch.float64).numpy()
+    want = ref.silu(xs[:, np.arange(I) % K])
+    assert np.allclose(ref.widen(got), want, rtol=2 ** -7, atol=1e-6)
+
+
+# ---- random inputs, the five configurations at reduced size -------------------------------------
+
+def test_config1_full():
+    c = wl.config1()
+    r = ref.gemm_epilogue(c["A"], c["B"])
+    got = G().gemm(c["A"], c["B"], 0)
+    s = check.assert_close(got, r, what="config 1")
+    assert s["max_err_ulp"] <= 1.01
+    for cfg in range(ncfg()):
+        check.assert_close(G().gemm(c["A"], c["B"], 0, cfg=cfg), r, what=f"config 1 cfg {cfg}")
+
+
+def test_config2_reduced_with_bias():
+    c = wl.config2(1024)
+    r = ref.gemm_epilogue(c["A"], c["B"], bias=c["bias"])
+    for cfg in range(ncfg()):
+        check.assert_close(G().gemm(c["A"], c["B"], 0, bias=c["bias"], cfg=cfg, group_m=1 + cfg % 5), r,
+                           what=f"cfg {cfg}")
+
+
+def test_batched_reduced_with_distinct_permutations():
+    batch, n = 6, 256
+    X = wl.uniform((batch, n, n), "gb.X")
+    Pm = torch.stack([torch.eye(n, dtype=torch.bfloat16)[wl.permutation(n, f"gb.p{b}")] for b in range(batch)])
+    Xd, Pd = X.cuda(), Pm.cuda()
+    Cd = torch.zeros(batch, n, n, dtype=torch.bfloat16, device="cuda")
+    fact.binding.check(fact.fact_gemm_batched(batch, n, n, n, Pd, n, n * n, Xd, n, n * n, 0, Cd, n, n * n, None))
+    got = G().bits_of(Cd)
+    for b in range(batch):
+        want = wl.bits(X[b][wl.permutation(n, f"gb.p{b}")].contiguous())
+        assert np.array_equal(got[b], want), f"batch {b}"
+    # shared B (stride 0) and random data within tolerance
+    c = wl.config3a(batch, n)
+    Ad, Bd = c["A"].cuda(), c["B"].cuda()
+    fact.binding.check(fact.fact_gemm_batched(batch, n, n, n, Ad, n, n * n, Bd, n, 0, 0, Cd, n, n * n, None))
+    got = G().bits_of(Cd)
+    for b in range(batch):
+        check.assert_close(got[b], ref.gemm_epilogue(c["A"][b], c["B"][0]), what=f"batch {b}")
+
+
+@pytest.mark.parametrize("trans_b", [0, 1])
+def test_splitk_every_factor_is_exact_on_integers_and_deterministic(trans_b):
+    M, N, K = 136, 264, 2048 + 72
+    A = wl.small_int((M, K), -1, 1, "gs.A")
+    B = wl.small_int((K, N), -1, 1, "gs.B")
+    Bs = B if not trans_b else B.t().contiguous()
+    bias = wl.small_int((N,), -2, 2, "gs.b")
+    r = ref.gemm_epilogue(A, Bs, bool(trans_b), bias=bias)
+    for split in (1, 2, 3, 5, 8, 33):
+        got = G().gemm(A, Bs, trans_b, bias=bias, split=split)
+        check.assert_bits_equal(got, r, what=f"split {split}")
+    c = wl.config3b(128, 128, 8192)
+    Bs = c["B"] if not trans_b else c["B"].t().contiguous()
+    r = ref.gemm_epilogue(c["A"], Bs, bool(trans_b))
+    first = G().gemm(c["A"], Bs, trans_b, split=16)
+    check.assert_close(first, r, what="large-K reduced")
+    for _ in range(3):
+        assert np.array_equal(G().gemm(c["A"], Bs, trans_b, split=16), first)    # fixed reduction order
+    check.assert_close(G().gemm(c["A"], Bs, trans_b, split=0), r, what="table's split")
+
+
+@pytest.mark.parametrize("kind", ["gelu", "swiglu"])
+def test_block_mlp_reduced(kind):
+    T, d, dff = 520, 256, 768
+    X = wl.normal((T, d), 1.0, "gm.X")
+    W1 = wl.normal((dff, d), 0.05, "gm.W1")
+    Wu = wl.normal((dff, d), 0.05, "gm.Wu")
+    b1 = wl.normal((dff,), 0.05, "gm.b1")
+    W2 = wl.normal((d, dff), 0.05, "gm.W2")
+    b2 = wl.normal((d,), 0.05, "gm.b2")
+    R = wl.normal((T, d), 1.0, "gm.R")
+    gated = kind == "swiglu"
+    act = fact.ACT_SILU_GATE if gated else fact.ACT_GELU_TANH
+    Hd = G().poisoned(T, dff)
+    Yd = G().poisoned(T, d)
+    need = fact.fact_block_mlp_workspace_bytes(T, d, dff, act)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    rc = fact.fact_block_mlp(T, d, dff, X.cuda(), W1.cuda(), Wu.cuda() if gated else None,
+                             None if gated else b1.cuda(), act, W2.cuda(), None if gated else b2.cuda(),
+                             R.cuda(), Hd, Yd, ws, need)
+    fact.binding.check(rc, "fact_block_mlp")
+    Hg, Yg = G().bits_of(Hd), G().bits_of(Yd)
+    # end to end against the oracle's own H
+    h, y = ref.block_mlp(X, W1, Wu if gated else None, None if gated else b1, act, W2,
+                         None if gated else b2, R)
+    check.assert_close(Hg, h, what="H")
+    check.assert_close(Yg, y, what="Y end to end")
+    # stage-wise strict: the oracle's second GEMM fed the GPU's H bits
+    _, y2 = ref.block_mlp(X, W1, Wu if gated else None, None if gated else b1, act, W2,
+                          None if gated else b2, R, H_bits=Hg)
+    s = check.assert_close(Yg, y2, what="Y stage-wise")
+    assert s["max_err_ulp"] <= 1.01, s
+
+
+def test_errors_launch_nothing():
+    A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    C = G().poisoned(64, 64)
+    assert fact.fact_gemm(64, 64, 64, A, 32, A, 64, 0, C, 64, None) == -2
+    assert fact.fact_gemm_splitk(64, 64, 4096, A, 4096, A, 64, 0, C, 64, None, 4, None, 0) == -6
+    assert fact.fact_gemm_ex(1, 64, 64, 64, A, 64, 0, A, 64, 0, 0, C, 64, 0, None, 99, 0, 0, None, 0) == -7
+    assert (G().bits_of(C) == G().POISON).all()
