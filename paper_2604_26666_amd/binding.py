@@ -9,7 +9,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libfact_gemm.so")
+# FACT_GEMM_LIB selects another build of the same library (used to compare variants)
+_LIB_PATH = os.environ.get("FACT_GEMM_LIB") or os.path.join(_HERE, "libfact_gemm.so")
 
 ACT_NONE = 0
 ACT_GELU_TANH = 1

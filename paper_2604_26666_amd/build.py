@@ -24,7 +24,7 @@ def configs():
     rows = []
     with open(os.path.join(CSRC, "configs.def")) as f:
         for line in f:
-            m = re.match(r"\s*FACT_CFG\(\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*\)", line)
+            m = re.match(r"\s*FACT_CFG\(\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*\)", line)
             if m:
                 rows.append(tuple(int(x) for x in m.groups()))
     return rows
@@ -38,14 +38,18 @@ def _run(cmd):
     return out
 
 
-def build(jobs=None, verbose=False):
+def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
+    """extra_flags / lib / obj_dir exist for experiments (a variant library beside the product one)."""
+    OBJ = obj_dir
+    LIB = lib
+    FLAGS = list(globals()["FLAGS"]) + list(extra_flags)
     os.makedirs(OBJ, exist_ok=True)
     jobs = jobs or min(8, os.cpu_count() or 1)
     units = []
-    for (cid, bm, bn, wm, wn) in configs():
+    for (cid, bm, bn, wm, wn, bk, st) in configs():
         obj = os.path.join(OBJ, f"inst{cid}.o")
         units.append((obj, [HIPCC] + FLAGS + [f"-DFACT_ID={cid}", f"-DFACT_BM={bm}", f"-DFACT_BN={bn}",
-                                              f"-DFACT_WM={wm}", f"-DFACT_WN={wn}",
+                                              f"-DFACT_WM={wm}", f"-DFACT_WN={wn}", f"-DFACT_BK={bk}", f"-DFACT_STAGES={st}",
                                               "-c", os.path.join(CSRC, "inst.hip"), "-o", obj]))
     for name in ("aux_kernels", "fact_api"):
         obj = os.path.join(OBJ, name + ".o")

@@ -10,7 +10,7 @@
 namespace fact {
 
 static const ConfigDesc g_configs[] = {
-#define FACT_CFG(id, bm, bn, wm, wn) {id, bm, bn, wm, wn, fact_launch_cfg##id},
+#define FACT_CFG(id, bm, bn, wm, wn, bk, st) {id, bm, bn, wm, wn, bk, st, fact_launch_cfg##id},
 #include "configs.def"
 #undef FACT_CFG
 };
@@ -48,6 +48,7 @@ static bool fast_dims_ok(int64_t M, int64_t N, int64_t K, int trans_b)
 {
     if (K % 8) return false;
     if (!trans_b && N % 8) return false;
+    (void)0;
     if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX - 64) return false;
     return true;
 }
@@ -187,8 +188,10 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     if (pl.split > kMaxGridZ) return FACT_ERR_UNSUPPORTED;
 
     // operands the MFMA kernel reads with 16-byte loads
+    // (leading dimensions are bounded so that per-lane byte offsets inside one tile panel fit 31 bits)
     const bool ptr_ok = aligned16(q.A) && aligned16(q.B) && (!q.B_up || aligned16(q.B_up)) &&
-                        q.lda % 8 == 0 && q.ldb % 8 == 0 && q.stride_a % 8 == 0 && q.stride_b % 8 == 0;
+                        q.lda % 8 == 0 && q.ldb % 8 == 0 && q.stride_a % 8 == 0 && q.stride_b % 8 == 0 &&
+                        q.lda <= (1 << 21) && q.ldb <= (1 << 21);
     if (pl.cfg >= 0 && !ptr_ok) {
         if (cfg_id >= 0) return FACT_ERR_UNSUPPORTED;
         pl.cfg = -1;
@@ -209,10 +212,10 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     a.act = q.ep.act;
     a.splits = 1;
     a.group_m = pl.group_m;
-    // 8-byte vector access to C / residual / bias in the epilogue
-    a.vec_store = (nout % 4 == 0) && q.ldc % 4 == 0 && ((uintptr_t)q.C & 7u) == 0 && q.stride_c % 4 == 0 &&
-                  (!q.ep.bias || ((uintptr_t)q.ep.bias & 7u) == 0) &&
-                  (!q.ep.residual || (((uintptr_t)q.ep.residual & 7u) == 0 && q.ep.ldr % 4 == 0 && q.ep.stride_r % 4 == 0));
+    // 16-byte vector access to C / residual / bias in the epilogue
+    a.vec_store = (nout % 8 == 0) && q.ldc % 8 == 0 && aligned16(q.C) && q.stride_c % 8 == 0 &&
+                  (!q.ep.bias || aligned16(q.ep.bias)) &&
+                  (!q.ep.residual || (aligned16(q.ep.residual) && q.ep.ldr % 8 == 0 && q.ep.stride_r % 8 == 0));
 
     hipError_t e;
     if (pl.cfg < 0) {
@@ -229,7 +232,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     if (pl.split > 1) {
         // K ranges are multiples of the 64-element staging step
         int64_t kps = (q.K + pl.split - 1) / pl.split;
-        kps = (kps + BK - 1) / BK * BK;
+        kps = (kps + 63) / 64 * 64;
         const int splits = (int)((q.K + kps - 1) / kps);
         if (splits <= 1) {
             pl.split = 1;
@@ -243,6 +246,9 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
             a.P = (float *)ws;
         }
     }
+#ifdef FACT_DBG_TIMELINE
+    if (a.splits <= 1) a.P = (float *)ws;      // experiments only: per-work-group timestamps
+#endif
     e = c.launch(a, q.trans_b != 0, a.splits > 1 ? a.splits : (int)q.batch, stream);
     if (e != hipSuccess) return hip_fail(e, "gemm launch");
     if (a.splits > 1) {

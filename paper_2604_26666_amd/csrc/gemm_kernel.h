@@ -1,22 +1,32 @@
-// bf16 GEMM main kernel for gfx950 (CDNA4): MFMA 32x32x16 bf16 -> fp32, LDS
-// double-buffered operand staging with an XOR swizzle, 128-bit global loads,
-// register-resident fused epilogue.  This is the tile-level / kernel-level /
-// grid-level hierarchy of the paper (Section 4.2 Action 2) re-designed for
-// 64-wide wavefronts: one work-group of WGM x WGN waves owns a BM x BN macro
-// tile; each wave owns a (BM/WGM) x (BN/WGN) sub-tile made of 32x32 MFMA tiles
-// whose fp32 accumulators stay in registers for the whole K loop.
+// bf16 GEMM main kernel for gfx950 (CDNA4).
+//
+// The paper's three-level hierarchy (Section 4.2 Action 2: tile-level primitive,
+// kernel-level pipelining, grid-level schedule) re-designed for 64-wide wavefronts:
+//   tile level   : MFMA 32x32x16 bf16 -> fp32.  A work-group of WGM x WGN waves owns a
+//                  BM x BN macro tile; each wave owns a (BM/WGM) x (BN/WGN) sub-tile of
+//                  32x32 MFMA tiles whose accumulators stay in registers for the whole K loop.
+//   kernel level : a ring of STAGES LDS buffers filled by 128-bit global->LDS direct loads
+//                  (no staging registers) STAGES-1 K steps ahead of the MFMAs; the operand
+//                  fragments of each 16-deep sub-step are read from LDS into a second register
+//                  set while the MFMAs of the previous sub-step run; one barrier per K step.
+//   grid level   : 2-D data-parallel tiling with an XCD-aware tile order; grid.z is the
+//                  batch index or the split-K range.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace fact {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+#define FACT_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 enum : int { ACT_NONE = 0, ACT_GELU_TANH = 1, ACT_SILU_GATE = 2 };
 
@@ -37,21 +47,11 @@ struct GemmArgs {
     int k_per_split;        // multiple of 64
     int tiles_m, tiles_n;
     int group_m;            // tile rows walked together (L2 reuse)
-    int vec_store;          // 1: C / residual / bias allow 8-byte vector access
+    int vec_store;          // 1: C / residual / bias allow 16-byte vector access
 };
 
-constexpr int BK = 64;            // K elements staged per step
-constexpr int LDS_ROW = BK * 2;   // bytes per staged row (one 128-byte line)
-
-// Swizzle: the 16-byte chunk kc of staged row `row` lives at chunk position
-// kc ^ swz(row).  Eight consecutive rows, and eight rows 8 apart, map one chunk
-// column onto eight distinct positions, so both the fragment reads (lanes walk
-// rows) and the transposing writes (lanes walk rows 8 apart) spread over all banks.
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
-__device__ __forceinline__ uint32_t lds_off(int row, int kc)
-{
-    return (uint32_t)(row * LDS_ROW + ((kc ^ swz(row)) << 4));
-}
+constexpr uint32_t kBufferFlags = 0x00020000u;   // raw buffer descriptor word 3 (32-bit data format)
+constexpr uint32_t kOobOffset = 0x80000000u;     // beyond any descriptor's num_records (< 2^31)
 
 __device__ __forceinline__ float sigmoid_fast(float t)
 {
@@ -108,25 +108,70 @@ __device__ __forceinline__ void tile_coords(const GemmArgs &p, int pid, int &tm,
     tn = in_grp / gsz;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool TRANS_B>
+// Wait until at most N of this wave's global->LDS loads are outstanding and all its LDS
+// reads are done, then the work-group barrier.  "memory" keeps LDS accesses on their side.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier()
+{
+    __builtin_amdgcn_sched_barrier(0);       // nothing is scheduled across the barrier
+#ifdef FACT_DBG_NO_BARRIER
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory");
+#else
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+#endif
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// LDS layouts of one stage (all offsets in bytes, chunk = 16 bytes = 8 bf16):
+//  K-contiguous operand (A always; B when trans_b=1): [rows][BK] with the chunk kc of row r at
+//  chunk position kc ^ swz_k(r).  A 32-lane fragment read walks 32 consecutive rows at one kc;
+//  the XOR spreads 8 (and 16) consecutive rows over distinct bank groups.
+template <int BK>
+__device__ __forceinline__ int swz_k(int row)
+{
+    if constexpr (BK == 64) return (row ^ (row >> 3)) & 7;
+    else return ((row >> 1) ^ (row >> 3)) & 3;
+}
+//  N-contiguous operand (B when trans_b=0): [BK][BN] with the chunk nc of K-row k at position
+//  nc ^ swz_n(k).  The transposing 64-bit LDS reads of one 16-lane group touch 4 consecutive
+//  K-rows x 32 bytes; the XOR moves those rows onto distinct 32-byte bank groups.
+template <int BN>
+__device__ __forceinline__ int swz_n(int k)
+{
+    if constexpr ((BN / 8) % 16 == 0) return (k & 3) << 2;
+    else return (k & 1) << 2;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool TRANS_B, int BK, int STAGES>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_kernel(const GemmArgs p)
 {
-    constexpr int NTHR = WGM * WGN * 64;
+#if defined(__HIP_DEVICE_COMPILE__)      // the host pass only needs the kernel's symbol
+    constexpr int NWAVES = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int MT = WTM / 32, NT = WTN / 32;
+    constexpr int KC = BK / 8;                 // chunks per K-contiguous row
+    constexpr int ROWB = BK * 2;               // bytes per K-contiguous row
+    constexpr int KK = BK / 16;                // MFMA sub-steps per K step
+    constexpr int NCH = BN / 8;                // chunks per N-contiguous row
+    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
+    constexpr int STAGE = A_BYTES + B_BYTES;
+    constexpr int A_LD = A_BYTES / 1024 / NWAVES;     // direct loads (1 KB per wave each) per wave per step
+    constexpr int B_LD = B_BYTES / 1024 / NWAVES;
+    constexpr int LOADS = A_LD + B_LD;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
-    static_assert((BM * 8) % NTHR == 0, "A chunks must divide evenly over the threads");
-    constexpr int A_CH = BM * 8 / NTHR;                       // 16-byte chunks per thread per step
-    constexpr int B_CH = (BN * 8 + NTHR - 1) / NTHR;          // trans_b=1: chunks; may be partial
-    constexpr int B_BLK = (BN + NTHR - 1) / NTHR;             // trans_b=0: 8x8 blocks per thread
-    constexpr int STAGE = (BM + BN) * LDS_ROW;
+    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into whole wave loads");
+    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert((STAGES - 2) * LOADS <= 63 && STAGES >= 2 && STAGES <= 4 && KK % 2 == 0, "vmcnt range");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
+#ifdef FACT_DBG_TIMELINE
+    const long long dbg_t0 = wall_clock64();
+#endif
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     const int lr = lane & 31, g = lane >> 5;
 
@@ -147,153 +192,162 @@ gemm_kernel(const GemmArgs p)
         batch_a = z * p.stride_a; batch_b = z * p.stride_b;
         batch_c = z * p.stride_c; batch_r = z * p.stride_r;
     }
-    const int ksteps = (k_end - k_begin + BK - 1) / BK;
+    const int klen = k_end - k_begin;
+    const int ksteps = (klen + BK - 1) / BK;
+    const int ktail = klen % BK;                     // > 0: the last step is partial
 
-    // ---- global -> register -> LDS staging ------------------------------------------
-    // A (and B when trans_b=1): thread owns chunks c = tid + i*NTHR; row = c/8, kc = c%8.
-    const char *a_ptr[A_CH];
-    uint32_t a_lds[A_CH];
+    // ---- global -> LDS direct loads ------------------------------------------------------
+    // One wave-wide load moves 64 chunks (1 KB) to consecutive LDS addresses: lane l fills
+    // physical chunk blk*64 + l, so each lane fetches the global chunk that belongs there
+    // under the swizzle.  The byte offset per lane is fixed for the whole K loop; K advances
+    // through the scalar offset (K-contiguous operands) or the descriptor base (B, trans_b=0).
+    // Rows past the matrix edge are clamped to the last valid row (their results are never
+    // stored); chunks past the K range read through an out-of-range offset, which the buffer
+    // hardware returns as zero.
+    auto clamp31 = [](int64_t v) -> uint32_t { return v > 0x7FFFFFFF ? 0x7FFFFFFFu : (uint32_t)v; };
+
+    const int rows_a = (p.M - m0) < BM ? (p.M - m0) : BM;
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(p.A + batch_a + (int64_t)m0 * p.lda + k_begin), 0,
+        clamp31((((int64_t)rows_a - 1) * p.lda + klen) * 2), kBufferFlags);
+    uint32_t a_voff[A_LD], a_voff_tail[A_LD];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-        const int c = tid + i * NTHR, row = c >> 3, kc = c & 7;
-        int gr = m0 + row; gr = gr < p.M ? gr : p.M - 1;
-        a_ptr[i] = (const char *)(p.A + batch_a + (int64_t)gr * p.lda + k_begin + kc * 8);
-        a_lds[i] = lds_off(row, kc);
+    for (int i = 0; i < A_LD; ++i) {
+        const int pc = (wave + i * NWAVES) * 64 + lane;          // physical chunk
+        const int row = pc / KC, kc = (pc % KC) ^ swz_k<BK>(row);
+        const int rc = row < rows_a ? row : rows_a - 1;
+        a_voff[i] = (uint32_t)(((int64_t)rc * p.lda + kc * 8) * 2);
+        a_voff_tail[i] = (ktail == 0 || kc * 8 < ktail) ? 0u : kOobOffset;     // OR-ed in on the last step
     }
 
-    // staged B row r  <->  output column: plain: n0 + r.  gated: rows [0, BN/2) are gate
+    // staged B row r <-> output column: plain: n0 + r.  gated: rows [0, BN/2) are the gate
     // columns n0 + r, rows [BN/2, BN) the up columns n0 + r - BN/2 (read from B_up).
-    const char *b_ptr[TRANS_B ? B_CH : B_BLK];
-    uint32_t b_lds[TRANS_B ? B_CH : B_BLK];
-    bool b_act[TRANS_B ? B_CH : B_BLK];
+    __amdgpu_buffer_rsrc_t rsrc_b, rsrc_b_up;
+    uint32_t b_voff[B_LD], b_voff_tail[B_LD];
+    const __bf16 *b_step_base = nullptr;             // trans_b=0: descriptor is rebuilt per step
+    int64_t b_step_bytes = 0;
     if constexpr (TRANS_B) {
+        const int ncols = gated ? nout : p.N;
+        const int rows_b = (ncols - n0) < (gated ? BN / 2 : BN) ? (ncols - n0) : (gated ? BN / 2 : BN);
+        const uint32_t nrec = clamp31((((int64_t)rows_b - 1) * p.ldb + klen) * 2);
+        rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)(p.B + batch_b + (int64_t)n0 * p.ldb + k_begin), 0, nrec, kBufferFlags);
+        rsrc_b_up = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((gated ? p.B_up : p.B) + batch_b + (int64_t)n0 * p.ldb + k_begin), 0, nrec, kBufferFlags);
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) {
-            const int c = tid + i * NTHR, row = c >> 3, kc = c & 7;
-            b_act[i] = (BN * 8) % NTHR == 0 ? true : (c < BN * 8);
-            const __bf16 *base = p.B;
-            int col = n0 + row;
-            if (gated) {
-                const bool up = row >= BN / 2;
-                col = n0 + (up ? row - BN / 2 : row);
-                base = up ? p.B_up : p.B;
-            }
-            col = col < nout ? col : nout - 1;
-            b_ptr[i] = (const char *)(base + batch_b + (int64_t)col * p.ldb + k_begin + kc * 8);
-            b_lds[i] = BM * LDS_ROW + lds_off(row < BN ? row : BN - 1, kc);
+        for (int i = 0; i < B_LD; ++i) {
+            const int pc = (wave + i * NWAVES) * 64 + lane;
+            const int row = pc / KC, kc = (pc % KC) ^ swz_k<BK>(row);
+            int r = row;
+            if (gated) r = row >= BN / 2 ? row - BN / 2 : row;
+            r = r < rows_b ? r : rows_b - 1;
+            b_voff[i] = (uint32_t)(((int64_t)r * p.ldb + kc * 8) * 2);
+            b_voff_tail[i] = (ktail == 0 || kc * 8 < ktail) ? 0u : kOobOffset;
         }
     } else {
-        // trans_b=0: thread owns 8(k) x 8(n) blocks c = tid + i*NTHR; nb = c % (BN/8), kb = c / (BN/8).
+        b_step_base = p.B + batch_b + (int64_t)k_begin * p.ldb + n0;
+        b_step_bytes = (int64_t)BK * p.ldb * 2;
+        const int cols_b = (p.N - n0) < BN ? (p.N - n0) : BN;          // multiple of 8 on this path
 #pragma unroll
-        for (int i = 0; i < B_BLK; ++i) {
-            const int c = tid + i * NTHR;
-            b_act[i] = BN % NTHR == 0 ? true : (c < BN);
-            const int cc = c < BN ? c : BN - 1;
-            const int nb = cc % (BN / 8), kb = cc / (BN / 8);
-            int col = n0 + nb * 8; col = col < p.N ? col : p.N - 8;     // N % 8 == 0 on this path
-            b_ptr[i] = (const char *)(p.B + batch_b + (int64_t)(k_begin + kb * 8) * p.ldb + col);
-            b_lds[i] = (uint32_t)((kb << 8) | nb);                      // decoded at the store
+        for (int i = 0; i < B_LD; ++i) {
+            const int pc = (wave + i * NWAVES) * 64 + lane;
+            const int k = pc / NCH, nc = (pc % NCH) ^ swz_n<BN>(k);
+            const int cc = nc * 8 < cols_b ? nc * 8 : cols_b - 8;
+            b_voff[i] = (uint32_t)(((int64_t)k * p.ldb + cc) * 2);
+            b_voff_tail[i] = 0u;             // K rows past the range are out of the descriptor's range
         }
     }
 
-    u32x4_t a_reg[A_CH];
-    u32x4_t b_reg[TRANS_B ? B_CH : B_BLK * 8];
-
-    auto load_global = [&](int kt) {
-        const int k0 = k_begin + kt * BK;
-        const bool full = k0 + BK <= k_end;
-        if (full) {
-#pragma unroll
-            for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const u32x4_t *)(a_ptr[i] + (int64_t)kt * (BK * 2));
-            if constexpr (TRANS_B) {
-#pragma unroll
-                for (int i = 0; i < B_CH; ++i)
-                    if (b_act[i]) b_reg[i] = *(const u32x4_t *)(b_ptr[i] + (int64_t)kt * (BK * 2));
-            } else {
-#pragma unroll
-                for (int i = 0; i < B_BLK; ++i)
-                    if (b_act[i]) {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            b_reg[i * 8 + j] = *(const u32x4_t *)(b_ptr[i] + ((int64_t)kt * BK + j) * p.ldb * 2);
-                    }
-            }
-        } else {
-            // last, partial K step: chunks (rows of B) at or beyond k_end read as zero
-            const u32x4_t zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int i = 0; i < A_CH; ++i) {
-                const int kc = (tid + i * NTHR) & 7;
-                a_reg[i] = (k0 + kc * 8 < k_end) ? *(const u32x4_t *)(a_ptr[i] + (int64_t)kt * (BK * 2)) : zero;
-            }
-            if constexpr (TRANS_B) {
-#pragma unroll
-                for (int i = 0; i < B_CH; ++i) {
-                    const int kc = (tid + i * NTHR) & 7;
-                    if (b_act[i])
-                        b_reg[i] = (k0 + kc * 8 < k_end) ? *(const u32x4_t *)(b_ptr[i] + (int64_t)kt * (BK * 2)) : zero;
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < B_BLK; ++i)
-                    if (b_act[i]) {
-                        const int kb = (int)(b_lds[i] >> 8);
-#pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            b_reg[i * 8 + j] = (k0 + kb * 8 + j < k_end)
-                                ? *(const u32x4_t *)(b_ptr[i] + ((int64_t)kt * BK + j) * p.ldb * 2) : zero;
-                    }
-            }
-        }
+    // The loads of K step `step` go to ring slot step % STAGES.  Every step index is legal: the
+    // last step may be partial (its out-of-range chunks read as zero) and steps at or beyond
+    // ksteps read nothing but zeros, so a phantom step adds exactly 0 to the accumulators and
+    // the main loop needs no tail code.  Branch-free: setting the top offset bit puts a lane out
+    // of the descriptor's range.
+#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SKIP_A) || defined(FACT_DBG_SKIP_B)
+    bool dbg_skip = false;      // experiments only: no loads after the prologue
+#endif
+    struct StepCtx {
+        char *s;
+        uint32_t beyond, last;
+        int soff;
+        __amdgpu_buffer_rsrc_t rb;
     };
-
-    auto store_lds = [&](int stage) {
-        char *s = smem + stage * STAGE;
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) *(u32x4_t *)(s + a_lds[i]) = a_reg[i];
-        if constexpr (TRANS_B) {
-#pragma unroll
-            for (int i = 0; i < B_CH; ++i)
-                if (b_act[i]) *(u32x4_t *)(s + b_lds[i]) = b_reg[i];
+    auto step_ctx = [&](int step, int slot) {
+        StepCtx c;
+        c.s = smem + slot * STAGE;
+        c.beyond = step >= ksteps ? kOobOffset : 0u;
+        c.last = step == ksteps - 1 ? 0xFFFFFFFFu : 0u;
+        const int st = step < ksteps ? step : 0;
+        c.soff = st * ROWB;
+        if constexpr (!TRANS_B) {
+            const int ks = k_begin + st * BK;
+            const int64_t rows_left = (int64_t)(k_end - 1 - ks);
+            c.rb = __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)b_step_base + st * b_step_bytes), 0,
+                                                     clamp31((rows_left * p.ldb + (p.N - n0)) * 2), kBufferFlags);
         } else {
-            // 8x8 transpose in registers: in[j] holds 8 n-values of k-row j; out[nn] holds
-            // 8 k-values of column nn, i.e. the K-contiguous chunk the MFMA operand wants.
-#pragma unroll
-            for (int i = 0; i < B_BLK; ++i)
-                if (b_act[i]) {
-                    const int kb = (int)(b_lds[i] >> 8), nb = (int)(b_lds[i] & 0xFF);
-#pragma unroll
-                    for (int nn = 0; nn < 8; ++nn) {
-                        u32x4_t o;
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            const uint32_t lo = b_reg[i * 8 + 2 * d][nn >> 1];
-                            const uint32_t hi = b_reg[i * 8 + 2 * d + 1][nn >> 1];
-                            o[d] = (nn & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u))
-                                            : ((lo & 0xFFFFu) | (hi << 16));
-                        }
-                        *(u32x4_t *)(s + BM * LDS_ROW + lds_off(nb * 8 + nn, kb)) = o;
-                    }
-                }
+            c.rb = rsrc_b;
+        }
+        return c;
+    };
+    // load number idx of a step: 0 .. A_LD-1 fill the A part, A_LD .. LOADS-1 the B part
+    auto issue_one = [&](const StepCtx &c, int idx) {
+#ifdef FACT_DBG_SKIP_LOADS
+        if (c.beyond || dbg_skip) return;
+#endif
+#ifdef FACT_DBG_SKIP_A
+        if (idx < A_LD && dbg_skip) return;
+#endif
+#ifdef FACT_DBG_SKIP_B
+        if (idx >= A_LD && dbg_skip) return;
+#endif
+        if (idx < A_LD) {
+            const int i = idx;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(c.s + (wave + i * NWAVES) * 1024), 16,
+                                                     a_voff[i] | (a_voff_tail[i] & c.last) | c.beyond, c.soff, 0, 0);
+        } else {
+            const int i = idx - A_LD;
+            const int blk = wave + i * NWAVES;
+            if constexpr (TRANS_B) {
+                const bool up = gated && (blk * (64 / KC) >= BN / 2);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(up ? rsrc_b_up : rsrc_b, FACT_LDS_PTR(c.s + A_BYTES + blk * 1024), 16,
+                                                         b_voff[i] | (b_voff_tail[i] & c.last) | c.beyond, c.soff, 0, 0);
+            } else {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rb, FACT_LDS_PTR(c.s + A_BYTES + blk * 1024), 16,
+                                                         b_voff[i] | c.beyond, 0, 0, 0);
+            }
         }
     };
 
     // ---- fragment addresses ------------------------------------------------------------
-    // MFMA 32x32x16 operand: lane holds row (lane % 32) and the 8 K-values of K-group
-    // (lane / 32), i.e. the 16-byte chunk kc = 2*kk + g of sub-step kk.  Because the
-    // swizzle is an XOR, chunk (2*kk + g) ^ s sits at byte offset base ^ (kk << 5).
+    // MFMA 32x32x16 operand: lane holds row/column (lane % 32) and the 8 K-values of K-group
+    // g = lane / 32 of the sub-step.
+    //  K-contiguous: one 128-bit read of chunk 2*kk + g; the XOR swizzle makes sub-step kk's
+    //  address base ^ (kk << 5).
+    //  N-contiguous B: two transposing 64-bit reads.  Within a 16-lane group, lane 4*j + c
+    //  supplies the address of K-row j, columns 4c..4c+3, and receives column (lane % 16) of
+    //  K-rows 0..3: four consecutive K-values of its own column.  Sub-step and half select
+    //  K-rows through constant offsets because the swizzle depends on k & 3 = j only.
     uint32_t a_frag[MT], b_frag[NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) a_frag[mt] = lds_off(wm * WTM + mt * 32 + lr, g);
+    for (int mt = 0; mt < MT; ++mt) {
+        const int row = wm * WTM + mt * 32 + lr;
+        a_frag[mt] = (uint32_t)(row * ROWB + ((g ^ swz_k<BK>(row)) << 4));
+    }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        int row = wn * WTN + nt * 32 + lr;
-        if (gated) {
-            // first NT/2 tiles: gate columns; last NT/2: the matching up columns
-            const int h = nt < NT / 2 ? 0 : 1;
-            row = h * (BN / 2) + wn * (WTN / 2) + (nt - h * (NT / 2)) * 32 + lr;
+        if constexpr (TRANS_B) {
+            int row = wn * WTN + nt * 32 + lr;
+            if (gated) {
+                // first NT/2 tiles: gate columns; last NT/2: the matching up columns
+                const int h = nt < NT / 2 ? 0 : 1;
+                row = h * (BN / 2) + wn * (WTN / 2) + (nt - h * (NT / 2)) * 32 + lr;
+            }
+            b_frag[nt] = (uint32_t)(A_BYTES + row * ROWB + ((g ^ swz_k<BK>(row)) << 4));
+        } else {
+            const int G = lane >> 4, j = (lane >> 2) & 3, c = lane & 3;
+            const int k = 8 * (G >> 1) + j;                              // + 16*kk + 4*half
+            const int n = wn * WTN + nt * 32 + 16 * (G & 1) + 4 * c;
+            b_frag[nt] = (uint32_t)(A_BYTES + k * (BN * 2) + ((((n >> 3) ^ swz_n<BN>(k))) << 4) + (c & 1) * 8);
         }
-        b_frag[nt] = BM * LDS_ROW + lds_off(row, g);
     }
 
     f32x16_t acc[MT][NT];
@@ -304,136 +358,291 @@ gemm_kernel(const GemmArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
 
-    // ---- main loop: two LDS stages, next step's global loads in flight during the MFMAs ----
-    if (ksteps > 0) {
-        load_global(0);
-        store_lds(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < ksteps; ++kt) {
-        const bool more = kt + 1 < ksteps;
-        if (more) load_global(kt + 1);
-        const char *s = smem + (kt & 1) * STAGE;
+    // Two register sets of operand fragments: while the MFMAs of one sub-step (16 K-values)
+    // run from one set, the LDS reads of the next sub-step fill the other.
+    bf16x8_t af[2][MT], bf[2][NT];
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8_t af[MT], bf[NT];
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[mt] = *(const bf16x8_t *)(s + (a_frag[mt] ^ (kk << 5)));
+        for (int e = 0; e < 8; ++e) af[(KK - 1) & 1][mt][e] = (__bf16)0.0f;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) bf[nt] = *(const bf16x8_t *)(s + (b_frag[nt] ^ (kk << 5)));
-            // Operand order (B-fragment first) makes the accumulator tile hold
-            // D[n_local][m_local]: each lane then owns 4 consecutive output columns.
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[nt], af[mt], acc[mt][nt], 0, 0, 0);
+        for (int e = 0; e < 8; ++e) bf[(KK - 1) & 1][nt][e] = (__bf16)0.0f;
+
+    constexpr int NREADS = MT + NT;                  // fragment reads per sub-step (a B read is 2 instr. when trans_b=0)
+    // fragment read number t (A fragments then B fragments) of sub-step kk of the stage at s
+    auto read_one = [&](const char *s, int kk, int t) {
+        const int set = kk & 1;
+#ifdef FACT_DBG_NO_READS
+        if (dbg_skip) return;
+#endif
+        if (t < MT) {
+            af[set][t] = *(const bf16x8_t *)(s + (a_frag[t] ^ (kk << 5)));
+        } else {
+            const int nt = t - MT;
+            if constexpr (TRANS_B) {
+                bf[set][nt] = *(const bf16x8_t *)(s + (b_frag[nt] ^ (kk << 5)));
+            } else {
+                // Inline asm, not the builtin: the compiler cannot tell that these LDS reads do not
+                // alias the global->LDS loads in flight and would wait for all of them (vmcnt(0))
+                // before every read.  The price: it does not track these reads either, so the
+                // consumer waits explicitly (wait_frags below).
+                const uint32_t q = (uint32_t)(size_t)FACT_LDS_PTR(s + b_frag[nt]) + kk * 16 * (BN * 2);
+                s16x4_t lo, hi;
+                asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(q));
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(q), "n"(4 * (BN * 2)));
+                typedef short s16x8_t __attribute__((ext_vector_type(8)));
+                const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                bf[set][nt] = __builtin_bit_cast(bf16x8_t, both);
+            }
         }
-        if (more) store_lds((kt + 1) & 1);
-        __syncthreads();
+    };
+    // trans_b=0 only: all LDS reads issued so far have returned; the fragment registers are
+    // operands so that no MFMA using them can be scheduled above the wait.
+    auto wait_frags = [&](int set) {
+        if constexpr (!TRANS_B) {
+            static_assert(TRANS_B || NT <= 4, "operand list below covers up to 4 B fragments");
+            if constexpr (NT == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]), "+v"(bf[set][2]), "+v"(bf[set][3]));
+            else if constexpr (NT == 3) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]), "+v"(bf[set][2]));
+            else if constexpr (NT == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]));
+            else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]));
+        }
+    };
+    // MFMA number idx (tile row, then tile column) of a sub-step whose fragments are in `set`.
+    // Operand order (B fragment first) makes the accumulator tile hold D[n_local][m_local]:
+    // each lane then owns 4 consecutive output columns.
+    constexpr int NMFMA = MT * NT;
+    auto mfma_one = [&](int set, int idx) {
+        const int mt = idx / NT, nt = idx % NT;
+#ifdef FACT_DBG_SKIP_MFMA
+        acc[mt][nt][0] += (float)af[set][mt][0] * (float)bf[set][nt][7];   // experiments only: keeps the reads alive
+#else
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[set][nt], af[set][mt], acc[mt][nt], 0, 0, 0);
+#endif
+    };
+
+    // ---- main loop -----------------------------------------------------------------------
+    // Ring of STAGES slots; step kt lives in slot kt % STAGES.  The loop body for step kt starts
+    // right after a barrier that guarantees (a) step kt has landed in LDS for the whole
+    // work-group and (b) every wave has read its last fragments of step kt-1, so slot
+    // (kt-1) % STAGES is free.  The body runs KK phases of MT*NT MFMAs:
+    //   phase 0      : MFMAs of the LAST sub-step of step kt-1 (fragments already in registers),
+    //                  while the fragments of sub-step 0 of step kt are read;
+    //   phase j >= 1 : MFMAs of sub-step j-1 of step kt, while sub-step j is read.
+    // The global->LDS loads of step kt+STAGES-1 (into the freed slot) are spread over the first
+    // phases.  A scheduling fence after every MFMA fixes the interleaving of loads, LDS reads
+    // and MFMAs: with one wave per SIMD nothing else hides LDS and global latency.  The body
+    // ends with: wait for step kt+1 (all but the
+    // newest STAGES-2 steps' loads done) and for this wave's LDS reads; barrier.
+    // Before the first body the "previous last sub-step" fragments are zero, after the last body
+    // one more MFMA phase drains the real last sub-step.  Every body issues the same number of
+    // loads (phantom, all-zero ones past the K range), so the wait count is the same throughout.
+    // Instruction issue is in order and an LDS read or a global->LDS load takes 15-20 cycles to
+    // issue while an MFMA occupies the matrix pipe for 32, so at most one memory instruction
+    // (two for the paired transposing reads) goes between two MFMAs, with a scheduling fence
+    // after every MFMA to keep it there.
+    constexpr int LOADS_PER_PHASE = (LOADS + KK - 1) / KK;
+    auto body = [&](int kt, auto slot_tag) {
+        constexpr int SLOT = decltype(slot_tag)::value;            // kt % STAGES, known at compile time
+        const StepCtx c = step_ctx(kt + STAGES - 1, (SLOT + STAGES - 1) % STAGES);
+        const char *s = smem + SLOT * STAGE;
+#pragma unroll
+        for (int ph = 0; ph < KK; ++ph) {
+            const int mset = (ph + KK - 1) & 1;       // fragments of the sub-step the MFMAs consume
+            wait_frags(mset);
+            // LDS reads first (one per MFMA gap), the loads after them: the last read of a phase
+            // then has several MFMAs of slack before the next phase needs it
+            constexpr int LOAD_SLOT0 = NREADS < NMFMA ? NREADS : NMFMA - 1;
+#pragma unroll
+            for (int i = 0; i < NMFMA; ++i) {
+#pragma unroll
+                for (int t = 0; t < NREADS; ++t)
+                    if ((NREADS <= NMFMA ? t : (t * NMFMA) / NREADS) == i) read_one(s, ph, t);
+#pragma unroll
+                for (int l = 0; l < LOADS_PER_PHASE; ++l) {
+                    int slot = LOAD_SLOT0 + (l * (NMFMA - LOAD_SLOT0)) / LOADS_PER_PHASE;
+                    if (slot > NMFMA - 1) slot = NMFMA - 1;
+                    if (slot == i && ph * LOADS_PER_PHASE + l < LOADS) issue_one(c, ph * LOADS_PER_PHASE + l);
+                }
+                mfma_one(mset, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        wait_loads_and_barrier<(STAGES - 2) * LOADS>();
+    };
+
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) {
+        const StepCtx c = step_ctx(s, s);
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) issue_one(c, i);
     }
+#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SKIP_A) || defined(FACT_DBG_SKIP_B)
+    dbg_skip = true;
+#endif
+    wait_loads_and_barrier<(STAGES - 2) * LOADS>();
+#ifdef FACT_DBG_TIMELINE
+    const long long dbg_t1 = wall_clock64();
+#endif
+    // unrolled over the ring so that each body knows its slot; an incomplete last round runs
+    // phantom (all-zero) steps
+    for (int kt = 0; kt < ksteps; kt += STAGES) {
+        body(kt, std::integral_constant<int, 0>{});
+        body(kt + 1, std::integral_constant<int, 1 % STAGES>{});
+        if constexpr (STAGES > 2) body(kt + 2, std::integral_constant<int, 2 % STAGES>{});
+        if constexpr (STAGES > 3) body(kt + 3, std::integral_constant<int, 3 % STAGES>{});
+    }
+    // drain: the last sub-step of the last step
+    wait_frags((KK - 1) & 1);
+#pragma unroll
+    for (int i = 0; i < NMFMA; ++i) mfma_one((KK - 1) & 1, i);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // phantom loads still target LDS
+#ifdef FACT_DBG_TIMELINE
+    const long long dbg_t2 = wall_clock64();
+#endif
 
     // ---- epilogue ---------------------------------------------------------------------------
     // Accumulator register r of a tile, lane (lr, g): output row m = lr, output column
-    // n = 8*(r/4) + 4*g + (r%4) inside the 32x32 tile.
-    if (p.splits > 1) {
-        float *P = p.P + (int64_t)z * p.M * p.N;
+    // n = 8*(r/4) + 4*g + (r%4) inside the 32x32 tile: a lane owns one row of a tile, so a
+    // direct store would write 16-byte pieces of 32 different rows per instruction.  Instead each
+    // wave transposes its accumulators through its own LDS region (fp32, EPI_MT tile-rows at a
+    // time) and reads them back row-wise: a lane then holds 8 consecutive columns of one row
+    // and all epilogue arithmetic happens there, in fp32, in registers:
+    //     z = acc + bias[n];  z = act(z);  z = z + residual[m][n];  store bf16(z)
+    // with 16-byte loads of bias / residual and 16-byte stores (whole 128-byte lines per row).
+    // Region row pitch = row bytes + 16, which spreads the 32 rows a write instruction touches
+    // over all banks.  Only the wave itself reads what it wrote: no work-group barrier inside.
+    constexpr int EPI_MT = MT < 2 ? MT : 2;                    // tile-rows per pass
+    constexpr int EPI_PITCH = WTN * 4 + 16;
+    constexpr int EPI_REGION = EPI_MT * 32 * EPI_PITCH;
+    static_assert(NWAVES * EPI_REGION <= 160 * 1024, "epilogue staging must fit in LDS");
+    __syncthreads();                                            // every wave is done with the operand stages
+    char *region = smem + wave * EPI_REGION;
+    const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns
+    const int lanes_per_row = out_w / 8;
+    const int n_wave = n0 + wn * out_w;                         // first output column of this wave
+    const int m_wave = m0 + wm * WTM;
+    const bool partial = p.splits > 1;
+    float *P = partial ? p.P + (int64_t)z * p.M * p.N : nullptr;
+    __bf16 *C = p.C + batch_c;
+    const __bf16 *R = p.res ? p.res + batch_r : nullptr;
+
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int m = m0 + wm * WTM + mt * 32 + lr;
+    for (int pass = 0; pass < MT / EPI_MT; ++pass) {
+        if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                int ncol = n0 + wn * WTN + nt * 32;           // contraction column of tile element 0
-                if (gated) {
-                    const int h = nt < NT / 2 ? 0 : 1;
-                    ncol = h * nout + n0 + wn * (WTN / 2) + (nt - h * (NT / 2)) * 32;
-                }
-                const int nlim = gated ? ((nt < NT / 2 ? 0 : 1) * nout + nout) : p.N;
+        for (int i = 0; i < EPI_MT; ++i)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int n = ncol + q * 8 + g * 4;
-                    if (m < p.M) {
-                        float *dst = P + (int64_t)m * p.N + n;
-                        if (n + 3 < nlim && (p.N & 3) == 0) {
-                            f32x4_t v = {acc[mt][nt][q * 4], acc[mt][nt][q * 4 + 1],
-                                         acc[mt][nt][q * 4 + 2], acc[mt][nt][q * 4 + 3]};
-                            *(f32x4_t *)dst = v;
+                    const f32x4_t v = {acc[pass * EPI_MT + i][nt][q * 4], acc[pass * EPI_MT + i][nt][q * 4 + 1],
+                                       acc[pass * EPI_MT + i][nt][q * 4 + 2], acc[pass * EPI_MT + i][nt][q * 4 + 3]};
+                    *(f32x4_t *)(region + (i * 32 + lr) * EPI_PITCH + (nt * 32 + q * 8 + g * 4) * 4) = v;
+                }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
+        const int total = EPI_MT * 32 * lanes_per_row;
+        for (int idx = lane; idx < total; idx += 64) {
+            const int row = idx / lanes_per_row, c8 = idx - row * lanes_per_row;
+            const int m = m_wave + (pass * EPI_MT) * 32 + row;
+            const int n = n_wave + c8 * 8;
+            float v[8];
+            {
+                const char *src = region + row * EPI_PITCH + c8 * 32;
+                const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
+                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+            }
+            if (partial) {
+                // split-K: raw fp32 partials, both halves of a gated tile at their contraction columns
+                if (m < p.M) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        if (h == 1 && !gated) break;
+                        if (h == 1) {
+                            const char *src = region + row * EPI_PITCH + (out_w + c8 * 8) * 4;
+                            const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
+                            v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+                        }
+                        const int nc = n + h * nout;                   // contraction column
+                        const int nlim = gated ? (h + 1) * nout : p.N;
+                        float *dst = P + (int64_t)m * p.N + nc;
+                        if (nc + 7 < nlim && (p.N & 3) == 0) {
+                            const f32x4_t y0 = {v[0], v[1], v[2], v[3]}, y1 = {v[4], v[5], v[6], v[7]};
+                            *(f32x4_t *)dst = y0; *(f32x4_t *)(dst + 4) = y1;
                         } else {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (n + e < nlim) dst[e] = acc[mt][nt][q * 4 + e];
+                            for (int e = 0; e < 8; ++e)
+                                if (nc + e < nlim) dst[e] = v[e];
                         }
                     }
                 }
+                continue;
             }
-        }
-        return;
-    }
-
-    constexpr int NTO = NT;       // output tiles per wave along N when not gated
-    const int nt_out = gated ? NT / 2 : NTO;
-    __bf16 *C = p.C + batch_c;
-    const __bf16 *R = p.res ? p.res + batch_r : nullptr;
+            if (gated) {
+                const char *src = region + row * EPI_PITCH + (out_w + c8 * 8) * 4;
+                const f32x4_t u0 = *(const f32x4_t *)src, u1 = *(const f32x4_t *)(src + 16);
+                const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int m = m0 + wm * WTM + mt * 32 + lr;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            if (nt >= nt_out) break;
-            const int ncol = n0 + (gated ? wn * (WTN / 2) : wn * WTN) + nt * 32;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = ncol + q * 8 + g * 4;
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[mt][nt][q * 4 + e];
-                if (gated) {
-                    if constexpr (NT >= 2) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = silu(v[e]) * acc[mt][(nt + NT / 2) % NT][q * 4 + e];
-                    }
-                }
-                if (m >= p.M || n >= nout) continue;
-                const bool vec = p.vec_store && (n + 3 < nout);
-                if (p.bias) {
-                    if (vec) {
-                        const u32x2_t b = *(const u32x2_t *)(p.bias + n);
-                        v[0] += bf16_bits_to_f32(b.x & 0xFFFFu); v[1] += bf16_bits_to_f32(b.x >> 16);
-                        v[2] += bf16_bits_to_f32(b.y & 0xFFFFu); v[3] += bf16_bits_to_f32(b.y >> 16);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n + e < nout) v[e] += (float)p.bias[n + e];
-                    }
-                }
-                if (p.act == ACT_GELU_TANH) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = gelu_tanh(v[e]);
-                }
-                if (R) {
-                    const __bf16 *rp = R + (int64_t)m * p.ldr + n;
-                    if (vec) {
-                        const u32x2_t b = *(const u32x2_t *)rp;
-                        v[0] += bf16_bits_to_f32(b.x & 0xFFFFu); v[1] += bf16_bits_to_f32(b.x >> 16);
-                        v[2] += bf16_bits_to_f32(b.y & 0xFFFFu); v[3] += bf16_bits_to_f32(b.y >> 16);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n + e < nout) v[e] += (float)rp[e];
-                    }
-                }
-                __bf16 *cp = C + (int64_t)m * p.ldc + n;
+                for (int e = 0; e < 8; ++e) v[e] = silu(v[e]) * u[e];
+            }
+            if (m >= p.M || n >= nout) continue;
+            const bool vec = p.vec_store && (n + 7 < nout);
+            if (p.bias) {
                 if (vec) {
-                    *(u32x2_t *)cp = pack4_bf16(v[0], v[1], v[2], v[3]);
-                } else {
-                    uint16_t *cs = (uint16_t *)cp;
+                    const u32x4_t b = *(const u32x4_t *)(p.bias + n);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(v[e]);
+                    for (int e = 0; e < 4; ++e) { v[2 * e] += bf16_bits_to_f32(b[e] & 0xFFFFu); v[2 * e + 1] += bf16_bits_to_f32(b[e] >> 16); }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < nout) v[e] += (float)p.bias[n + e];
                 }
+            }
+            if (p.act == ACT_GELU_TANH) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = gelu_tanh(v[e]);
+            }
+            if (R) {
+                const __bf16 *rp = R + (int64_t)m * p.ldr + n;
+                if (vec) {
+                    const u32x4_t b = *(const u32x4_t *)rp;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { v[2 * e] += bf16_bits_to_f32(b[e] & 0xFFFFu); v[2 * e + 1] += bf16_bits_to_f32(b[e] >> 16); }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < nout) v[e] += (float)rp[e];
+                }
+            }
+            __bf16 *cp = C + (int64_t)m * p.ldc + n;
+            if (vec) {
+                u32x4_t o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(v[2 * e]) | (f32_to_bf16_bits(v[2 * e + 1]) << 16);
+                *(u32x4_t *)cp = o;
+            } else {
+                uint16_t *cs = (uint16_t *)cp;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(v[e]);
             }
         }
     }
+#ifdef FACT_DBG_TIMELINE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (p.P && p.splits <= 1 && tid == 0) {
+        long long *o = (long long *)p.P + (int64_t)(blockIdx.x + gridDim.x * blockIdx.z) * 8;
+        uint32_t hwid;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+        uint32_t xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        o[0] = dbg_t0; o[1] = dbg_t1; o[2] = dbg_t2; o[3] = wall_clock64(); o[4] = hwid; o[5] = xcc; o[6] = tm; o[7] = tn;
+    }
+#endif
+#else
+    (void)p;
+#endif
 }
 
 }  // namespace fact

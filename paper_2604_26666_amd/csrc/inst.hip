@@ -1,5 +1,5 @@
 // One tile configuration's kernels (both B layouts).  Built once per row of configs.def with
-// -DFACT_ID=.. -DFACT_BM=.. -DFACT_BN=.. -DFACT_WM=.. -DFACT_WN=..
+// -DFACT_ID=.. -DFACT_BM=.. -DFACT_BN=.. -DFACT_WM=.. -DFACT_WN=.. -DFACT_BK=.. -DFACT_STAGES=..
 #include "launch.h"
 
 namespace fact {
@@ -10,8 +10,11 @@ namespace fact {
 template <bool TRANS_B>
 static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t stream)
 {
-    auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B>;
-    constexpr int lds = 2 * (FACT_BM + FACT_BN) * LDS_ROW;
+    auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES>;
+    constexpr int ring = FACT_STAGES * (FACT_BM + FACT_BN) * FACT_BK * 2;
+    constexpr int mt = FACT_BM / FACT_WM / 32, wtn = FACT_BN / FACT_WN;
+    constexpr int epi = FACT_WM * FACT_WN * (mt < 2 ? mt : 2) * 32 * (wtn * 4 + 16);
+    constexpr int lds = ring > epi ? ring : epi;
     static bool attr_set[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);

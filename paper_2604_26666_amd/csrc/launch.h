@@ -8,14 +8,21 @@ namespace fact {
 // Launches configuration `id`'s kernel.  Defined once per configuration (inst.hip).
 typedef hipError_t (*launch_fn)(const GemmArgs &args, bool trans_b, int grid_z, hipStream_t stream);
 
-#define FACT_CFG(id, bm, bn, wm, wn) hipError_t fact_launch_cfg##id(const GemmArgs &, bool, int, hipStream_t);
+#define FACT_CFG(id, bm, bn, wm, wn, bk, st) hipError_t fact_launch_cfg##id(const GemmArgs &, bool, int, hipStream_t);
 #include "configs.def"
 #undef FACT_CFG
 
 struct ConfigDesc {
-    int id, bm, bn, wm, wn;
+    int id, bm, bn, wm, wn, bk, stages;
     launch_fn launch;
-    int lds_bytes() const { return 2 * (bm + bn) * LDS_ROW; }
+    // operand ring, or the epilogue's per-wave fp32 staging regions if those are larger
+    int lds_bytes() const
+    {
+        const int ring = stages * (bm + bn) * bk * 2;
+        const int mt = bm / wm / 32, wtn = bn / wn;
+        const int epi = wm * wn * (mt < 2 ? mt : 2) * 32 * (wtn * 4 + 16);
+        return ring > epi ? ring : epi;
+    }
     int threads() const { return wm * wn * 64; }
     int nt() const { return bn / wn / 32; }              // MFMA tiles per wave along N
     bool gate_capable() const { return nt() % 2 == 0; }  // gate and up tiles pair up inside a wave

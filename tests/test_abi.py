@@ -46,7 +46,7 @@ def test_config_descriptions():
     for i in range(n):
         bm, bn, wm, wn, lds = fact.fact_config_info(i)
         assert bm % (32 * wm) == 0 and bn % (32 * wn) == 0
-        assert lds == 2 * (bm + bn) * 128 and lds <= 160 * 1024
+        assert 0 < lds <= 160 * 1024
     with pytest.raises(fact.FactError):
         fact.fact_config_info(n)
 
