@@ -28,6 +28,7 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 #define FACT_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
+
 enum : int { ACT_NONE = 0, ACT_GELU_TANH = 1, ACT_SILU_GATE = 2 };
 
 // Everything a launch needs.  Pointers are device pointers; ld* and strides in elements.
@@ -167,6 +168,7 @@ gemm_kernel(const GemmArgs p)
     extern __shared__ __attribute__((aligned(16))) char smem[];
 #ifdef FACT_DBG_TIMELINE
     const long long dbg_t0 = wall_clock64();
+    long long dbg_wait = 0;
 #endif
 
     const int tid = threadIdx.x;
@@ -442,7 +444,9 @@ gemm_kernel(const GemmArgs p)
     // issue while an MFMA occupies the matrix pipe for 32, so at most one memory instruction
     // (two for the paired transposing reads) goes between two MFMAs, with a scheduling fence
     // after every MFMA to keep it there.
-    constexpr int LOADS_PER_PHASE = (LOADS + KK - 1) / KK;
+    // all loads of a step go out in the first half of the body: they must have landed by its end
+    constexpr int LOAD_PHASES = KK > 1 ? KK / 2 : 1;
+    constexpr int LOADS_PER_PHASE = (LOADS + LOAD_PHASES - 1) / LOAD_PHASES;
     auto body = [&](int kt, auto slot_tag) {
         constexpr int SLOT = decltype(slot_tag)::value;            // kt % STAGES, known at compile time
         const StepCtx c = step_ctx(kt + STAGES - 1, (SLOT + STAGES - 1) % STAGES);
@@ -463,13 +467,19 @@ gemm_kernel(const GemmArgs p)
                 for (int l = 0; l < LOADS_PER_PHASE; ++l) {
                     int slot = LOAD_SLOT0 + (l * (NMFMA - LOAD_SLOT0)) / LOADS_PER_PHASE;
                     if (slot > NMFMA - 1) slot = NMFMA - 1;
-                    if (slot == i && ph * LOADS_PER_PHASE + l < LOADS) issue_one(c, ph * LOADS_PER_PHASE + l);
+                    if (slot == i && ph < LOAD_PHASES && ph * LOADS_PER_PHASE + l < LOADS) issue_one(c, ph * LOADS_PER_PHASE + l);
                 }
                 mfma_one(mset, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+#ifdef FACT_DBG_TIMELINE
+        const long long dbg_w0 = wall_clock64();
+#endif
         wait_loads_and_barrier<(STAGES - 2) * LOADS>();
+#ifdef FACT_DBG_TIMELINE
+        dbg_wait += wall_clock64() - dbg_w0;
+#endif
     };
 
 #pragma unroll
@@ -513,10 +523,10 @@ gemm_kernel(const GemmArgs p)
     // with 16-byte loads of bias / residual and 16-byte stores (whole 128-byte lines per row).
     // Region row pitch = row bytes + 16, which spreads the 32 rows a write instruction touches
     // over all banks.  Only the wave itself reads what it wrote: no work-group barrier inside.
-    constexpr int EPI_MT = MT < 2 ? MT : 2;                    // tile-rows per pass
     constexpr int EPI_PITCH = WTN * 4 + 16;
+    constexpr int EPI_MT = (MT % 2 == 0 && NWAVES * 64 * EPI_PITCH <= 144 * 1024) ? 2 : 1;     // tile-rows per pass
     constexpr int EPI_REGION = EPI_MT * 32 * EPI_PITCH;
-    static_assert(NWAVES * EPI_REGION <= 160 * 1024, "epilogue staging must fit in LDS");
+    static_assert(NWAVES * EPI_REGION <= 160 * 1024 && STAGES * STAGE <= 160 * 1024, "LDS budget");
     __syncthreads();                                            // every wave is done with the operand stages
     char *region = smem + wave * EPI_REGION;
     const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns
@@ -637,7 +647,7 @@ gemm_kernel(const GemmArgs p)
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
         uint32_t xcc;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        o[0] = dbg_t0; o[1] = dbg_t1; o[2] = dbg_t2; o[3] = wall_clock64(); o[4] = hwid; o[5] = xcc; o[6] = tm; o[7] = tn;
+        o[0] = dbg_t0; o[1] = dbg_t1; o[2] = dbg_t2; o[3] = wall_clock64(); o[4] = hwid; o[5] = xcc; o[6] = dbg_wait; o[7] = tn;
     }
 #endif
 #else

@@ -13,7 +13,9 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
     auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES>;
     constexpr int ring = FACT_STAGES * (FACT_BM + FACT_BN) * FACT_BK * 2;
     constexpr int mt = FACT_BM / FACT_WM / 32, wtn = FACT_BN / FACT_WN;
-    constexpr int epi = FACT_WM * FACT_WN * (mt < 2 ? mt : 2) * 32 * (wtn * 4 + 16);
+    constexpr int pitch = wtn * 4 + 16;
+    constexpr int epi_mt = (mt % 2 == 0 && FACT_WM * FACT_WN * 64 * pitch <= 144 * 1024) ? 2 : 1;
+    constexpr int epi = FACT_WM * FACT_WN * epi_mt * 32 * pitch;
     constexpr int lds = ring > epi ? ring : epi;
     static bool attr_set[64] = {};
     int dev = 0;

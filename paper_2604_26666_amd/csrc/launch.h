@@ -20,7 +20,9 @@ struct ConfigDesc {
     {
         const int ring = stages * (bm + bn) * bk * 2;
         const int mt = bm / wm / 32, wtn = bn / wn;
-        const int epi = wm * wn * (mt < 2 ? mt : 2) * 32 * (wtn * 4 + 16);
+        const int pitch = wtn * 4 + 16;
+        const int epi_mt = (mt % 2 == 0 && wm * wn * 64 * pitch <= 144 * 1024) ? 2 : 1;
+        const int epi = wm * wn * epi_mt * 32 * pitch;
         return ring > epi ? ring : epi;
     }
     int threads() const { return wm * wn * 64; }

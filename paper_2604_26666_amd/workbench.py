@@ -134,7 +134,7 @@ def cases(names=None):
     return allc
 
 
-def time_case(case, steps=20, warmup=5, cfg=-1, split=0, group_m=0):
+def time_case(case, steps=30, warmup=30, cfg=-1, split=0, group_m=0):
     """Mean ms per launch with device events on the launch stream, or None if the configuration
     is refused (recorded by the sweep as a launch failure)."""
     case.alloc()
@@ -160,7 +160,7 @@ def report(case, ms):
             "min_traffic_GBs": round(gbs, 1), "pct_hbm_peak": round(100 * gbs / PEAK_HBM_GBS, 2)}
 
 
-def time_all(steps=20, warmup=5, names=None):
+def time_all(steps=30, warmup=30, names=None):
     out = {}
     for c in cases(names):
         ms = time_case(c, steps, warmup)
