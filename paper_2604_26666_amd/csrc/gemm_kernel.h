@@ -553,89 +553,107 @@ gemm_kernel(const GemmArgs p)
                 }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
         const int total = EPI_MT * 32 * lanes_per_row;
-        for (int idx = lane; idx < total; idx += 64) {
-            const int row = idx / lanes_per_row, c8 = idx - row * lanes_per_row;
-            const int m = m_wave + (pass * EPI_MT) * 32 + row;
-            const int n = n_wave + c8 * 8;
-            float v[8];
-            {
-                const char *src = region + row * EPI_PITCH + c8 * 32;
-                const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
-                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-            }
-            if (partial) {
-                // split-K: raw fp32 partials, both halves of a gated tile at their contraction columns
-                if (m < p.M) {
+        // Read-back in batches of EPI_U row-chunks per lane: first every LDS read and every
+        // bias / residual load of the batch is issued, then the arithmetic and the stores follow,
+        // so the global-load latency is paid once per batch, not once per chunk.  (The residual
+        // may alias C, which keeps the compiler from hoisting those loads over stores itself.)
+        constexpr int EPI_U = 4;
+        for (int base = lane; base < total; base += 64 * EPI_U) {
+            float v[EPI_U][8], u[EPI_U][8];
+            u32x4_t rb[EPI_U], bb[EPI_U];
+            int mm[EPI_U], nn[EPI_U];
+            bool live[EPI_U], vec[EPI_U];
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        if (h == 1 && !gated) break;
-                        if (h == 1) {
-                            const char *src = region + row * EPI_PITCH + (out_w + c8 * 8) * 4;
-                            const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
-                            v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-                        }
-                        const int nc = n + h * nout;                   // contraction column
-                        const int nlim = gated ? (h + 1) * nout : p.N;
-                        float *dst = P + (int64_t)m * p.N + nc;
-                        if (nc + 7 < nlim && (p.N & 3) == 0) {
-                            const f32x4_t y0 = {v[0], v[1], v[2], v[3]}, y1 = {v[4], v[5], v[6], v[7]};
-                            *(f32x4_t *)dst = y0; *(f32x4_t *)(dst + 4) = y1;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (nc + e < nlim) dst[e] = v[e];
-                        }
+            for (int j = 0; j < EPI_U; ++j) {
+                const int idx = base + 64 * j;
+                const int row = idx / lanes_per_row, c8 = idx - row * lanes_per_row;
+                mm[j] = m_wave + (pass * EPI_MT) * 32 + row;
+                nn[j] = n_wave + c8 * 8;
+                live[j] = idx < total && mm[j] < p.M && nn[j] < nout;
+                vec[j] = live[j] && p.vec_store && (nn[j] + 7 < nout);
+                if (idx < total) {
+                    const char *src = region + row * EPI_PITCH + c8 * 32;
+                    const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
+                    v[j][0] = x0.x; v[j][1] = x0.y; v[j][2] = x0.z; v[j][3] = x0.w;
+                    v[j][4] = x1.x; v[j][5] = x1.y; v[j][6] = x1.z; v[j][7] = x1.w;
+                    if (gated) {
+                        const char *su = src + out_w * 4;
+                        const f32x4_t u0 = *(const f32x4_t *)su, u1 = *(const f32x4_t *)(su + 16);
+                        u[j][0] = u0.x; u[j][1] = u0.y; u[j][2] = u0.z; u[j][3] = u0.w;
+                        u[j][4] = u1.x; u[j][5] = u1.y; u[j][6] = u1.z; u[j][7] = u1.w;
                     }
                 }
-                continue;
-            }
-            if (gated) {
-                const char *src = region + row * EPI_PITCH + (out_w + c8 * 8) * 4;
-                const f32x4_t u0 = *(const f32x4_t *)src, u1 = *(const f32x4_t *)(src + 16);
-                const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = silu(v[e]) * u[e];
-            }
-            if (m >= p.M || n >= nout) continue;
-            const bool vec = p.vec_store && (n + 7 < nout);
-            if (p.bias) {
-                if (vec) {
-                    const u32x4_t b = *(const u32x4_t *)(p.bias + n);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { v[2 * e] += bf16_bits_to_f32(b[e] & 0xFFFFu); v[2 * e + 1] += bf16_bits_to_f32(b[e] >> 16); }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (n + e < nout) v[e] += (float)p.bias[n + e];
+                if (!partial && vec[j]) {
+                    if (p.bias) bb[j] = *(const u32x4_t *)(p.bias + nn[j]);
+                    if (R) rb[j] = *(const u32x4_t *)(R + (int64_t)mm[j] * p.ldr + nn[j]);
                 }
             }
-            if (p.act == ACT_GELU_TANH) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = gelu_tanh(v[e]);
-            }
-            if (R) {
-                const __bf16 *rp = R + (int64_t)m * p.ldr + n;
-                if (vec) {
-                    const u32x4_t b = *(const u32x4_t *)rp;
+            for (int j = 0; j < EPI_U; ++j) {
+                const int m = mm[j], n = nn[j];
+                if (partial) {
+                    // split-K: raw fp32 partials, both halves of a gated tile at their contraction columns
+                    if (base + 64 * j < total && m < p.M) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { v[2 * e] += bf16_bits_to_f32(b[e] & 0xFFFFu); v[2 * e + 1] += bf16_bits_to_f32(b[e] >> 16); }
+                        for (int h = 0; h < 2; ++h) {
+                            if (h == 1 && !gated) break;
+                            const float *w = h ? u[j] : v[j];
+                            const int nc = n + h * nout;                   // contraction column
+                            const int nlim = gated ? (h + 1) * nout : p.N;
+                            float *dst = P + (int64_t)m * p.N + nc;
+                            if (nc + 7 < nlim && (p.N & 3) == 0) {
+                                const f32x4_t y0 = {w[0], w[1], w[2], w[3]}, y1 = {w[4], w[5], w[6], w[7]};
+                                *(f32x4_t *)dst = y0; *(f32x4_t *)(dst + 4) = y1;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (nc + e < nlim) dst[e] = w[e];
+                            }
+                        }
+                    }
+                    continue;
+                }
+                if (!live[j]) continue;
+                float z[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) z[e] = gated ? silu(v[j][e]) * u[j][e] : v[j][e];
+                if (p.bias) {
+                    if (vec[j]) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bb[j][e] >> 16); }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < nout) z[e] += (float)p.bias[n + e];
+                    }
+                }
+                if (p.act == ACT_GELU_TANH) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                }
+                if (R) {
+                    if (vec[j]) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                    } else {
+                        const __bf16 *rp = R + (int64_t)m * p.ldr + n;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < nout) z[e] += (float)rp[e];
+                    }
+                }
+                __bf16 *cp = C + (int64_t)m * p.ldc + n;
+                if (vec[j]) {
+                    u32x4_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(z[2 * e]) | (f32_to_bf16_bits(z[2 * e + 1]) << 16);
+                    *(u32x4_t *)cp = o;
                 } else {
+                    uint16_t *cs = (uint16_t *)cp;
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        if (n + e < nout) v[e] += (float)rp[e];
+                        if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(z[e]);
                 }
-            }
-            __bf16 *cp = C + (int64_t)m * p.ldc + n;
-            if (vec) {
-                u32x4_t o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(v[2 * e]) | (f32_to_bf16_bits(v[2 * e + 1]) << 16);
-                *(u32x4_t *)cp = o;
-            } else {
-                uint16_t *cs = (uint16_t *)cp;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(v[e]);
             }
         }
     }

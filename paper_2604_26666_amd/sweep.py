@@ -1,0 +1,115 @@
+"""On-device sweep: time every compiled tile configuration on the benchmark shapes and write the
+per-shape table the library consults (csrc/tile_table.inc).
+
+This is the auto-tuning step of the paper (Section 4.2 Action 5; methodology in Section 5.1: each
+configuration is run with warm-up and timed iterations, configurations that cannot run are
+recorded as launch failures) followed by the registry write of Action 6, reduced to what this
+library needs: (shape, layout, epilogue class) -> (tile configuration, split-K factor, tile-row
+group).  A candidate is accepted only if its output agrees with the first accepted candidate of
+the same shape: bit for bit when K is not split (every configuration adds the same products in the
+same order); when it is split, within 2^-6 of the largest output magnitude per element and 4e-3 in
+relative Frobenius norm.
+
+Run on a machine with the GPU:  python -m paper_2604_26666_amd.sweep [case-prefix ...]
+Then rebuild the library (python -m paper_2604_26666_amd.build).
+"""
+import json
+import os
+import sys
+
+import torch
+
+from . import binding as fact
+from . import workbench as wb
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+TABLE = os.path.join(HERE, "csrc", "tile_table.inc")
+LOG = os.path.join(HERE, "csrc", "tile_table.sweep.json")
+
+HEADER = """// Per-shape tile-configuration table: {batch, M, N, K, trans_b, gated, config id, split_k, group_m}.
+// Rows come from the on-device sweep (python -m paper_2604_26666_amd.sweep); shapes not listed
+// use the analytic model in fact_api.hip.  N is the contraction's column count (2 x d_ff when gated).
+"""
+
+
+def _bits(t):
+    return t.view(torch.int16)
+
+
+def _agree(out, ref, split):
+    if split <= 1:
+        return bool(torch.equal(_bits(out), _bits(ref)))
+    # a different split changes the fp32 summation order: compare at the scale of the matrix
+    a, b = out.float(), ref.float()
+    scale = float(b.abs().max()) + 1e-30
+    return bool((a - b).abs().max() <= 2.0 ** -6 * scale and (a - b).norm() <= 4e-3 * b.norm() + 1e-30)
+
+
+def sweep_case(case, steps=20, warmup=20, groups=(1, 2, 4, 8, 16), splits=(2, 4, 8, 16, 32, 64, 128)):
+    case.alloc()
+    ncfg = fact.fact_num_configs()
+    results, failures = [], []
+    ref = None
+    split_list = [1] + [s for s in splits if case.splitk and case.K // s >= 256]
+    for cfg in range(ncfg):
+        for split in split_list:
+            for g in groups:
+                case.t["C"].fill_(0)
+                ms = wb.time_case(case, steps, warmup, cfg, split, g)
+                if ms is None:
+                    failures.append({"cfg": cfg, "split": split, "group_m": g, "reason": "refused"})
+                    break
+                out = case.t["C"].clone()
+                if ref is None:
+                    ref = out
+                if not _agree(out, ref, split):
+                    failures.append({"cfg": cfg, "split": split, "group_m": g, "reason": "output mismatch"})
+                    continue
+                results.append({"cfg": cfg, "split": split, "group_m": g, "ms": ms})
+    results.sort(key=lambda r: r["ms"])
+    return results, failures
+
+
+def main(argv):
+    names = argv or None
+    rows, log = [], {}
+    for case in wb.cases(names):
+        res, fail = sweep_case(case)
+        case.free()
+        if not res:
+            print(f"{case.name}: no configuration ran", flush=True)
+            continue
+        best = res[0]
+        rep = wb.report(case, best["ms"])
+        print(f"{case.name}: best cfg {best['cfg']} {fact.fact_config_info(best['cfg'])} split {best['split']} "
+              f"group_m {best['group_m']}: {rep}; {len(res)} ran, {len(fail)} failed", flush=True)
+        log[case.name] = {"best": best, "report": rep, "top": res[:8], "ran": len(res), "failed": fail}
+        gated = 1 if case.act == fact.ACT_SILU_GATE else 0
+        rows.append(f"    {{{case.batch}, {case.M}, {case.N}, {case.K}, {case.trans_b}, {gated}, "
+                    f"{best['cfg']}, {best['split']}, {best['group_m']}}},   // {case.name}: {rep['tflops']} TFLOP/s")
+    # keep rows of shapes that were not swept this time
+    keep = []
+    swept = {r.split("//")[1].split(":")[0].strip() for r in rows}
+    if os.path.exists(TABLE):
+        for line in open(TABLE):
+            if line.strip().startswith("{") and "//" in line:
+                name = line.split("//")[1].split(":")[0].strip()
+                if name not in swept:
+                    keep.append(line.rstrip("\n"))
+    with open(TABLE, "w") as f:
+        f.write(HEADER)
+        for r in keep + rows:
+            f.write(r + "\n")
+    old = {}
+    if os.path.exists(LOG):
+        try:
+            old = json.load(open(LOG))
+        except Exception:
+            old = {}
+    old.update(log)
+    json.dump(old, open(LOG, "w"), indent=1)
+    print("wrote", TABLE)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:])
