@@ -18,6 +18,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6        # 256 CU x 4096 FLOP/clk/CU x 2.4 GHz, dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# L2-fill + write-back bytes per launch of the headline workload, from the two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy) summarised in
+# profiles/gemm_kernel_config2_hbm_traffic.md.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = {8192: 786810 * 1024 * 2.000 + 131072 * 1024 * 1.000}
+
 
 def time_calls(fn, steps, warmup):
     """Mean milliseconds per call: HIP events on the stream the kernels are launched on."""
@@ -58,6 +63,9 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--n", type=int, default=8192, help="size of the square workload (default: the headline 8192)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: a few GEMM launches and a few plain "
+                         "1 GiB device-to-device copies (the known-size kernel the counters are scaled by); no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists here)")
@@ -78,6 +86,17 @@ def main():
     def step():
         fact.binding.check(fact.fact_gemm(n, n, n, A, n, B, n, 0, C, n, ep))
 
+    if args.traffic_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            step()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "gemm_launches": 3, "copies": 3, "copy_bytes": src.numel() * 4}))
+        return
+
     ms = time_calls(step, args.steps, args.warmup)
     flops = 2.0 * n * n * n
     tflops = flops / (ms * 1e-3) / 1e12
@@ -94,7 +113,7 @@ def main():
                    "tile": f"{tile[0]}x{tile[1]}x64, {tile[2]}x{tile[3]} waves", "config_id": cfg, "split_k": split},
         "pct_of_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(n),
                      "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": alg_bytes,
                      "kernel_ms": round(ms, 5)},
     }
