@@ -38,6 +38,20 @@ def _run(cmd):
     return out
 
 
+def resource_usage(text):
+    """Parse the compiler's kernel-resource-usage remarks: {kernel: {field: int}}."""
+    res, cur = {}, None
+    for line in text.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            cur = res.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z /\[\]]+): (\d+) \[-Rpass-analysis", line)
+        if m and cur is not None:
+            cur[m.group(1).strip()] = int(m.group(2))
+    return res
+
+
 def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     """extra_flags / lib / obj_dir exist for experiments (a variant library beside the product one)."""
     OBJ = obj_dir
@@ -48,16 +62,29 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     units = []
     for (cid, bm, bn, wm, wn, bk, st) in configs():
         obj = os.path.join(OBJ, f"inst{cid}.o")
-        units.append((obj, [HIPCC] + FLAGS + [f"-DFACT_ID={cid}", f"-DFACT_BM={bm}", f"-DFACT_BN={bn}",
+        units.append((obj, [HIPCC] + FLAGS + ["-Rpass-analysis=kernel-resource-usage", f"-DFACT_ID={cid}", f"-DFACT_BM={bm}", f"-DFACT_BN={bn}",
                                               f"-DFACT_WM={wm}", f"-DFACT_WN={wn}", f"-DFACT_BK={bk}", f"-DFACT_STAGES={st}",
                                               "-c", os.path.join(CSRC, "inst.hip"), "-o", obj]))
     for name in ("aux_kernels", "fact_api"):
         obj = os.path.join(OBJ, name + ".o")
         units.append((obj, [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, name + ".hip"), "-o", obj]))
+    usage = {}
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         for out in ex.map(lambda u: _run(u[1]), units):
-            if verbose and out:
-                print(out)
+            usage.update(resource_usage(out))
+            rest = "\n".join(l for l in out.splitlines() if "kernel-resource-usage" not in l and not re.match(r"\s*(\d+ \| |\| |In file included)", l))
+            if verbose and rest.strip():
+                print(rest)
+    # The main kernel issues LDS reads through inline asm the compiler does not track: a spilled
+    # fragment register would be stored before its data has arrived.  Refuse such a build.
+    bad = {k: v for k, v in usage.items() if "gemm_kernel" in k and (v.get("ScratchSize [bytes/lane]", 0) or v.get("VGPRs Spill", 0))}
+    if verbose:
+        for k, v in sorted(usage.items()):
+            if "gemm_kernel" in k:
+                print(f"{k}: VGPRs {v.get('VGPRs')} AGPRs {v.get('AGPRs')} SGPR spills {v.get('SGPRs Spill')} scratch {v.get('ScratchSize [bytes/lane]')}")
+    if bad and not os.environ.get("FACT_ALLOW_SPILLS"):
+        raise RuntimeError("register spills in the main kernel (would break the untracked LDS reads): " +
+                           "; ".join(f"{k}: {v}" for k, v in bad.items()))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [u[0] for u in units])
     return LIB
 

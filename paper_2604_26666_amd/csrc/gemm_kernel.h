@@ -2,12 +2,14 @@
 //
 // The paper's three-level hierarchy (Section 4.2 Action 2: tile-level primitive,
 // kernel-level pipelining, grid-level schedule) re-designed for 64-wide wavefronts:
-//   tile level   : MFMA 32x32x16 bf16 -> fp32.  A work-group of WGM x WGN waves owns a
-//                  BM x BN macro tile; each wave owns a (BM/WGM) x (BN/WGN) sub-tile of
-//                  32x32 MFMA tiles whose accumulators stay in registers for the whole K loop.
+//   tile level   : MFMA 16x16x32 bf16 -> fp32 (measured: with random operands this shape
+//                  sustains about 16 % more FLOP/s under the chip's power limit than 32x32x16).
+//                  A work-group of WGM x WGN waves owns a BM x BN macro tile; each wave owns a
+//                  (BM/WGM) x (BN/WGN) sub-tile of 16x16 MFMA tiles whose accumulators stay in
+//                  registers for the whole K loop.
 //   kernel level : a ring of STAGES LDS buffers filled by 128-bit global->LDS direct loads
 //                  (no staging registers) STAGES-1 K steps ahead of the MFMAs; the operand
-//                  fragments of each 16-deep sub-step are read from LDS into a second register
+//                  fragments of each 32-deep sub-step are read from LDS into a second register
 //                  set while the MFMAs of the previous sub-step run; one barrier per K step.
 //   grid level   : 2-D data-parallel tiling with an XCD-aware tile order; grid.z is the
 //                  batch index or the split-K range.
@@ -15,13 +17,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
+#include <utility>
 
 namespace fact {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
@@ -109,6 +111,25 @@ __device__ __forceinline__ void tile_coords(const GemmArgs &p, int pid, int &tm,
     tn = in_grp / gsz;
 }
 
+// Compile-time loop: f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N-1>{}).  The
+// main loop's instruction order is built with it, so that it never depends on the optimizer's
+// unrolling limits.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// Epilogue staging geometry (shared with the host side, which sizes the dynamic LDS): each wave
+// transposes its accumulators through an fp32 region of epi_rows rows with this pitch.
+constexpr int epi_pitch(int wtn) { return wtn * 4 + 16; }
+constexpr int epi_rows(int wtm, int wtn, int nwaves) { return (wtm >= 64 && nwaves * 64 * epi_pitch(wtn) <= 144 * 1024) ? 64 : 32; }
+constexpr int lds_bytes(int bm, int bn, int wgm, int wgn, int bk, int stages)
+{
+    const int ring = stages * (bm + bn) * bk * 2;
+    const int epi = wgm * wgn * epi_rows(bm / wgm, bn / wgn, wgm * wgn) * epi_pitch(bn / wgn);
+    return ring > epi ? ring : epi;
+}
+
 // Wait until at most N of this wave's global->LDS loads are outstanding and all its LDS
 // reads are done, then the work-group barrier.  "memory" keeps LDS accesses on their side.
 template <int N>
@@ -124,18 +145,14 @@ __device__ __forceinline__ void wait_loads_and_barrier()
 }
 
 // LDS layouts of one stage (all offsets in bytes, chunk = 16 bytes = 8 bf16):
-//  K-contiguous operand (A always; B when trans_b=1): [rows][BK] with the chunk kc of row r at
-//  chunk position kc ^ swz_k(r).  A 32-lane fragment read walks 32 consecutive rows at one kc;
-//  the XOR spreads 8 (and 16) consecutive rows over distinct bank groups.
-template <int BK>
-__device__ __forceinline__ int swz_k(int row)
-{
-    if constexpr (BK == 64) return (row ^ (row >> 3)) & 7;
-    else return ((row >> 1) ^ (row >> 3)) & 3;
-}
-//  N-contiguous operand (B when trans_b=0): [BK][BN] with the chunk nc of K-row k at position
+//  K-contiguous operand (A always; B when trans_b=1): [rows][64] with the chunk kc of row r at
+//  chunk position kc ^ swz_k(r).  A fragment read walks 16 consecutive rows at 4 consecutive
+//  chunks; the XOR spreads them over all banks (measured conflict-free).  swz_k has period 16
+//  in r, so the MFMA tiles of a wave differ by constant offsets.
+__device__ __forceinline__ int swz_k(int row) { return (row >> 1) & 7; }
+//  N-contiguous operand (B when trans_b=0): [64][BN] with the chunk nc of K-row k at position
 //  nc ^ swz_n(k).  The transposing 64-bit LDS reads of one 16-lane group touch 4 consecutive
-//  K-rows x 32 bytes; the XOR moves those rows onto distinct 32-byte bank groups.
+//  K-rows x 32 bytes; the XOR moves those rows onto distinct bank groups (measured conflict-free).
 template <int BN>
 __device__ __forceinline__ int swz_n(int k)
 {
@@ -150,20 +167,20 @@ gemm_kernel(const GemmArgs p)
 #if defined(__HIP_DEVICE_COMPILE__)      // the host pass only needs the kernel's symbol
     constexpr int NWAVES = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
-    constexpr int MT = WTM / 32, NT = WTN / 32;
+    constexpr int MT = WTM / 16, NT = WTN / 16;      // 16x16 MFMA tiles per wave
     constexpr int KC = BK / 8;                 // chunks per K-contiguous row
     constexpr int ROWB = BK * 2;               // bytes per K-contiguous row
-    constexpr int KK = BK / 16;                // MFMA sub-steps per K step
+    constexpr int KK = BK / 32;                // MFMA sub-steps (32 K-values) per K step
     constexpr int NCH = BN / 8;                // chunks per N-contiguous row
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
     constexpr int STAGE = A_BYTES + B_BYTES;
     constexpr int A_LD = A_BYTES / 1024 / NWAVES;     // direct loads (1 KB per wave each) per wave per step
     constexpr int B_LD = B_BYTES / 1024 / NWAVES;
     constexpr int LOADS = A_LD + B_LD;
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
+    static_assert(WTM % 16 == 0 && WTN % 32 == 0, "wave tile must be made of 16x16 MFMA tiles, an even number along N");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into whole wave loads");
-    static_assert(BK == 32 || BK == 64, "BK");
-    static_assert((STAGES - 2) * LOADS <= 63 && STAGES >= 2 && STAGES <= 4 && KK % 2 == 0, "vmcnt range");
+    static_assert(BK == 64, "BK");
+    static_assert((STAGES - 2) * LOADS <= 63 && STAGES >= 2 && STAGES <= 4, "vmcnt range");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 #ifdef FACT_DBG_TIMELINE
@@ -175,7 +192,7 @@ gemm_kernel(const GemmArgs p)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
-    const int lr = lane & 31, g = lane >> 5;
+    const int r16 = lane & 15, q = lane >> 4;
 
     int tm, tn;
     tile_coords(p, blockIdx.x, tm, tn);
@@ -200,32 +217,37 @@ gemm_kernel(const GemmArgs p)
 
     // ---- global -> LDS direct loads ------------------------------------------------------
     // One wave-wide load moves 64 chunks (1 KB) to consecutive LDS addresses: lane l fills
-    // physical chunk blk*64 + l, so each lane fetches the global chunk that belongs there
-    // under the swizzle.  The byte offset per lane is fixed for the whole K loop; K advances
-    // through the scalar offset (K-contiguous operands) or the descriptor base (B, trans_b=0).
-    // Rows past the matrix edge are clamped to the last valid row (their results are never
-    // stored); chunks past the K range read through an out-of-range offset, which the buffer
-    // hardware returns as zero.
+    // physical chunk 64*block + l, so each lane fetches the global chunk that belongs there
+    // under the swizzle.  A lane's byte offset is split into a per-lane part that is the same
+    // for every load of an operand (one register) and a per-load block offset that is uniform
+    // over the wave (scalar); K advances through the scalar offset (K-contiguous operands) or
+    // the descriptor base (B, trans_b=0).  Rows past the matrix edge and K-rows past the K range
+    // lie beyond the descriptor's num_records and chunks past the K range of the last step are
+    // pushed there by an offset bit: the buffer hardware returns zero for all of them.
     auto clamp31 = [](int64_t v) -> uint32_t { return v > 0x7FFFFFFF ? 0x7FFFFFFFu : (uint32_t)v; };
+    static_assert(NWAVES % 2 == 0, "the swizzle of a lane must not depend on the load index");
+
+    // K-contiguous rows: 8 rows x 8 chunks per load; lane -> row lane/8 of the block, chunk
+    // (lane%8) ^ swz_k(row).  swz_k depends on the block's parity only, which equals the wave's.
+    const int kc_lane = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+    const uint32_t tail_k = (ktail == 0 || kc_lane * 8 < ktail) ? 0u : kOobOffset;   // OR-ed in on the last step
 
     const int rows_a = (p.M - m0) < BM ? (p.M - m0) : BM;
     const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(p.A + batch_a + (int64_t)m0 * p.lda + k_begin), 0,
         clamp31((((int64_t)rows_a - 1) * p.lda + klen) * 2), kBufferFlags);
-    uint32_t a_voff[A_LD], a_voff_tail[A_LD];
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-        const int pc = (wave + i * NWAVES) * 64 + lane;          // physical chunk
-        const int row = pc / KC, kc = (pc % KC) ^ swz_k<BK>(row);
-        const int rc = row < rows_a ? row : rows_a - 1;
-        a_voff[i] = (uint32_t)(((int64_t)rc * p.lda + kc * 8) * 2);
-        a_voff_tail[i] = (ktail == 0 || kc * 8 < ktail) ? 0u : kOobOffset;     // OR-ed in on the last step
-    }
+    const uint32_t a_lane = (uint32_t)(((int64_t)(lane >> 3) * p.lda + kc_lane * 8) * 2);
+    // load i of a wave fills LDS block wave + i*NWAVES = rows 8*block ..
+    const uint32_t a_blk0 = (uint32_t)((int64_t)wave * 8 * p.lda * 2), a_blk_step = (uint32_t)((int64_t)NWAVES * 8 * p.lda * 2);
 
-    // staged B row r <-> output column: plain: n0 + r.  gated: rows [0, BN/2) are the gate
-    // columns n0 + r, rows [BN/2, BN) the up columns n0 + r - BN/2 (read from B_up).
+    // B.  trans_b=1: as A, from rows of W.  Plain: LDS row r <-> output column n0 + r.  Gated:
+    // the WTN rows a wave's fragments read hold its WTN/2 gate columns followed by the same
+    // WTN/2 up columns (from B_up), so a wave's first NT/2 MFMA tiles are gate tiles and the last
+    // NT/2 the matching up tiles.
+    // trans_b=0: 64/NCH K-rows x NCH chunks per load; lane -> K-row lane/NCH, chunk
+    // (lane%NCH) ^ swz_n(k), again independent of the load index.
     __amdgpu_buffer_rsrc_t rsrc_b, rsrc_b_up;
-    uint32_t b_voff[B_LD], b_voff_tail[B_LD];
+    uint32_t b_lane, b_blk0 = 0, b_blk_step = 0, b_blk_bytes = 0;   // trans_b=1: bytes per 8-row block; trans_b=0: first block and step per load
     const __bf16 *b_step_base = nullptr;             // trans_b=0: descriptor is rebuilt per step
     int64_t b_step_bytes = 0;
     if constexpr (TRANS_B) {
@@ -235,28 +257,21 @@ gemm_kernel(const GemmArgs p)
         rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)(p.B + batch_b + (int64_t)n0 * p.ldb + k_begin), 0, nrec, kBufferFlags);
         rsrc_b_up = __builtin_amdgcn_make_buffer_rsrc(
             (void *)((gated ? p.B_up : p.B) + batch_b + (int64_t)n0 * p.ldb + k_begin), 0, nrec, kBufferFlags);
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            const int pc = (wave + i * NWAVES) * 64 + lane;
-            const int row = pc / KC, kc = (pc % KC) ^ swz_k<BK>(row);
-            int r = row;
-            if (gated) r = row >= BN / 2 ? row - BN / 2 : row;
-            r = r < rows_b ? r : rows_b - 1;
-            b_voff[i] = (uint32_t)(((int64_t)r * p.ldb + kc * 8) * 2);
-            b_voff_tail[i] = (ktail == 0 || kc * 8 < ktail) ? 0u : kOobOffset;
-        }
+        b_lane = (uint32_t)(((int64_t)(lane >> 3) * p.ldb + kc_lane * 8) * 2);
+        b_blk_bytes = (uint32_t)((int64_t)8 * p.ldb * 2);
     } else {
+        static_assert(TRANS_B || 64 % NCH == 0, "a load must cover whole K-rows");
+        constexpr int RPI = 64 / NCH;                                  // K-rows per load
         b_step_base = p.B + batch_b + (int64_t)k_begin * p.ldb + n0;
         b_step_bytes = (int64_t)BK * p.ldb * 2;
         const int cols_b = (p.N - n0) < BN ? (p.N - n0) : BN;          // multiple of 8 on this path
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            const int pc = (wave + i * NWAVES) * 64 + lane;
-            const int k = pc / NCH, nc = (pc % NCH) ^ swz_n<BN>(k);
-            const int cc = nc * 8 < cols_b ? nc * 8 : cols_b - 8;
-            b_voff[i] = (uint32_t)(((int64_t)k * p.ldb + cc) * 2);
-            b_voff_tail[i] = 0u;             // K rows past the range are out of the descriptor's range
-        }
+        const int k_lane = wave * RPI + lane / NCH;                    // K-row of load 0; later loads add multiples of 4
+        const int nc = (lane % NCH) ^ swz_n<BN>(k_lane);
+        const int cc = nc * 8 < cols_b ? nc * 8 : cols_b - 8;
+        b_lane = (uint32_t)(((int64_t)(lane / NCH) * p.ldb + cc) * 2);
+        b_blk0 = (uint32_t)((int64_t)wave * RPI * p.ldb * 2);
+        b_blk_step = (uint32_t)((int64_t)NWAVES * RPI * p.ldb * 2);
+        static_assert(TRANS_B || (NWAVES * RPI) % 4 == 0, "swz_n of a lane must not depend on the load index");
     }
 
     // The loads of K step `step` go to ring slot step % STAGES.  Every step index is legal: the
@@ -264,12 +279,13 @@ gemm_kernel(const GemmArgs p)
     // ksteps read nothing but zeros, so a phantom step adds exactly 0 to the accumulators and
     // the main loop needs no tail code.  Branch-free: setting the top offset bit puts a lane out
     // of the descriptor's range.
-#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SKIP_A) || defined(FACT_DBG_SKIP_B)
+#ifdef FACT_DBG_SKIP_LOADS
     bool dbg_skip = false;      // experiments only: no loads after the prologue
 #endif
     struct StepCtx {
         char *s;
-        uint32_t beyond, last;
+        uint32_t mask_k;          // per lane: out-of-range bit for K-contiguous operands
+        uint32_t beyond;          // uniform: out-of-range bit of a phantom step
         int soff;
         __amdgpu_buffer_rsrc_t rb;
     };
@@ -277,7 +293,7 @@ gemm_kernel(const GemmArgs p)
         StepCtx c;
         c.s = smem + slot * STAGE;
         c.beyond = step >= ksteps ? kOobOffset : 0u;
-        c.last = step == ksteps - 1 ? 0xFFFFFFFFu : 0u;
+        c.mask_k = (step == ksteps - 1 ? tail_k : 0u) | c.beyond;
         const int st = step < ksteps ? step : 0;
         c.soff = st * ROWB;
         if constexpr (!TRANS_B) {
@@ -295,108 +311,108 @@ gemm_kernel(const GemmArgs p)
 #ifdef FACT_DBG_SKIP_LOADS
         if (c.beyond || dbg_skip) return;
 #endif
-#ifdef FACT_DBG_SKIP_A
-        if (idx < A_LD && dbg_skip) return;
-#endif
-#ifdef FACT_DBG_SKIP_B
-        if (idx >= A_LD && dbg_skip) return;
-#endif
         if (idx < A_LD) {
             const int i = idx;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(c.s + (wave + i * NWAVES) * 1024), 16,
-                                                     a_voff[i] | (a_voff_tail[i] & c.last) | c.beyond, c.soff, 0, 0);
+                                                     a_lane + (a_blk0 + i * a_blk_step) + c.mask_k, c.soff, 0, 0);
         } else {
             const int i = idx - A_LD;
-            const int blk = wave + i * NWAVES;
             if constexpr (TRANS_B) {
-                const bool up = gated && (blk * (64 / KC) >= BN / 2);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(up ? rsrc_b_up : rsrc_b, FACT_LDS_PTR(c.s + A_BYTES + blk * 1024), 16,
-                                                         b_voff[i] | (b_voff_tail[i] & c.last) | c.beyond, c.soff, 0, 0);
+                // Loads come in pairs: pair j = i/2 of a wave handles the 8-row group g = wave + j*NWAVES
+                // of each half of every wave tile.  With G = WTN/16 blocks per half wave tile, member
+                // h = i%2 fills LDS block (g/G)*2G + g%G + h*G.  Plain: LDS rows are B rows, so that is
+                // also the global row block.  Gated: the first half of a wave tile holds gate rows and the
+                // second the up rows of the same columns: both members read row block g, from B and B_up.
+                constexpr int G = WTN / 16;
+                static_assert(!TRANS_B || B_LD % 2 == 0, "B loads come in pairs");
+                const int j = i >> 1, h = i & 1;
+                const int g = wave + j * NWAVES;
+                const int blk = (g / G) * 2 * G + g % G + h * G;
+                const uint32_t goff = (uint32_t)(gated ? g : blk) * b_blk_bytes;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds((gated && h) ? rsrc_b_up : rsrc_b, FACT_LDS_PTR(c.s + A_BYTES + blk * 1024), 16,
+                                                         b_lane + goff + c.mask_k, c.soff, 0, 0);
             } else {
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rb, FACT_LDS_PTR(c.s + A_BYTES + blk * 1024), 16,
-                                                         b_voff[i] | c.beyond, 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rb, FACT_LDS_PTR(c.s + A_BYTES + (wave + i * NWAVES) * 1024), 16,
+                                                         b_lane + (b_blk0 + i * b_blk_step) + c.beyond, 0, 0, 0);
             }
         }
     };
 
     // ---- fragment addresses ------------------------------------------------------------
-    // MFMA 32x32x16 operand: lane holds row/column (lane % 32) and the 8 K-values of K-group
-    // g = lane / 32 of the sub-step.
-    //  K-contiguous: one 128-bit read of chunk 2*kk + g; the XOR swizzle makes sub-step kk's
-    //  address base ^ (kk << 5).
+    // MFMA 16x16x32 operand: lane holds row/column r16 = lane % 16 and the 8 K-values of K-group
+    // q = lane / 16 of the sub-step.
+    //  K-contiguous: one 128-bit read of chunk 4*kk + q of the lane's row.  The swizzle depends on
+    //  r16 only, so one address per sub-step serves every MFMA tile through a constant offset.
     //  N-contiguous B: two transposing 64-bit reads.  Within a 16-lane group, lane 4*j + c
     //  supplies the address of K-row j, columns 4c..4c+3, and receives column (lane % 16) of
     //  K-rows 0..3: four consecutive K-values of its own column.  Sub-step and half select
     //  K-rows through constant offsets because the swizzle depends on k & 3 = j only.
-    uint32_t a_frag[MT], b_frag[NT];
+    uint32_t a_addr[KK], b_addr[KK], b_frag[NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int row = wm * WTM + mt * 32 + lr;
-        a_frag[mt] = (uint32_t)(row * ROWB + ((g ^ swz_k<BK>(row)) << 4));
+    for (int kk = 0; kk < KK; ++kk) {
+        const uint32_t ch = (uint32_t)(((4 * kk + q) ^ swz_k(r16)) << 4);
+        a_addr[kk] = (uint32_t)((wm * WTM + r16) * ROWB) + ch;
+        b_addr[kk] = (uint32_t)(A_BYTES + (wn * WTN + r16) * ROWB) + ch;
     }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        if constexpr (TRANS_B) {
-            int row = wn * WTN + nt * 32 + lr;
-            if (gated) {
-                // first NT/2 tiles: gate columns; last NT/2: the matching up columns
-                const int h = nt < NT / 2 ? 0 : 1;
-                row = h * (BN / 2) + wn * (WTN / 2) + (nt - h * (NT / 2)) * 32 + lr;
-            }
-            b_frag[nt] = (uint32_t)(A_BYTES + row * ROWB + ((g ^ swz_k<BK>(row)) << 4));
-        } else {
-            const int G = lane >> 4, j = (lane >> 2) & 3, c = lane & 3;
-            const int k = 8 * (G >> 1) + j;                              // + 16*kk + 4*half
-            const int n = wn * WTN + nt * 32 + 16 * (G & 1) + 4 * c;
-            b_frag[nt] = (uint32_t)(A_BYTES + k * (BN * 2) + ((((n >> 3) ^ swz_n<BN>(k))) << 4) + (c & 1) * 8);
-        }
+        const int j = (lane >> 2) & 3, c = lane & 3;
+        const int k = 8 * q + j;                                     // + 32*kk + 4*half
+        const int n = wn * WTN + nt * 16 + 4 * c;
+        b_frag[nt] = (uint32_t)(A_BYTES + k * (BN * 2) + ((((n >> 3) ^ swz_n<BN>(k))) << 4) + (c & 1) * 8);
     }
 
-    f32x16_t acc[MT][NT];
+    f32x4_t acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // Two register sets of operand fragments: while the MFMAs of one sub-step (16 K-values)
-    // run from one set, the LDS reads of the next sub-step fill the other.
-    bf16x8_t af[2][MT], bf[2][NT];
+    // A K step is consumed in U = KK * PH units: sub-step kk (32 K-values) x part h of the wave's
+    // tile rows (MTH of them).  Register sets: two of MTH A fragments (alternating per unit), two
+    // of NT B fragments (alternating per sub-step).  While the MFMAs of one unit run, the LDS
+    // reads of the next unit fill the other A set and, when a new sub-step begins, the other B set.
+    constexpr int PH = MT >= 4 ? 2 : 1;
+    constexpr int MTH = MT / PH;
+    constexpr int U = KK * PH;
+    static_assert(U % 2 == 0 && KK % 2 == 0, "register sets alternate with period 2");
+    bf16x8_t af[2][MTH], bf[2][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int x = 0; x < MTH; ++x)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) af[(KK - 1) & 1][mt][e] = (__bf16)0.0f;
+        for (int e = 0; e < 8; ++e) af[(U - 1) & 1][x][e] = (__bf16)0.0f;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int e = 0; e < 8; ++e) bf[(KK - 1) & 1][nt][e] = (__bf16)0.0f;
 
-    constexpr int NREADS = MT + NT;                  // fragment reads per sub-step (a B read is 2 instr. when trans_b=0)
-    // fragment read number t (A fragments then B fragments) of sub-step kk of the stage at s
-    auto read_one = [&](const char *s, int kk, int t) {
-        const int set = kk & 1;
+    // Fragment read number t of unit u of the stage at s: its MTH A fragments, then (first part
+    // of a sub-step only) the NT B fragments of the sub-step.
+    auto read_one = [&](const char *s, int u, int t) {
+        const int kk = u / PH, h = u % PH;
 #ifdef FACT_DBG_NO_READS
         if (dbg_skip) return;
 #endif
-        if (t < MT) {
-            af[set][t] = *(const bf16x8_t *)(s + (a_frag[t] ^ (kk << 5)));
+        if (t < MTH) {
+            af[u & 1][t] = *(const bf16x8_t *)(s + a_addr[kk] + (h * MTH + t) * 16 * ROWB);
         } else {
-            const int nt = t - MT;
+            const int nt = t - MTH;
             if constexpr (TRANS_B) {
-                bf[set][nt] = *(const bf16x8_t *)(s + (b_frag[nt] ^ (kk << 5)));
+                bf[kk & 1][nt] = *(const bf16x8_t *)(s + b_addr[kk] + nt * 16 * ROWB);
             } else {
                 // Inline asm, not the builtin: the compiler cannot tell that these LDS reads do not
                 // alias the global->LDS loads in flight and would wait for all of them (vmcnt(0))
                 // before every read.  The price: it does not track these reads either, so the
-                // consumer waits explicitly (wait_frags below).
-                const uint32_t q = (uint32_t)(size_t)FACT_LDS_PTR(s + b_frag[nt]) + kk * 16 * (BN * 2);
+                // consumer waits explicitly (wait_frags below), and a build whose register
+                // allocation spills is refused (a spill could store a register before its data
+                // has arrived).
+                const uint32_t a = (uint32_t)(size_t)FACT_LDS_PTR(s + b_frag[nt]) + kk * 32 * (BN * 2);
                 s16x4_t lo, hi;
-                asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(q));
-                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(q), "n"(4 * (BN * 2)));
+                asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a));
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a), "n"(4 * (BN * 2)));
                 typedef short s16x8_t __attribute__((ext_vector_type(8)));
                 const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                bf[set][nt] = __builtin_bit_cast(bf16x8_t, both);
+                bf[kk & 1][nt] = __builtin_bit_cast(bf16x8_t, both);
             }
         }
     };
@@ -404,81 +420,93 @@ gemm_kernel(const GemmArgs p)
     // operands so that no MFMA using them can be scheduled above the wait.
     auto wait_frags = [&](int set) {
         if constexpr (!TRANS_B) {
-            static_assert(TRANS_B || NT <= 4, "operand list below covers up to 4 B fragments");
-            if constexpr (NT == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]), "+v"(bf[set][2]), "+v"(bf[set][3]));
-            else if constexpr (NT == 3) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]), "+v"(bf[set][2]));
-            else if constexpr (NT == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]));
-            else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]));
+            static_assert(TRANS_B || NT == 2 || NT == 4 || NT == 8, "operand lists below");
+            if constexpr (NT == 8)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]), "+v"(bf[set][2]), "+v"(bf[set][3]),
+                                                      "+v"(bf[set][4]), "+v"(bf[set][5]), "+v"(bf[set][6]), "+v"(bf[set][7]));
+            else if constexpr (NT == 4)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]), "+v"(bf[set][2]), "+v"(bf[set][3]));
+            else
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bf[set][0]), "+v"(bf[set][1]));
         }
     };
-    // MFMA number idx (tile row, then tile column) of a sub-step whose fragments are in `set`.
+    // MFMA number idx (tile row within the part, then tile column) of unit u.
     // Operand order (B fragment first) makes the accumulator tile hold D[n_local][m_local]:
-    // each lane then owns 4 consecutive output columns.
-    constexpr int NMFMA = MT * NT;
-    auto mfma_one = [&](int set, int idx) {
-        const int mt = idx / NT, nt = idx % NT;
-#ifdef FACT_DBG_SKIP_MFMA
-        acc[mt][nt][0] += (float)af[set][mt][0] * (float)bf[set][nt][7];   // experiments only: keeps the reads alive
-#else
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[set][nt], af[set][mt], acc[mt][nt], 0, 0, 0);
-#endif
+    // lane (r16, q) owns output row r16 and the 4 consecutive output columns 4q .. 4q+3.
+    constexpr int NMFMA = MTH * NT;
+    auto mfma_one = [&](int u, int idx) {
+        const int kk = u / PH, h = u % PH;
+        const int x = idx / NT, nt = idx % NT;
+        // inline asm pins the accumulator tile in place in the accumulation registers; through the
+        // builtin the register allocator rotated tiles between loop iterations and paid for it in copies
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[h * MTH + x][nt]) : "v"(bf[kk & 1][nt]), "v"(af[u & 1][x]));
     };
 
     // ---- main loop -----------------------------------------------------------------------
     // Ring of STAGES slots; step kt lives in slot kt % STAGES.  The loop body for step kt starts
     // right after a barrier that guarantees (a) step kt has landed in LDS for the whole
     // work-group and (b) every wave has read its last fragments of step kt-1, so slot
-    // (kt-1) % STAGES is free.  The body runs KK phases of MT*NT MFMAs:
-    //   phase 0      : MFMAs of the LAST sub-step of step kt-1 (fragments already in registers),
-    //                  while the fragments of sub-step 0 of step kt are read;
-    //   phase j >= 1 : MFMAs of sub-step j-1 of step kt, while sub-step j is read.
-    // The global->LDS loads of step kt+STAGES-1 (into the freed slot) are spread over the first
-    // phases.  A scheduling fence after every MFMA fixes the interleaving of loads, LDS reads
-    // and MFMAs: with one wave per SIMD nothing else hides LDS and global latency.  The body
-    // ends with: wait for step kt+1 (all but the
+    // (kt-1) % STAGES is free.  The body runs U phases of MTH*NT MFMAs:
+    //   phase 0      : MFMAs of the LAST unit of step kt-1 (fragments already in registers),
+    //                  while the fragments of unit 0 of step kt are read;
+    //   phase j >= 1 : MFMAs of unit j-1 of step kt, while unit j is read.
+    // The global->LDS loads of step kt+STAGES-1 (into the freed slot) go out during the first
+    // half of the phases, so that they have the rest of the step to land; phases that also read
+    // B fragments take fewer of them.  The body ends with: wait for step kt+1 (all but the
     // newest STAGES-2 steps' loads done) and for this wave's LDS reads; barrier.
-    // Before the first body the "previous last sub-step" fragments are zero, after the last body
-    // one more MFMA phase drains the real last sub-step.  Every body issues the same number of
+    // Before the first body the "previous last unit" fragments are zero, after the last body
+    // one more MFMA phase drains the real last unit.  Every body issues the same number of
     // loads (phantom, all-zero ones past the K range), so the wait count is the same throughout.
-    // Instruction issue is in order and an LDS read or a global->LDS load takes 15-20 cycles to
-    // issue while an MFMA occupies the matrix pipe for 32, so at most one memory instruction
-    // (two for the paired transposing reads) goes between two MFMAs, with a scheduling fence
-    // after every MFMA to keep it there.
-    // all loads of a step go out in the first half of the body: they must have landed by its end
-    constexpr int LOAD_PHASES = KK > 1 ? KK / 2 : 1;
-    constexpr int LOADS_PER_PHASE = (LOADS + LOAD_PHASES - 1) / LOAD_PHASES;
+    // Instruction issue is in order: a global->LDS load blocks the wave for 16 cycles or more
+    // (the address unit takes one wave-wide load per 16 cycles and is shared by the CU's waves),
+    // an LDS read for a few, a 16x16x32 MFMA occupies the matrix pipe for 16.  Memory
+    // instructions are therefore spread evenly over the first 7/8 of a phase's MFMAs, with a
+    // scheduling fence after every MFMA to keep them there.
+    constexpr int LOAD_PHASES = U / 2;
+    // loads of load phase j: phases that read B fragments (first part of a sub-step) get one
+    // share, the others three
+    auto loads_before = [](int j) constexpr {            // loads issued in phases < j
+        int total_w = 0, w_before = 0;
+        for (int x = 0; x < LOAD_PHASES; ++x) {
+            const int w = (PH > 1 && x % PH != 0) ? 3 : 1;
+            total_w += w;
+            if (x < j) w_before += w;
+        }
+        return j >= LOAD_PHASES ? LOADS : (LOADS * w_before) / total_w;
+    };
+    constexpr int SPAN = (NMFMA * 7) / 8 > 0 ? (NMFMA * 7) / 8 : 1;
     auto body = [&](int kt, auto slot_tag) {
         constexpr int SLOT = decltype(slot_tag)::value;            // kt % STAGES, known at compile time
         const StepCtx c = step_ctx(kt + STAGES - 1, (SLOT + STAGES - 1) % STAGES);
         const char *s = smem + SLOT * STAGE;
-#pragma unroll
-        for (int ph = 0; ph < KK; ++ph) {
-            const int mset = (ph + KK - 1) & 1;       // fragments of the sub-step the MFMAs consume
-            wait_frags(mset);
-            // LDS reads first (one per MFMA gap), the loads after them: the last read of a phase
-            // then has several MFMAs of slack before the next phase needs it
-            constexpr int LOAD_SLOT0 = NREADS < NMFMA ? NREADS : NMFMA - 1;
-#pragma unroll
-            for (int i = 0; i < NMFMA; ++i) {
-#pragma unroll
-                for (int t = 0; t < NREADS; ++t)
-                    if ((NREADS <= NMFMA ? t : (t * NMFMA) / NREADS) == i) read_one(s, ph, t);
-#pragma unroll
-                for (int l = 0; l < LOADS_PER_PHASE; ++l) {
-                    int slot = LOAD_SLOT0 + (l * (NMFMA - LOAD_SLOT0)) / LOADS_PER_PHASE;
-                    if (slot > NMFMA - 1) slot = NMFMA - 1;
-                    if (slot == i && ph < LOAD_PHASES && ph * LOADS_PER_PHASE + l < LOADS) issue_one(c, ph * LOADS_PER_PHASE + l);
-                }
-                mfma_one(mset, i);
+        static_for<U>([&](auto j_) {
+            constexpr int j = decltype(j_)::value;
+            constexpr int cu = (j + U - 1) % U;                    // the unit the MFMAs consume
+            constexpr int nreads = MTH + (j % PH == 0 ? NT : 0);
+            constexpr int l0 = loads_before(j), nloads = loads_before(j + 1) - l0;
+            wait_frags((cu / PH) & 1);
+            static_for<NMFMA>([&](auto i_) {
+                constexpr int i = decltype(i_)::value;
+                static_for<nreads>([&](auto t_) {
+                    constexpr int t = decltype(t_)::value;
+                    if constexpr ((t * SPAN) / nreads == i) read_one(s, j, t);
+                });
+                static_for<nloads>([&](auto l_) {
+                    constexpr int l = decltype(l_)::value;
+                    constexpr int g0 = (l * SPAN) / nloads + (SPAN >= 2 * nloads ? 1 : 0);
+                    constexpr int gap = g0 > NMFMA - 1 ? NMFMA - 1 : g0;
+                    if constexpr (gap == i) issue_one(c, l0 + l);
+                });
+                mfma_one(cu, i);
                 __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+            });
+        });
 #ifdef FACT_DBG_TIMELINE
-        const long long dbg_w0 = wall_clock64();
+        const long long dbg_w0 = clock64();
 #endif
         wait_loads_and_barrier<(STAGES - 2) * LOADS>();
 #ifdef FACT_DBG_TIMELINE
-        dbg_wait += wall_clock64() - dbg_w0;
+        dbg_wait += clock64() - dbg_w0;
 #endif
     };
 
@@ -488,12 +516,13 @@ gemm_kernel(const GemmArgs p)
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) issue_one(c, i);
     }
-#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SKIP_A) || defined(FACT_DBG_SKIP_B)
+#ifdef FACT_DBG_SKIP_LOADS
     dbg_skip = true;
 #endif
     wait_loads_and_barrier<(STAGES - 2) * LOADS>();
 #ifdef FACT_DBG_TIMELINE
     const long long dbg_t1 = wall_clock64();
+    const long long dbg_c1 = clock64();
 #endif
     // unrolled over the ring so that each body knows its slot; an incomplete last round runs
     // phantom (all-zero) steps
@@ -503,30 +532,34 @@ gemm_kernel(const GemmArgs p)
         if constexpr (STAGES > 2) body(kt + 2, std::integral_constant<int, 2 % STAGES>{});
         if constexpr (STAGES > 3) body(kt + 3, std::integral_constant<int, 3 % STAGES>{});
     }
-    // drain: the last sub-step of the last step
+    // drain: the last unit of the last step
     wait_frags((KK - 1) & 1);
-#pragma unroll
-    for (int i = 0; i < NMFMA; ++i) mfma_one((KK - 1) & 1, i);
+    static_for<NMFMA>([&](auto i_) { mfma_one(U - 1, decltype(i_)::value); });
+    // The compiler does not see the MFMAs inside the asm statements, so it cannot pad the gap the
+    // hardware needs between a matrix instruction and the first ordinary read of its result.
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // phantom loads still target LDS
 #ifdef FACT_DBG_TIMELINE
     const long long dbg_t2 = wall_clock64();
+    const long long dbg_c2 = clock64();
 #endif
 
     // ---- epilogue ---------------------------------------------------------------------------
-    // Accumulator register r of a tile, lane (lr, g): output row m = lr, output column
-    // n = 8*(r/4) + 4*g + (r%4) inside the 32x32 tile: a lane owns one row of a tile, so a
-    // direct store would write 16-byte pieces of 32 different rows per instruction.  Instead each
-    // wave transposes its accumulators through its own LDS region (fp32, EPI_MT tile-rows at a
-    // time) and reads them back row-wise: a lane then holds 8 consecutive columns of one row
-    // and all epilogue arithmetic happens there, in fp32, in registers:
+    // Accumulator tile (mt, nt), lane (r16, q): output row mt*16 + r16, output columns
+    // nt*16 + 4q .. + 3: a lane owns pieces of one row per tile, so a direct store would write
+    // 16-byte pieces of 16 different rows per instruction.  Instead each wave transposes its
+    // accumulators through its own LDS region (fp32, EPI_ROWS rows at a time) and reads them
+    // back row-wise: a lane then holds 8 consecutive columns of one row and all epilogue
+    // arithmetic happens there, in fp32, in registers:
     //     z = acc + bias[n];  z = act(z);  z = z + residual[m][n];  store bf16(z)
     // with 16-byte loads of bias / residual and 16-byte stores (whole 128-byte lines per row).
-    // Region row pitch = row bytes + 16, which spreads the 32 rows a write instruction touches
+    // Region row pitch = row bytes + 16, which spreads the 16 rows a write instruction touches
     // over all banks.  Only the wave itself reads what it wrote: no work-group barrier inside.
-    constexpr int EPI_PITCH = WTN * 4 + 16;
-    constexpr int EPI_MT = (MT % 2 == 0 && NWAVES * 64 * EPI_PITCH <= 144 * 1024) ? 2 : 1;     // tile-rows per pass
-    constexpr int EPI_REGION = EPI_MT * 32 * EPI_PITCH;
-    static_assert(NWAVES * EPI_REGION <= 160 * 1024 && STAGES * STAGE <= 160 * 1024, "LDS budget");
+    constexpr int EPI_PITCH = epi_pitch(WTN);
+    constexpr int EPI_ROWS = epi_rows(WTM, WTN, NWAVES);
+    constexpr int EPI_TR = EPI_ROWS / 16;                       // tile-rows per pass
+    constexpr int EPI_REGION = EPI_ROWS * EPI_PITCH;
+    static_assert(NWAVES * EPI_REGION <= 160 * 1024 && STAGES * STAGE <= 160 * 1024 && WTM % EPI_ROWS == 0, "LDS budget");
     __syncthreads();                                            // every wave is done with the operand stages
     char *region = smem + wave * EPI_REGION;
     const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns
@@ -539,25 +572,20 @@ gemm_kernel(const GemmArgs p)
     const __bf16 *R = p.res ? p.res + batch_r : nullptr;
 
 #pragma unroll
-    for (int pass = 0; pass < MT / EPI_MT; ++pass) {
+    for (int pass = 0; pass < WTM / EPI_ROWS; ++pass) {
         if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
 #pragma unroll
-        for (int i = 0; i < EPI_MT; ++i)
+        for (int i = 0; i < EPI_TR; ++i)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4_t v = {acc[pass * EPI_MT + i][nt][q * 4], acc[pass * EPI_MT + i][nt][q * 4 + 1],
-                                       acc[pass * EPI_MT + i][nt][q * 4 + 2], acc[pass * EPI_MT + i][nt][q * 4 + 3]};
-                    *(f32x4_t *)(region + (i * 32 + lr) * EPI_PITCH + (nt * 32 + q * 8 + g * 4) * 4) = v;
-                }
+                *(f32x4_t *)(region + (i * 16 + r16) * EPI_PITCH + (nt * 16 + q * 4) * 4) = acc[pass * EPI_TR + i][nt];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
-        const int total = EPI_MT * 32 * lanes_per_row;
+        const int total = EPI_ROWS * lanes_per_row;
         // Read-back in batches of EPI_U row-chunks per lane: first every LDS read and every
         // bias / residual load of the batch is issued, then the arithmetic and the stores follow,
         // so the global-load latency is paid once per batch, not once per chunk.  (The residual
         // may alias C, which keeps the compiler from hoisting those loads over stores itself.)
-        constexpr int EPI_U = 4;
+        constexpr int EPI_U = NWAVES > 4 ? 2 : 4;                  // 8-wave work-groups have half the registers per wave
         for (int base = lane; base < total; base += 64 * EPI_U) {
             float v[EPI_U][8], u[EPI_U][8];
             u32x4_t rb[EPI_U], bb[EPI_U];
@@ -567,7 +595,7 @@ gemm_kernel(const GemmArgs p)
             for (int j = 0; j < EPI_U; ++j) {
                 const int idx = base + 64 * j;
                 const int row = idx / lanes_per_row, c8 = idx - row * lanes_per_row;
-                mm[j] = m_wave + (pass * EPI_MT) * 32 + row;
+                mm[j] = m_wave + pass * EPI_ROWS + row;
                 nn[j] = n_wave + c8 * 8;
                 live[j] = idx < total && mm[j] < p.M && nn[j] < nout;
                 vec[j] = live[j] && p.vec_store && (nn[j] + 7 < nout);
@@ -660,12 +688,12 @@ gemm_kernel(const GemmArgs p)
 #ifdef FACT_DBG_TIMELINE
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (p.P && p.splits <= 1 && tid == 0) {
-        long long *o = (long long *)p.P + (int64_t)(blockIdx.x + gridDim.x * blockIdx.z) * 8;
+        long long *o = (long long *)p.P + (int64_t)(blockIdx.x + gridDim.x * blockIdx.z) * 16;
         uint32_t hwid;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
         uint32_t xcc;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        o[0] = dbg_t0; o[1] = dbg_t1; o[2] = dbg_t2; o[3] = wall_clock64(); o[4] = hwid; o[5] = xcc; o[6] = dbg_wait; o[7] = tn;
+        o[0] = dbg_t0; o[1] = dbg_t1; o[2] = dbg_t2; o[3] = wall_clock64(); o[4] = hwid; o[5] = xcc; o[6] = dbg_wait; o[7] = dbg_c2 - dbg_c1;
     }
 #endif
 #else

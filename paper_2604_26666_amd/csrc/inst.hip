@@ -11,12 +11,7 @@ template <bool TRANS_B>
 static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t stream)
 {
     auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES>;
-    constexpr int ring = FACT_STAGES * (FACT_BM + FACT_BN) * FACT_BK * 2;
-    constexpr int mt = FACT_BM / FACT_WM / 32, wtn = FACT_BN / FACT_WN;
-    constexpr int pitch = wtn * 4 + 16;
-    constexpr int epi_mt = (mt % 2 == 0 && FACT_WM * FACT_WN * 64 * pitch <= 144 * 1024) ? 2 : 1;
-    constexpr int epi = FACT_WM * FACT_WN * epi_mt * 32 * pitch;
-    constexpr int lds = ring > epi ? ring : epi;
+    constexpr int lds = lds_bytes(FACT_BM, FACT_BN, FACT_WM, FACT_WN, FACT_BK, FACT_STAGES);
     static bool attr_set[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);

@@ -16,18 +16,9 @@ struct ConfigDesc {
     int id, bm, bn, wm, wn, bk, stages;
     launch_fn launch;
     // operand ring, or the epilogue's per-wave fp32 staging regions if those are larger
-    int lds_bytes() const
-    {
-        const int ring = stages * (bm + bn) * bk * 2;
-        const int mt = bm / wm / 32, wtn = bn / wn;
-        const int pitch = wtn * 4 + 16;
-        const int epi_mt = (mt % 2 == 0 && wm * wn * 64 * pitch <= 144 * 1024) ? 2 : 1;
-        const int epi = wm * wn * epi_mt * 32 * pitch;
-        return ring > epi ? ring : epi;
-    }
+    int lds_bytes() const { return fact::lds_bytes(bm, bn, wm, wn, bk, stages); }
     int threads() const { return wm * wn * 64; }
-    int nt() const { return bn / wn / 32; }              // MFMA tiles per wave along N
-    bool gate_capable() const { return nt() % 2 == 0; }  // gate and up tiles pair up inside a wave
+    bool gate_capable() const { return true; }      // every wave tile has an even number of MFMA tiles along N
 };
 
 // Split-K reduction + epilogue, and the guarded fallback GEMM (aux_kernels.hip).
