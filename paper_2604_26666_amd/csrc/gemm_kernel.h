@@ -51,6 +51,7 @@ struct GemmArgs {
     int tiles_m, tiles_n;
     int group_m;            // tile rows walked together (L2 reuse)
     int vec_store;          // 1: C / residual / bias allow 16-byte vector access
+    int pf_sa, pf_sb;       // L2 prefetch: work-groups that share an A row-panel / a B column-panel (0: off)
 };
 
 constexpr uint32_t kBufferFlags = 0x00020000u;   // raw buffer descriptor word 3 (32-bit data format)
@@ -129,6 +130,11 @@ constexpr int lds_bytes(int bm, int bn, int wgm, int wgn, int bk, int stages)
     const int epi = wgm * wgn * epi_rows(bm / wgm, bn / wgn, wgm * wgn) * epi_pitch(bn / wgn);
     return ring > epi ? ring : epi;
 }
+// plus a small sink for the L2 prefetch loads (256 bytes per wave) behind it
+constexpr int lds_total(int bm, int bn, int wgm, int wgn, int bk, int stages)
+{
+    return lds_bytes(bm, bn, wgm, wgn, bk, stages) + wgm * wgn * 256;
+}
 
 // Wait until at most N of this wave's global->LDS loads are outstanding and all its LDS
 // reads are done, then the work-group barrier.  "memory" keeps LDS accesses on their side.
@@ -180,7 +186,7 @@ gemm_kernel(const GemmArgs p)
     static_assert(WTM % 16 == 0 && WTN % 32 == 0, "wave tile must be made of 16x16 MFMA tiles, an even number along N");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into whole wave loads");
     static_assert(BK == 64, "BK");
-    static_assert((STAGES - 2) * LOADS <= 63 && STAGES >= 2 && STAGES <= 4, "vmcnt range");
+    static_assert((STAGES - 2) * (LOADS + 1) + 1 <= 63 && STAGES >= 2 && STAGES <= 4, "vmcnt range");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 #ifdef FACT_DBG_TIMELINE
@@ -264,6 +270,9 @@ gemm_kernel(const GemmArgs p)
         constexpr int RPI = 64 / NCH;                                  // K-rows per load
         b_step_base = p.B + batch_b + (int64_t)k_begin * p.ldb + n0;
         b_step_bytes = (int64_t)BK * p.ldb * 2;
+        rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)b_step_base, 0,
+                                                   clamp31((((int64_t)klen - 1) * p.ldb + (p.N - n0)) * 2), kBufferFlags);
+        rsrc_b_up = rsrc_b;
         const int cols_b = (p.N - n0) < BN ? (p.N - n0) : BN;          // multiple of 8 on this path
         const int k_lane = wave * RPI + lane / NCH;                    // K-row of load 0; later loads add multiples of 4
         const int nc = (lane % NCH) ^ swz_n<BN>(k_lane);
@@ -274,13 +283,61 @@ gemm_kernel(const GemmArgs p)
         static_assert(TRANS_B || (NWAVES * RPI) % 4 == 0, "swz_n of a lane must not depend on the load index");
     }
 
+    // ---- L2 prefetch ----------------------------------------------------------------------
+    // The work-groups resident on one XCD at a time walk K in step, pf_sa of them sharing each A
+    // row-panel and pf_sb each B column-panel.  One K step before a panel slab is loaded into LDS,
+    // each of the sharers touches its share of the slab's 128-byte lines with a one-dword load
+    // (into a sink behind the operand ring): the slab is then on its way into the XCD's L2 when
+    // all of them ask for it, instead of every work-group waiting out the same miss.  First half
+    // of the waves: A lines; second half: B lines; one load instruction per wave and K step.
+    // Lines are prefetched for full steps inside the K range only, rows past an edge fall out
+    // of the descriptor's range.
+    uint32_t pf_voff = kOobOffset;
+    uint32_t pf_step = 0;                                // byte advance per K step (scalar offset)
+    const bool pf_is_a = wave < NWAVES / 2;
+    bool pf_up = false;
+    {
+        const int hx = tid & (NWAVES * 32 - 1);          // index within the wave half
+        if (pf_is_a) {
+            if (p.pf_sa > 0) {
+                const int la = BM / p.pf_sa, line = (tn % p.pf_sa) * la + hx;
+                if (hx < la) pf_voff = (uint32_t)((int64_t)line * p.lda * 2);
+            }
+            pf_step = ROWB;
+        } else if (p.pf_sb > 0) {
+            const int share = (tm % p.group_m) % p.pf_sb;
+            if constexpr (TRANS_B) {
+                int lb = BN / p.pf_sb, row = share * lb + hx;
+                if (gated) {                              // shares alternate between the gate and the up rows
+                    const int sh = p.pf_sb > 1 ? p.pf_sb / 2 : 1;
+                    lb = (BN / 2) / sh; row = (p.pf_sb > 1 ? share >> 1 : 0) * lb + hx; pf_up = (share & 1) != 0;
+                }
+                if (hx < lb) pf_voff = (uint32_t)((int64_t)row * p.ldb * 2);
+                pf_step = ROWB;
+            } else {
+                constexpr int LPR = BN / 64;              // 128-byte lines per K-row of the slab
+                const int lb = BN / p.pf_sb, line = share * lb + hx;
+                const int kr = line / LPR, col = (line % LPR) * 64;
+                if (hx < lb && col < p.N - n0) pf_voff = (uint32_t)(((int64_t)kr * p.ldb + col) * 2);
+                pf_step = (uint32_t)b_step_bytes;         // the host enables this only if K * ldb * 2 < 2^31
+            }
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rsrc_pf = pf_is_a ? rsrc_a : (pf_up ? rsrc_b_up : rsrc_b);
+    char *pf_sink = smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES) + wave * 256;
+    auto prefetch_step = [&](int step) {
+        const uint32_t off = step < ksteps - 1 ? 0u : kOobOffset;
+        const int st = step < ksteps - 1 ? step : 0;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_pf, FACT_LDS_PTR(pf_sink), 4, pf_voff | off, st * (int)pf_step, 0, 0);
+    };
+
     // The loads of K step `step` go to ring slot step % STAGES.  Every step index is legal: the
     // last step may be partial (its out-of-range chunks read as zero) and steps at or beyond
     // ksteps read nothing but zeros, so a phantom step adds exactly 0 to the accumulators and
     // the main loop needs no tail code.  Branch-free: setting the top offset bit puts a lane out
     // of the descriptor's range.
-#ifdef FACT_DBG_SKIP_LOADS
-    bool dbg_skip = false;      // experiments only: no loads after the prologue
+#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SAME_M0) || defined(FACT_DBG_NO_VOFF)
+    bool dbg_skip = false;      // experiments only: no (or simplified) loads after the prologue
 #endif
     struct StepCtx {
         char *s;
@@ -310,6 +367,18 @@ gemm_kernel(const GemmArgs p)
     auto issue_one = [&](const StepCtx &c, int idx) {
 #ifdef FACT_DBG_SKIP_LOADS
         if (c.beyond || dbg_skip) return;
+#endif
+#if defined(FACT_DBG_SAME_M0) || defined(FACT_DBG_NO_VOFF)
+        if (dbg_skip) {          // experiments only (wrong results, in-bounds): one LDS target / one offset for every load
+#ifdef FACT_DBG_SAME_M0
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(smem + wave * 1024), 16,
+                                                     a_lane + (a_blk0 + (idx & 3) * a_blk_step) + c.mask_k, c.soff, 0, 0);
+#else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(c.s + (wave + (idx & 7) * NWAVES) * 1024), 16,
+                                                     a_lane, c.soff, 0, 0);
+#endif
+            return;
+        }
 #endif
         if (idx < A_LD) {
             const int i = idx;
@@ -450,30 +519,28 @@ gemm_kernel(const GemmArgs p)
     //   phase 0      : MFMAs of the LAST unit of step kt-1 (fragments already in registers),
     //                  while the fragments of unit 0 of step kt are read;
     //   phase j >= 1 : MFMAs of unit j-1 of step kt, while unit j is read.
-    // The global->LDS loads of step kt+STAGES-1 (into the freed slot) go out during the first
-    // half of the phases, so that they have the rest of the step to land; phases that also read
-    // B fragments take fewer of them.  The body ends with: wait for step kt+1 (all but the
+    // The global->LDS loads of step kt+STAGES-1 (into the freed slot) are spread over the step's
+    // MFMAs.  The body ends with: wait for step kt+1 (all but the
     // newest STAGES-2 steps' loads done) and for this wave's LDS reads; barrier.
     // Before the first body the "previous last unit" fragments are zero, after the last body
     // one more MFMA phase drains the real last unit.  Every body issues the same number of
     // loads (phantom, all-zero ones past the K range), so the wait count is the same throughout.
-    // Instruction issue is in order: a global->LDS load blocks the wave for 16 cycles or more
-    // (the address unit takes one wave-wide load per 16 cycles and is shared by the CU's waves),
-    // an LDS read for a few, a 16x16x32 MFMA occupies the matrix pipe for 16.  Memory
-    // instructions are therefore spread evenly over the first 7/8 of a phase's MFMAs, with a
-    // scheduling fence after every MFMA to keep them there.
-    constexpr int LOAD_PHASES = U / 2;
-    // loads of load phase j: phases that read B fragments (first part of a sub-step) get one
-    // share, the others three
-    auto loads_before = [](int j) constexpr {            // loads issued in phases < j
-        int total_w = 0, w_before = 0;
-        for (int x = 0; x < LOAD_PHASES; ++x) {
-            const int w = (PH > 1 && x % PH != 0) ? 3 : 1;
-            total_w += w;
-            if (x < j) w_before += w;
-        }
-        return j >= LOAD_PHASES ? LOADS : (LOADS * w_before) / total_w;
-    };
+    // Instruction issue is in order and a 16x16x32 MFMA occupies the matrix pipe for only 16
+    // cycles, so the LDS reads of a phase are spread evenly over the first 7/8 of its MFMAs, with
+    // a scheduling fence after every MFMA to keep every memory instruction where it was put.
+    // every step's loads are followed by one prefetch load; a wave may leave outstanding the
+    // newest STAGES-2 such groups and the prefetch behind the group it waits for
+    constexpr int WAIT_N = (STAGES - 2) * (LOADS + 1) + 1;
+    // The address unit is shared by the CU's waves and takes one wave-wide load per 16 cycles, so a
+    // step's loads are spread evenly: over the first LOAD_FRAC of the step's MFMAs with a two-slot
+    // ring (they must have landed by its end), over nearly all of it with a deeper ring.
+#ifndef FACT_LOAD_FRAC_NUM
+#define FACT_LOAD_FRAC_NUM 3
+#define FACT_LOAD_FRAC_DEN 4
+#endif
+    constexpr int TG = U * NMFMA;                        // MFMAs (= gaps) per K step
+    constexpr int LOAD_SPAN = STAGES > 2 ? (TG * 15) / 16 : (TG * FACT_LOAD_FRAC_NUM) / FACT_LOAD_FRAC_DEN;
+    auto load_gap = [](int l) constexpr { const int g = 1 + (l * LOAD_SPAN) / LOADS; return g < TG ? g : TG - 1; };
     constexpr int SPAN = (NMFMA * 7) / 8 > 0 ? (NMFMA * 7) / 8 : 1;
     auto body = [&](int kt, auto slot_tag) {
         constexpr int SLOT = decltype(slot_tag)::value;            // kt % STAGES, known at compile time
@@ -483,7 +550,6 @@ gemm_kernel(const GemmArgs p)
             constexpr int j = decltype(j_)::value;
             constexpr int cu = (j + U - 1) % U;                    // the unit the MFMAs consume
             constexpr int nreads = MTH + (j % PH == 0 ? NT : 0);
-            constexpr int l0 = loads_before(j), nloads = loads_before(j + 1) - l0;
             wait_frags((cu / PH) & 1);
             static_for<NMFMA>([&](auto i_) {
                 constexpr int i = decltype(i_)::value;
@@ -491,21 +557,20 @@ gemm_kernel(const GemmArgs p)
                     constexpr int t = decltype(t_)::value;
                     if constexpr ((t * SPAN) / nreads == i) read_one(s, j, t);
                 });
-                static_for<nloads>([&](auto l_) {
+                static_for<LOADS>([&](auto l_) {
                     constexpr int l = decltype(l_)::value;
-                    constexpr int g0 = (l * SPAN) / nloads + (SPAN >= 2 * nloads ? 1 : 0);
-                    constexpr int gap = g0 > NMFMA - 1 ? NMFMA - 1 : g0;
-                    if constexpr (gap == i) issue_one(c, l0 + l);
+                    if constexpr (load_gap(l) == j * NMFMA + i) issue_one(c, l);
                 });
+                if constexpr (load_gap(LOADS - 1) == j * NMFMA + i) prefetch_step(kt + STAGES);
                 mfma_one(cu, i);
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
-#ifdef FACT_DBG_TIMELINE
+#ifdef FACT_DBG_WAITCLK
         const long long dbg_w0 = clock64();
 #endif
-        wait_loads_and_barrier<(STAGES - 2) * LOADS>();
-#ifdef FACT_DBG_TIMELINE
+        wait_loads_and_barrier<WAIT_N>();
+#ifdef FACT_DBG_WAITCLK
         dbg_wait += clock64() - dbg_w0;
 #endif
     };
@@ -515,11 +580,12 @@ gemm_kernel(const GemmArgs p)
         const StepCtx c = step_ctx(s, s);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) issue_one(c, i);
+        prefetch_step(s + 1);
     }
-#ifdef FACT_DBG_SKIP_LOADS
+#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SAME_M0) || defined(FACT_DBG_NO_VOFF)
     dbg_skip = true;
 #endif
-    wait_loads_and_barrier<(STAGES - 2) * LOADS>();
+    wait_loads_and_barrier<WAIT_N>();
 #ifdef FACT_DBG_TIMELINE
     const long long dbg_t1 = wall_clock64();
     const long long dbg_c1 = clock64();
@@ -559,7 +625,7 @@ gemm_kernel(const GemmArgs p)
     constexpr int EPI_ROWS = epi_rows(WTM, WTN, NWAVES);
     constexpr int EPI_TR = EPI_ROWS / 16;                       // tile-rows per pass
     constexpr int EPI_REGION = EPI_ROWS * EPI_PITCH;
-    static_assert(NWAVES * EPI_REGION <= 160 * 1024 && STAGES * STAGE <= 160 * 1024 && WTM % EPI_ROWS == 0, "LDS budget");
+    static_assert(lds_total(BM, BN, WGM, WGN, BK, STAGES) <= 160 * 1024 && NWAVES * EPI_REGION <= lds_bytes(BM, BN, WGM, WGN, BK, STAGES) && WTM % EPI_ROWS == 0, "LDS budget");
     __syncthreads();                                            // every wave is done with the operand stages
     char *region = smem + wave * EPI_REGION;
     const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns

@@ -11,7 +11,7 @@ template <bool TRANS_B>
 static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t stream)
 {
     auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES>;
-    constexpr int lds = lds_bytes(FACT_BM, FACT_BN, FACT_WM, FACT_WN, FACT_BK, FACT_STAGES);
+    constexpr int lds = lds_total(FACT_BM, FACT_BN, FACT_WM, FACT_WN, FACT_BK, FACT_STAGES);
     static bool attr_set[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);

@@ -16,7 +16,7 @@ struct ConfigDesc {
     int id, bm, bn, wm, wn, bk, stages;
     launch_fn launch;
     // operand ring, or the epilogue's per-wave fp32 staging regions if those are larger
-    int lds_bytes() const { return fact::lds_bytes(bm, bn, wm, wn, bk, stages); }
+    int lds_bytes() const { return fact::lds_total(bm, bn, wm, wn, bk, stages); }
     int threads() const { return wm * wn * 64; }
     bool gate_capable() const { return true; }      // every wave tile has an even number of MFMA tiles along N
 };
