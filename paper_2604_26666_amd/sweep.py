@@ -55,7 +55,7 @@ def sweep_case(case, steps=20, warmup=20, groups=(1, 2, 4, 8, 16), splits=(2, 4,
         for split in split_list:
             for g in groups:
                 case.t["C"].fill_(0)
-                ms = wb.time_case(case, steps, warmup, cfg, split, g)
+                ms = wb.time_case(case, steps, warmup, cfg, split, g, min_warm_ms=6.0, min_timed_ms=8.0)
                 if ms is None:
                     failures.append({"cfg": cfg, "split": split, "group_m": g, "reason": "refused"})
                     break

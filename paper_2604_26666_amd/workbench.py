@@ -134,17 +134,27 @@ def cases(names=None):
     return allc
 
 
-def time_case(case, steps=30, warmup=30, cfg=-1, split=0, group_m=0):
+def time_case(case, steps=30, warmup=30, cfg=-1, split=0, group_m=0, min_warm_ms=20.0, min_timed_ms=10.0):
     """Mean ms per launch with device events on the launch stream, or None if the configuration
-    is refused (recorded by the sweep as a launch failure)."""
+    is refused (recorded by the sweep as a launch failure).  Short kernels get more warm-up and
+    timed launches (at least min_warm_ms / min_timed_ms of work): the GPU needs tens of
+    milliseconds under load to settle its clocks."""
     case.alloc()
     rc = case.run(cfg, split, group_m)
     if rc != 0:
         return None
-    for _ in range(warmup - 1):
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(4):
+        case.run(cfg, split, group_m)
+    b.record()
+    torch.cuda.synchronize()
+    est = max(a.elapsed_time(b) / 4, 1e-3)
+    warmup = min(max(warmup, int(min_warm_ms / est) + 1), 2000)
+    steps = min(max(steps, int(min_timed_ms / est) + 1), 1000)
+    for _ in range(warmup):
         case.run(cfg, split, group_m)
     torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for _ in range(steps):
         case.run(cfg, split, group_m)
