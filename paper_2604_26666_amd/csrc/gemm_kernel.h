@@ -627,6 +627,9 @@ gemm_kernel(const GemmArgs p)
     constexpr int EPI_REGION = EPI_ROWS * EPI_PITCH;
     static_assert(lds_total(BM, BN, WGM, WGN, BK, STAGES) <= 160 * 1024 && NWAVES * EPI_REGION <= lds_bytes(BM, BN, WGM, WGN, BK, STAGES) && WTM % EPI_ROWS == 0, "LDS budget");
     __syncthreads();                                            // every wave is done with the operand stages
+#ifdef FACT_DBG_TIMELINE
+    long long dbg_e[6] = {clock64(), 0, 0, 0, 0, 0};
+#endif
     char *region = smem + wave * EPI_REGION;
     const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns
     const int lanes_per_row = out_w / 8;
@@ -637,6 +640,76 @@ gemm_kernel(const GemmArgs p)
     __bf16 *C = p.C + batch_c;
     const __bf16 *R = p.res ? p.res + batch_r : nullptr;
 
+    // Fast path: the wave's whole tile lies inside C and everything allows 16-byte access.  Straight
+    // code, no per-element guards: the general path below spends most of its time in them.
+    // A lane's 8 columns are the same in every row-chunk it handles (64 is a multiple of the
+    // lanes per row), so its bias values are loaded once.
+    const bool fast = !partial && p.vec_store && m_wave + WTM <= p.M && n_wave + out_w <= nout;
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    auto fast_pass = [&](int pass, auto gated_tag) {
+        constexpr bool GATED = decltype(gated_tag)::value;
+        constexpr int OUT_W = GATED ? WTN / 2 : WTN;
+        constexpr int LPR = OUT_W / 8;                              // lanes per row
+        constexpr int TOTAL = EPI_ROWS * LPR;
+        constexpr int FU = NWAVES > 4 ? 2 : 4;                      // row-chunks per lane and batch
+        static_assert(64 % LPR == 0 && TOTAL % 64 == 0, "a lane keeps its columns; batches are whole waves");
+        const int c8 = lane % LPR;
+        const int n = n_wave + c8 * 8;
+        float bv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bv[e] = 0.0f;
+        if (p.bias) {
+            const u32x4_t b4 = *(const u32x4_t *)(p.bias + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+        }
+        const int act = p.act;
+#pragma unroll
+        for (int base = 0; base < TOTAL; base += 64 * FU) {
+            u32x4_t rb[FU];
+            f32x4_t x[FU][2], y[FU][2];
+            int row[FU];
+#pragma unroll
+            for (int j = 0; j < FU; ++j) {
+                if (base + 64 * j < TOTAL) {
+                    row[j] = (base + 64 * j + lane) / LPR;
+                    if (R) rb[j] = *(const u32x4_t *)(R + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldr + n);
+                    const char *src = region + row[j] * EPI_PITCH + c8 * 32;
+                    x[j][0] = *(const f32x4_t *)src; x[j][1] = *(const f32x4_t *)(src + 16);
+                    if constexpr (GATED) { y[j][0] = *(const f32x4_t *)(src + OUT_W * 4); y[j][1] = *(const f32x4_t *)(src + OUT_W * 4 + 16); }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < FU; ++j) {
+                if (base + 64 * j < TOTAL) {
+                    float z[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        z[e] = x[j][e >> 2][e & 3];
+                        if constexpr (GATED) z[e] = silu(z[e]) * y[j][e >> 2][e & 3];
+                        z[e] += bv[e];
+                    }
+                    if (act == ACT_GELU_TANH) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                    }
+                    if (R) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                    }
+                    u32x4_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
+                        o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                    }
+                    *(u32x4_t *)(C + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n) = o;
+                }
+            }
+        }
+    };
+
 #pragma unroll
     for (int pass = 0; pass < WTM / EPI_ROWS; ++pass) {
         if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
@@ -646,8 +719,19 @@ gemm_kernel(const GemmArgs p)
             for (int nt = 0; nt < NT; ++nt)
                 *(f32x4_t *)(region + (i * 16 + r16) * EPI_PITCH + (nt * 16 + q * 4) * 4) = acc[pass * EPI_TR + i][nt];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
+#ifdef FACT_DBG_TIMELINE
+        if (pass < 2) dbg_e[1 + 2 * pass] = clock64();
+#endif
         const int total = EPI_ROWS * lanes_per_row;
-        // Read-back in batches of EPI_U row-chunks per lane: first every LDS read and every
+        if (fast) {
+            if (gated) fast_pass(pass, std::true_type{}); else fast_pass(pass, std::false_type{});
+#ifdef FACT_DBG_TIMELINE
+            if (pass < 2) dbg_e[2 + 2 * pass] = clock64();
+#endif
+            continue;
+        }
+        // General path (tile edges, unaligned C / bias / residual, split-K partials), every access
+        // guarded.  Read-back in batches of EPI_U row-chunks per lane: first every LDS read and every
         // bias / residual load of the batch is issued, then the arithmetic and the stores follow,
         // so the global-load latency is paid once per batch, not once per chunk.  (The residual
         // may alias C, which keeps the compiler from hoisting those loads over stores itself.)
@@ -750,9 +834,13 @@ gemm_kernel(const GemmArgs p)
                 }
             }
         }
+#ifdef FACT_DBG_TIMELINE
+        if (pass < 2) dbg_e[2 + 2 * pass] = clock64();
+#endif
     }
 #ifdef FACT_DBG_TIMELINE
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    dbg_e[5] = clock64();
     if (p.P && p.splits <= 1 && tid == 0) {
         long long *o = (long long *)p.P + (int64_t)(blockIdx.x + gridDim.x * blockIdx.z) * 16;
         uint32_t hwid;
@@ -760,6 +848,7 @@ gemm_kernel(const GemmArgs p)
         uint32_t xcc;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
         o[0] = dbg_t0; o[1] = dbg_t1; o[2] = dbg_t2; o[3] = wall_clock64(); o[4] = hwid; o[5] = xcc; o[6] = dbg_wait; o[7] = dbg_c2 - dbg_c1;
+        for (int e = 0; e < 5; ++e) o[8 + e] = dbg_e[e + 1] - dbg_e[e];
     }
 #endif
 #else
