@@ -230,24 +230,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     if (tiles_m * tiles_n > INT32_MAX / 2) return FACT_ERR_DIM;
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
 
-    // L2 prefetch shares: with the tile order of the kernel, the work-groups resident on one XCD
-    // (32 CUs) form a block of gsz tile rows x (resident / gsz) tile columns
-    {
-        static const bool off = [] { const char *e = std::getenv("FACT_GEMM_PREFETCH"); return e && e[0] == '0'; }();
-        const int64_t grid = tiles_m * tiles_n * (a.splits > 1 ? 1 : q.batch);
-        const bool soff_ok = q.trans_b || (q.K * q.ldb * 2 < ((int64_t)1 << 31));
-        if (!off && grid >= 2 * kNumCU && soff_ok) {
-            const int gsz = (int)(pl.group_m < tiles_m ? pl.group_m : tiles_m);
-            const int resident = 32 * wgs_per_cu(c);
-            auto pow2_floor = [](int v) { int r = 1; while (r * 2 <= v) r *= 2; return r; };
-            int sb = pow2_floor(gsz), sa = pow2_floor(resident / gsz > 0 ? resident / gsz : 1);
-            if (sa > tiles_n) sa = pow2_floor((int)tiles_n);
-            if (sa > 32) sa = 32;
-            if (sb > 32) sb = 32;
-            a.pf_sa = sa; a.pf_sb = sb;
-        }
-    }
-
+    a.pf_dist = 1;
     if (pl.split > 1) {
         // K ranges are multiples of the 64-element staging step
         int64_t kps = (q.K + pl.split - 1) / pl.split;
@@ -263,6 +246,25 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
             a.splits = splits;
             a.k_per_split = (int)kps;
             a.P = (float *)ws;
+        }
+    }
+    // L2 prefetch (see the kernel).  Many work-groups: the ones resident on an XCD (32 CUs) form a
+    // block of gsz tile rows x (resident / gsz) tile columns that share panels; each touches its
+    // share one step ahead.  (With few work-groups, e.g. long split-K ranges streamed from HBM,
+    // unshared prefetching several steps ahead was measured to be slower than none.)
+    {
+        static const bool off = [] { const char *e = std::getenv("FACT_GEMM_PREFETCH"); return e && e[0] == '0'; }();
+        const int64_t grid = tiles_m * tiles_n * (a.splits > 1 ? a.splits : q.batch);
+        const bool soff_ok = q.trans_b || (q.K * q.ldb * 2 < ((int64_t)1 << 31));
+        auto pow2_floor = [](int v) { int r = 1; while (r * 2 <= v) r *= 2; return r; };
+        if (!off && soff_ok) {
+            if (grid >= 2 * kNumCU) {
+                const int gsz = (int)(pl.group_m < tiles_m ? pl.group_m : tiles_m);
+                const int resident = 32 * wgs_per_cu(c);
+                int sb = pow2_floor(gsz), sa = pow2_floor(resident / gsz > 0 ? resident / gsz : 1);
+                if (sa > tiles_n) sa = pow2_floor((int)tiles_n);
+                a.pf_sa = sa > 32 ? 32 : sa; a.pf_sb = sb > 32 ? 32 : sb; a.pf_dist = 1;
+            }
         }
     }
 #ifdef FACT_DBG_TIMELINE

@@ -52,6 +52,7 @@ struct GemmArgs {
     int group_m;            // tile rows walked together (L2 reuse)
     int vec_store;          // 1: C / residual / bias allow 16-byte vector access
     int pf_sa, pf_sb;       // L2 prefetch: work-groups that share an A row-panel / a B column-panel (0: off)
+    int pf_dist;            // L2 prefetch: K steps ahead of the step being loaded into LDS (>= 1)
 };
 
 constexpr uint32_t kBufferFlags = 0x00020000u;   // raw buffer descriptor word 3 (32-bit data format)
@@ -297,28 +298,36 @@ gemm_kernel(const GemmArgs p)
     const bool pf_is_a = wave < NWAVES / 2;
     bool pf_up = false;
     {
-        const int hx = tid & (NWAVES * 32 - 1);          // index within the wave half
+        constexpr int HT = NWAVES * 32;                   // threads per wave half
+        const int hx = tid & (HT - 1);                    // index within the wave half
+        // the lines of a share are spread evenly over the half's threads, so that every wave's
+        // load touches about the same number of lines
+        auto pick = [&](int lines, int &li) { const int str = lines < HT ? HT / lines : 1; li = hx / str; return hx % str == 0 && li < lines; };
+        int li = 0;
         if (pf_is_a) {
             if (p.pf_sa > 0) {
-                const int la = BM / p.pf_sa, line = (tn % p.pf_sa) * la + hx;
-                if (hx < la) pf_voff = (uint32_t)((int64_t)line * p.lda * 2);
+                const int la = BM / p.pf_sa;
+                if (pick(la, li)) pf_voff = (uint32_t)((int64_t)((tn % p.pf_sa) * la + li) * p.lda * 2);
             }
             pf_step = ROWB;
         } else if (p.pf_sb > 0) {
             const int share = (tm % p.group_m) % p.pf_sb;
             if constexpr (TRANS_B) {
-                int lb = BN / p.pf_sb, row = share * lb + hx;
+                int lb = BN / p.pf_sb, row0 = share * lb;
                 if (gated) {                              // shares alternate between the gate and the up rows
                     const int sh = p.pf_sb > 1 ? p.pf_sb / 2 : 1;
-                    lb = (BN / 2) / sh; row = (p.pf_sb > 1 ? share >> 1 : 0) * lb + hx; pf_up = (share & 1) != 0;
+                    lb = (BN / 2) / sh; row0 = (p.pf_sb > 1 ? share >> 1 : 0) * lb; pf_up = (share & 1) != 0;
                 }
-                if (hx < lb) pf_voff = (uint32_t)((int64_t)row * p.ldb * 2);
+                if (pick(lb, li)) pf_voff = (uint32_t)((int64_t)(row0 + li) * p.ldb * 2);
                 pf_step = ROWB;
             } else {
                 constexpr int LPR = BN / 64;              // 128-byte lines per K-row of the slab
-                const int lb = BN / p.pf_sb, line = share * lb + hx;
-                const int kr = line / LPR, col = (line % LPR) * 64;
-                if (hx < lb && col < p.N - n0) pf_voff = (uint32_t)(((int64_t)kr * p.ldb + col) * 2);
+                const int lb = BN / p.pf_sb;
+                if (pick(lb, li)) {
+                    const int line = share * lb + li;
+                    const int kr = line / LPR, col = (line % LPR) * 64;
+                    if (col < p.N - n0) pf_voff = (uint32_t)(((int64_t)kr * p.ldb + col) * 2);
+                }
                 pf_step = (uint32_t)b_step_bytes;         // the host enables this only if K * ldb * 2 < 2^31
             }
         }
@@ -561,7 +570,7 @@ gemm_kernel(const GemmArgs p)
                     constexpr int l = decltype(l_)::value;
                     if constexpr (load_gap(l) == j * NMFMA + i) issue_one(c, l);
                 });
-                if constexpr (load_gap(LOADS - 1) == j * NMFMA + i) prefetch_step(kt + STAGES);
+                if constexpr (load_gap(LOADS - 1) == j * NMFMA + i) prefetch_step(kt + STAGES - 1 + p.pf_dist);
                 mfma_one(cu, i);
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -575,12 +584,16 @@ gemm_kernel(const GemmArgs p)
 #endif
     };
 
+    // The prefetch behind the loads of step x covers step x + pf_dist; the steps between the
+    // prologue's loads and the first of those are touched here, ahead of the loads (older than
+    // them, so the wait counts are unaffected).
+    for (int x = STAGES - 1; x < p.pf_dist; ++x) prefetch_step(x);
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) {
         const StepCtx c = step_ctx(s, s);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) issue_one(c, i);
-        prefetch_step(s + 1);
+        prefetch_step(s + p.pf_dist);
     }
 #if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SAME_M0) || defined(FACT_DBG_NO_VOFF)
     dbg_skip = true;
