@@ -154,9 +154,10 @@ __device__ __forceinline__ void wait_loads_and_barrier()
 // LDS layouts of one stage (all offsets in bytes, chunk = 16 bytes = 8 bf16):
 //  K-contiguous operand (A always; B when trans_b=1): [rows][64] with the chunk kc of row r at
 //  chunk position kc ^ swz_k(r).  A fragment read walks 16 consecutive rows at 4 consecutive
-//  chunks; the XOR spreads them over all banks (measured conflict-free).  swz_k has period 16
-//  in r, so the MFMA tiles of a wave differ by constant offsets.
-__device__ __forceinline__ int swz_k(int row) { return (row >> 1) & 7; }
+//  chunks; the XOR spreads them over the banks (measured: as fast as a contiguous read).  swz_k
+//  has period 8 in r, so the MFMA tiles of a wave differ by constant offsets and a lane of a
+//  global->LDS load (8 rows per load) sees the same swizzle in every load.
+__device__ __forceinline__ int swz_k(int row) { return row & 7; }
 //  N-contiguous operand (B when trans_b=0): [64][BN] with the chunk nc of K-row k at position
 //  nc ^ swz_n(k).  The transposing 64-bit LDS reads of one 16-lane group touch 4 consecutive
 //  K-rows x 32 bytes; the XOR moves those rows onto distinct bank groups (measured conflict-free).
@@ -231,58 +232,80 @@ gemm_kernel(const GemmArgs p)
     // the descriptor base (B, trans_b=0).  Rows past the matrix edge and K-rows past the K range
     // lie beyond the descriptor's num_records and chunks past the K range of the last step are
     // pushed there by an offset bit: the buffer hardware returns zero for all of them.
+    //
+    // The LDS address of such a load is M0 + immediate offset + 16*lane, and writing M0 costs
+    // the wave about 8 cycles of matrix-pipe time.  A wave therefore fills runs of LOAD_RUN
+    // consecutive blocks that share one M0 and differ in the immediate offset (< 4096).  The
+    // immediate also counts towards the global address (measured, range check included); the
+    // per-load offset takes it back, and every descriptor starts kOffBias bytes early (its
+    // num_records that much larger) so that the offset never goes negative.
     auto clamp31 = [](int64_t v) -> uint32_t { return v > 0x7FFFFFFF ? 0x7FFFFFFFu : (uint32_t)v; };
-    static_assert(NWAVES % 2 == 0, "the swizzle of a lane must not depend on the load index");
+    constexpr uint32_t kOffBias = 3072;
+    constexpr int A_RUN = A_LD < 4 ? A_LD : 4, B_RUN = B_LD < 4 ? B_LD : 4;
+    static_assert(A_LD % A_RUN == 0 && B_LD % B_RUN == 0, "loads split into whole runs");
 
     // K-contiguous rows: 8 rows x 8 chunks per load; lane -> row lane/8 of the block, chunk
-    // (lane%8) ^ swz_k(row).  swz_k depends on the block's parity only, which equals the wave's.
-    const int kc_lane = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+    // (lane%8) ^ swz_k(row), the same in every block.
+    const int kc_lane = (lane & 7) ^ swz_k(lane >> 3);
     const uint32_t tail_k = (ktail == 0 || kc_lane * 8 < ktail) ? 0u : kOobOffset;   // OR-ed in on the last step
 
     const int rows_a = (p.M - m0) < BM ? (p.M - m0) : BM;
-    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(p.A + batch_a + (int64_t)m0 * p.lda + k_begin), 0,
-        clamp31((((int64_t)rows_a - 1) * p.lda + klen) * 2), kBufferFlags);
-    const uint32_t a_lane = (uint32_t)(((int64_t)(lane >> 3) * p.lda + kc_lane * 8) * 2);
-    // load i of a wave fills LDS block wave + i*NWAVES = rows 8*block ..
-    const uint32_t a_blk0 = (uint32_t)((int64_t)wave * 8 * p.lda * 2), a_blk_step = (uint32_t)((int64_t)NWAVES * 8 * p.lda * 2);
+    const char *base_a = (const char *)(p.A + batch_a + (int64_t)m0 * p.lda + k_begin) - kOffBias;
+    const uint32_t nrec_a = clamp31((((int64_t)rows_a - 1) * p.lda + klen) * 2 + kOffBias);
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void *)base_a, 0, nrec_a, kBufferFlags);
+    const uint32_t a_lane = (uint32_t)(((int64_t)(lane >> 3) * p.lda + kc_lane * 8) * 2) + kOffBias;
+    const uint32_t a_blk_bytes = (uint32_t)((int64_t)8 * p.lda * 2);            // bytes per 8-row block
 
     // B.  trans_b=1: as A, from rows of W.  Plain: LDS row r <-> output column n0 + r.  Gated:
     // the WTN rows a wave's fragments read hold its WTN/2 gate columns followed by the same
     // WTN/2 up columns (from B_up), so a wave's first NT/2 MFMA tiles are gate tiles and the last
     // NT/2 the matching up tiles.
     // trans_b=0: 64/NCH K-rows x NCH chunks per load; lane -> K-row lane/NCH, chunk
-    // (lane%NCH) ^ swz_n(k), again independent of the load index.
-    __amdgpu_buffer_rsrc_t rsrc_b, rsrc_b_up;
-    uint32_t b_lane, b_blk0 = 0, b_blk_step = 0, b_blk_bytes = 0;   // trans_b=1: bytes per 8-row block; trans_b=0: first block and step per load
+    // (lane%NCH) ^ swz_n(k); with fewer than 4 K-rows per load the swizzle, and with it the
+    // per-lane part, alternates between loads (B_NV variants).
+    constexpr int RPI = TRANS_B ? 8 : 64 / NCH;                            // rows per load
+    constexpr int B_NV = TRANS_B ? 1 : (RPI >= 4 ? 1 : 4 / RPI);
+    static_assert(TRANS_B || (64 % NCH == 0 && B_LD % B_NV == 0), "a load covers whole K-rows; swizzle variants cycle within a wave's loads");
+    // One B descriptor per wave: in a gated launch the half (gate or up rows) a wave's loads fill
+    // is the same for all of them, and so is the matrix they read.  The choice is made on the base
+    // pointer, a scalar.
+    constexpr int G = WTN / 16;                                            // 8-row blocks per half wave tile
+    static_assert(!TRANS_B || G % B_LD == 0, "a wave's B loads lie inside one half of a wave tile");
+    const char *base_b = nullptr, *base_b_up = nullptr;
+    uint32_t nrec_b = 0;
+    uint32_t b_lane[B_NV], b_blk_bytes;                                    // bytes per block of RPI rows
     const __bf16 *b_step_base = nullptr;             // trans_b=0: descriptor is rebuilt per step
     int64_t b_step_bytes = 0;
     if constexpr (TRANS_B) {
         const int ncols = gated ? nout : p.N;
         const int rows_b = (ncols - n0) < (gated ? BN / 2 : BN) ? (ncols - n0) : (gated ? BN / 2 : BN);
-        const uint32_t nrec = clamp31((((int64_t)rows_b - 1) * p.ldb + klen) * 2);
-        rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)(p.B + batch_b + (int64_t)n0 * p.ldb + k_begin), 0, nrec, kBufferFlags);
-        rsrc_b_up = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)((gated ? p.B_up : p.B) + batch_b + (int64_t)n0 * p.ldb + k_begin), 0, nrec, kBufferFlags);
-        b_lane = (uint32_t)(((int64_t)(lane >> 3) * p.ldb + kc_lane * 8) * 2);
+        nrec_b = clamp31((((int64_t)rows_b - 1) * p.ldb + klen) * 2 + kOffBias);
+        base_b = (const char *)(p.B + batch_b + (int64_t)n0 * p.ldb + k_begin) - kOffBias;
+        base_b_up = (const char *)((gated ? p.B_up : p.B) + batch_b + (int64_t)n0 * p.ldb + k_begin) - kOffBias;
+        b_lane[0] = (uint32_t)(((int64_t)(lane >> 3) * p.ldb + kc_lane * 8) * 2) + kOffBias;
         b_blk_bytes = (uint32_t)((int64_t)8 * p.ldb * 2);
     } else {
-        static_assert(TRANS_B || 64 % NCH == 0, "a load must cover whole K-rows");
-        constexpr int RPI = 64 / NCH;                                  // K-rows per load
         b_step_base = p.B + batch_b + (int64_t)k_begin * p.ldb + n0;
         b_step_bytes = (int64_t)BK * p.ldb * 2;
-        rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void *)b_step_base, 0,
-                                                   clamp31((((int64_t)klen - 1) * p.ldb + (p.N - n0)) * 2), kBufferFlags);
-        rsrc_b_up = rsrc_b;
+        base_b = base_b_up = (const char *)b_step_base - kOffBias;      // whole panel: used by the prefetch
+        nrec_b = clamp31((((int64_t)klen - 1) * p.ldb + (p.N - n0)) * 2 + kOffBias);
         const int cols_b = (p.N - n0) < BN ? (p.N - n0) : BN;          // multiple of 8 on this path
-        const int k_lane = wave * RPI + lane / NCH;                    // K-row of load 0; later loads add multiples of 4
-        const int nc = (lane % NCH) ^ swz_n<BN>(k_lane);
-        const int cc = nc * 8 < cols_b ? nc * 8 : cols_b - 8;
-        b_lane = (uint32_t)(((int64_t)(lane / NCH) * p.ldb + cc) * 2);
-        b_blk0 = (uint32_t)((int64_t)wave * RPI * p.ldb * 2);
-        b_blk_step = (uint32_t)((int64_t)NWAVES * RPI * p.ldb * 2);
-        static_assert(TRANS_B || (NWAVES * RPI) % 4 == 0, "swz_n of a lane must not depend on the load index");
+#pragma unroll
+        for (int v = 0; v < B_NV; ++v) {
+            const int k_lane = v * RPI + lane / NCH;                   // K-row within a group of B_NV blocks
+            const int nc = (lane % NCH) ^ swz_n<BN>(k_lane);
+            const int cc = nc * 8 < cols_b ? nc * 8 : cols_b - 8;
+            b_lane[v] = (uint32_t)(((int64_t)(lane / NCH) * p.ldb + cc) * 2) + kOffBias;
+        }
+        b_blk_bytes = (uint32_t)((int64_t)RPI * p.ldb * 2);
     }
+
+    // gated: LDS block (2*wn + h)*G + x holds 8-row group x of half h (0: gate rows from B, 1: the up
+    // rows of the same columns from B_up) of wave column wn; both halves read row block wn*G + x.
+    // A wave fills blocks wave*B_LD .. wave*B_LD + B_LD - 1: inside one half when B_LD <= G.
+    const int b_seg0 = (wave * B_LD) / G;
+    const bool b_wave_up = TRANS_B && gated && B_LD <= G && (b_seg0 & 1);
+    const __amdgpu_buffer_rsrc_t rsrc_bw = __builtin_amdgcn_make_buffer_rsrc((void *)(b_wave_up ? base_b_up : base_b), 0, nrec_b, kBufferFlags);
 
     // ---- L2 prefetch ----------------------------------------------------------------------
     // The work-groups resident on one XCD at a time walk K in step, pf_sa of them sharing each A
@@ -307,7 +330,7 @@ gemm_kernel(const GemmArgs p)
         if (pf_is_a) {
             if (p.pf_sa > 0) {
                 const int la = BM / p.pf_sa;
-                if (pick(la, li)) pf_voff = (uint32_t)((int64_t)((tn % p.pf_sa) * la + li) * p.lda * 2);
+                if (pick(la, li)) pf_voff = (uint32_t)((int64_t)((tn % p.pf_sa) * la + li) * p.lda * 2) + kOffBias;
             }
             pf_step = ROWB;
         } else if (p.pf_sb > 0) {
@@ -318,7 +341,7 @@ gemm_kernel(const GemmArgs p)
                     const int sh = p.pf_sb > 1 ? p.pf_sb / 2 : 1;
                     lb = (BN / 2) / sh; row0 = (p.pf_sb > 1 ? share >> 1 : 0) * lb; pf_up = (share & 1) != 0;
                 }
-                if (pick(lb, li)) pf_voff = (uint32_t)((int64_t)(row0 + li) * p.ldb * 2);
+                if (pick(lb, li)) pf_voff = (uint32_t)((int64_t)(row0 + li) * p.ldb * 2) + kOffBias;
                 pf_step = ROWB;
             } else {
                 constexpr int LPR = BN / 64;              // 128-byte lines per K-row of the slab
@@ -326,15 +349,16 @@ gemm_kernel(const GemmArgs p)
                 if (pick(lb, li)) {
                     const int line = share * lb + li;
                     const int kr = line / LPR, col = (line % LPR) * 64;
-                    if (col < p.N - n0) pf_voff = (uint32_t)(((int64_t)kr * p.ldb + col) * 2);
+                    if (col < p.N - n0) pf_voff = (uint32_t)(((int64_t)kr * p.ldb + col) * 2) + kOffBias;
                 }
                 pf_step = (uint32_t)b_step_bytes;         // the host enables this only if K * ldb * 2 < 2^31
             }
         }
     }
-    const __amdgpu_buffer_rsrc_t rsrc_pf = pf_is_a ? rsrc_a : (pf_up ? rsrc_b_up : rsrc_b);
+    const __amdgpu_buffer_rsrc_t rsrc_pf = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(pf_is_a ? base_a : (pf_up ? base_b_up : base_b)), 0, pf_is_a ? nrec_a : nrec_b, kBufferFlags);
     char *pf_sink = smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES) + wave * 256;
-    auto prefetch_step = [&](int step) {
+    auto prefetch_step = [&](int step) __attribute__((always_inline)) {
         const uint32_t off = step < ksteps - 1 ? 0u : kOobOffset;
         const int st = step < ksteps - 1 ? step : 0;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_pf, FACT_LDS_PTR(pf_sink), 4, pf_voff | off, st * (int)pf_step, 0, 0);
@@ -345,8 +369,8 @@ gemm_kernel(const GemmArgs p)
     // ksteps read nothing but zeros, so a phantom step adds exactly 0 to the accumulators and
     // the main loop needs no tail code.  Branch-free: setting the top offset bit puts a lane out
     // of the descriptor's range.
-#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SAME_M0) || defined(FACT_DBG_NO_VOFF)
-    bool dbg_skip = false;      // experiments only: no (or simplified) loads after the prologue
+#ifdef FACT_DBG_SKIP_LOADS
+    bool dbg_skip = false;      // experiments only: no loads after the prologue
 #endif
     struct StepCtx {
         char *s;
@@ -355,7 +379,7 @@ gemm_kernel(const GemmArgs p)
         int soff;
         __amdgpu_buffer_rsrc_t rb;
     };
-    auto step_ctx = [&](int step, int slot) {
+    auto step_ctx = [&](int step, int slot) __attribute__((always_inline)) {
         StepCtx c;
         c.s = smem + slot * STAGE;
         c.beyond = step >= ksteps ? kOobOffset : 0u;
@@ -365,53 +389,38 @@ gemm_kernel(const GemmArgs p)
         if constexpr (!TRANS_B) {
             const int ks = k_begin + st * BK;
             const int64_t rows_left = (int64_t)(k_end - 1 - ks);
-            c.rb = __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)b_step_base + st * b_step_bytes), 0,
-                                                     clamp31((rows_left * p.ldb + (p.N - n0)) * 2), kBufferFlags);
+            c.rb = __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)b_step_base + st * b_step_bytes - kOffBias), 0,
+                                                     clamp31((rows_left * p.ldb + (p.N - n0)) * 2 + kOffBias), kBufferFlags);
         } else {
-            c.rb = rsrc_b;
+            c.rb = rsrc_bw;
         }
         return c;
     };
-    // load number idx of a step: 0 .. A_LD-1 fill the A part, A_LD .. LOADS-1 the B part
-    auto issue_one = [&](const StepCtx &c, int idx) {
+    // load number idx of a step: 0 .. A_LD-1 fill the A part, A_LD .. LOADS-1 the B part.  Load i
+    // of a wave fills LDS block wave * LD + i of the operand: run i / RUN, member i % RUN.
+    auto issue_one = [&](const StepCtx &c, auto idx_) __attribute__((always_inline)) {
+        constexpr int idx = decltype(idx_)::value;             // compile-time: it selects the immediate offset
 #ifdef FACT_DBG_SKIP_LOADS
         if (c.beyond || dbg_skip) return;
 #endif
-#if defined(FACT_DBG_SAME_M0) || defined(FACT_DBG_NO_VOFF)
-        if (dbg_skip) {          // experiments only (wrong results, in-bounds): one LDS target / one offset for every load
-#ifdef FACT_DBG_SAME_M0
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(smem + wave * 1024), 16,
-                                                     a_lane + (a_blk0 + (idx & 3) * a_blk_step) + c.mask_k, c.soff, 0, 0);
-#else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(c.s + (wave + (idx & 7) * NWAVES) * 1024), 16,
-                                                     a_lane, c.soff, 0, 0);
-#endif
-            return;
-        }
-#endif
-        if (idx < A_LD) {
-            const int i = idx;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(c.s + (wave + i * NWAVES) * 1024), 16,
-                                                     a_lane + (a_blk0 + i * a_blk_step) + c.mask_k, c.soff, 0, 0);
+        if constexpr (idx < A_LD) {
+            constexpr int i = idx, run0 = (i / A_RUN) * A_RUN, t = i % A_RUN;
+            const int blk = wave * A_LD + i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(c.s + (wave * A_LD + run0) * 1024), 16,
+                                                     a_lane + ((uint32_t)blk * a_blk_bytes - t * 1024) + c.mask_k, c.soff, t * 1024, 0);
         } else {
-            const int i = idx - A_LD;
+            constexpr int i = idx - A_LD, run0 = (i / B_RUN) * B_RUN, t = i % B_RUN;
+            const int blk = wave * B_LD + i;
+            char *dst = c.s + A_BYTES + (wave * B_LD + run0) * 1024;
             if constexpr (TRANS_B) {
-                // Loads come in pairs: pair j = i/2 of a wave handles the 8-row group g = wave + j*NWAVES
-                // of each half of every wave tile.  With G = WTN/16 blocks per half wave tile, member
-                // h = i%2 fills LDS block (g/G)*2G + g%G + h*G.  Plain: LDS rows are B rows, so that is
-                // also the global row block.  Gated: the first half of a wave tile holds gate rows and the
-                // second the up rows of the same columns: both members read row block g, from B and B_up.
-                constexpr int G = WTN / 16;
-                static_assert(!TRANS_B || B_LD % 2 == 0, "B loads come in pairs");
-                const int j = i >> 1, h = i & 1;
-                const int g = wave + j * NWAVES;
-                const int blk = (g / G) * 2 * G + g % G + h * G;
-                const uint32_t goff = (uint32_t)(gated ? g : blk) * b_blk_bytes;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds((gated && h) ? rsrc_b_up : rsrc_b, FACT_LDS_PTR(c.s + A_BYTES + blk * 1024), 16,
-                                                         b_lane + goff + c.mask_k, c.soff, 0, 0);
+                static_assert(!TRANS_B || B_LD <= G, "one descriptor per wave");
+                const int seg = blk / G, x = blk % G;
+                const uint32_t goff = (uint32_t)(gated ? (seg >> 1) * G + x : blk) * b_blk_bytes;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_bw, FACT_LDS_PTR(dst), 16,
+                                                         b_lane[0] + (goff - t * 1024) + c.mask_k, c.soff, t * 1024, 0);
             } else {
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rb, FACT_LDS_PTR(c.s + A_BYTES + (wave + i * NWAVES) * 1024), 16,
-                                                         b_lane + (b_blk0 + i * b_blk_step) + c.beyond, 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rb, FACT_LDS_PTR(dst), 16,
+                                                         b_lane[i % B_NV] + ((uint32_t)blk * b_blk_bytes - t * 1024) + c.beyond, 0, t * 1024, 0);
             }
         }
     };
@@ -466,7 +475,7 @@ gemm_kernel(const GemmArgs p)
 
     // Fragment read number t of unit u of the stage at s: its MTH A fragments, then (first part
     // of a sub-step only) the NT B fragments of the sub-step.
-    auto read_one = [&](const char *s, int u, int t) {
+    auto read_one = [&](const char *s, int u, int t) __attribute__((always_inline)) {
         const int kk = u / PH, h = u % PH;
 #ifdef FACT_DBG_NO_READS
         if (dbg_skip) return;
@@ -496,7 +505,7 @@ gemm_kernel(const GemmArgs p)
     };
     // trans_b=0 only: all LDS reads issued so far have returned; the fragment registers are
     // operands so that no MFMA using them can be scheduled above the wait.
-    auto wait_frags = [&](int set) {
+    auto wait_frags = [&](int set) __attribute__((always_inline)) {
         if constexpr (!TRANS_B) {
             static_assert(TRANS_B || NT == 2 || NT == 4 || NT == 8, "operand lists below");
             if constexpr (NT == 8)
@@ -512,7 +521,7 @@ gemm_kernel(const GemmArgs p)
     // Operand order (B fragment first) makes the accumulator tile hold D[n_local][m_local]:
     // lane (r16, q) owns output row r16 and the 4 consecutive output columns 4q .. 4q+3.
     constexpr int NMFMA = MTH * NT;
-    auto mfma_one = [&](int u, int idx) {
+    auto mfma_one = [&](int u, int idx) __attribute__((always_inline)) {
         const int kk = u / PH, h = u % PH;
         const int x = idx / NT, nt = idx % NT;
         // inline asm pins the accumulator tile in place in the accumulation registers; through the
@@ -551,24 +560,24 @@ gemm_kernel(const GemmArgs p)
     constexpr int LOAD_SPAN = STAGES > 2 ? (TG * 15) / 16 : (TG * FACT_LOAD_FRAC_NUM) / FACT_LOAD_FRAC_DEN;
     auto load_gap = [](int l) constexpr { const int g = 1 + (l * LOAD_SPAN) / LOADS; return g < TG ? g : TG - 1; };
     constexpr int SPAN = (NMFMA * 7) / 8 > 0 ? (NMFMA * 7) / 8 : 1;
-    auto body = [&](int kt, auto slot_tag) {
+    auto body = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
         constexpr int SLOT = decltype(slot_tag)::value;            // kt % STAGES, known at compile time
         const StepCtx c = step_ctx(kt + STAGES - 1, (SLOT + STAGES - 1) % STAGES);
         const char *s = smem + SLOT * STAGE;
-        static_for<U>([&](auto j_) {
+        static_for<U>([&](auto j_) __attribute__((always_inline)) {
             constexpr int j = decltype(j_)::value;
             constexpr int cu = (j + U - 1) % U;                    // the unit the MFMAs consume
             constexpr int nreads = MTH + (j % PH == 0 ? NT : 0);
             wait_frags((cu / PH) & 1);
-            static_for<NMFMA>([&](auto i_) {
+            static_for<NMFMA>([&](auto i_) __attribute__((always_inline)) {
                 constexpr int i = decltype(i_)::value;
-                static_for<nreads>([&](auto t_) {
+                static_for<nreads>([&](auto t_) __attribute__((always_inline)) {
                     constexpr int t = decltype(t_)::value;
                     if constexpr ((t * SPAN) / nreads == i) read_one(s, j, t);
                 });
-                static_for<LOADS>([&](auto l_) {
+                static_for<LOADS>([&](auto l_) __attribute__((always_inline)) {
                     constexpr int l = decltype(l_)::value;
-                    if constexpr (load_gap(l) == j * NMFMA + i) issue_one(c, l);
+                    if constexpr (load_gap(l) == j * NMFMA + i) issue_one(c, l_);
                 });
                 if constexpr (load_gap(LOADS - 1) == j * NMFMA + i) prefetch_step(kt + STAGES - 1 + p.pf_dist);
                 mfma_one(cu, i);
@@ -588,14 +597,13 @@ gemm_kernel(const GemmArgs p)
     // prologue's loads and the first of those are touched here, ahead of the loads (older than
     // them, so the wait counts are unaffected).
     for (int x = STAGES - 1; x < p.pf_dist; ++x) prefetch_step(x);
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) {
+    static_for<STAGES - 1>([&](auto s_) __attribute__((always_inline)) {
+        constexpr int s = decltype(s_)::value;
         const StepCtx c = step_ctx(s, s);
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) issue_one(c, i);
+        static_for<LOADS>([&](auto i_) __attribute__((always_inline)) { issue_one(c, i_); });
         prefetch_step(s + p.pf_dist);
-    }
-#if defined(FACT_DBG_SKIP_LOADS) || defined(FACT_DBG_SAME_M0) || defined(FACT_DBG_NO_VOFF)
+    });
+#ifdef FACT_DBG_SKIP_LOADS
     dbg_skip = true;
 #endif
     wait_loads_and_barrier<WAIT_N>();
@@ -613,7 +621,7 @@ gemm_kernel(const GemmArgs p)
     }
     // drain: the last unit of the last step
     wait_frags((KK - 1) & 1);
-    static_for<NMFMA>([&](auto i_) { mfma_one(U - 1, decltype(i_)::value); });
+    static_for<NMFMA>([&](auto i_) __attribute__((always_inline)) { mfma_one(U - 1, decltype(i_)::value); });
     // The compiler does not see the MFMAs inside the asm statements, so it cannot pad the gap the
     // hardware needs between a matrix instruction and the first ordinary read of its result.
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -660,7 +668,7 @@ gemm_kernel(const GemmArgs p)
     const bool fast = !partial && p.vec_store && m_wave + WTM <= p.M && n_wave + out_w <= nout;
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
-    auto fast_pass = [&](int pass, auto gated_tag) {
+    auto fast_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
         constexpr bool GATED = decltype(gated_tag)::value;
         constexpr int OUT_W = GATED ? WTN / 2 : WTN;
         constexpr int LPR = OUT_W / 8;                              // lanes per row
@@ -723,8 +731,8 @@ gemm_kernel(const GemmArgs p)
         }
     };
 
-#pragma unroll
-    for (int pass = 0; pass < WTM / EPI_ROWS; ++pass) {
+    static_for<WTM / EPI_ROWS>([&](auto pass_) __attribute__((always_inline)) {
+        constexpr int pass = decltype(pass_)::value;
         if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
 #pragma unroll
         for (int i = 0; i < EPI_TR; ++i)
@@ -741,7 +749,7 @@ gemm_kernel(const GemmArgs p)
 #ifdef FACT_DBG_TIMELINE
             if (pass < 2) dbg_e[2 + 2 * pass] = clock64();
 #endif
-            continue;
+            return;
         }
         // General path (tile edges, unaligned C / bias / residual, split-K partials), every access
         // guarded.  Read-back in batches of EPI_U row-chunks per lane: first every LDS read and every
@@ -850,7 +858,7 @@ gemm_kernel(const GemmArgs p)
 #ifdef FACT_DBG_TIMELINE
         if (pass < 2) dbg_e[2 + 2 * pass] = clock64();
 #endif
-    }
+    });
 #ifdef FACT_DBG_TIMELINE
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     dbg_e[5] = clock64();
