@@ -9,7 +9,7 @@ namespace fact {
 // columns of one row, adds the partials in ascending split order (fixed order, so the
 // result is bit-reproducible), applies the epilogue and rounds once.  The paper's
 // counterpart is the fix-up step of its Stream-K schedule (Section 5.2.3).
-__global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmArgs p)
+__global__ void __launch_bounds__(64) splitk_reduce_kernel(const GemmArgs p)
 {
     const bool gated = p.act == ACT_SILU_GATE;
     const int nout = gated ? (p.N >> 1) : p.N;
@@ -25,12 +25,23 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmArgs p)
         const float *src = p.P + (int64_t)m * p.N + n;
         const bool full = n + 3 < nout;
         if (full && vec_p) {
-            for (int s = 0; s < p.splits; ++s) {
-                const f32x4_t a = *(const f32x4_t *)(src + s * plane);
-                v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
-                if (gated) {
-                    const f32x4_t b = *(const f32x4_t *)(src + s * plane + nout);
-                    u[0] += b.x; u[1] += b.y; u[2] += b.z; u[3] += b.w;
+            // batches of 8 partials: all loads of a batch are issued before the first add, the adds
+            // keep the ascending split order
+            for (int s0 = 0; s0 < p.splits; s0 += 8) {
+                f32x4_t a[8], b[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (s0 + j < p.splits) {
+                        a[j] = *(const f32x4_t *)(src + (s0 + j) * plane);
+                        if (gated) b[j] = *(const f32x4_t *)(src + (s0 + j) * plane + nout);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (s0 + j < p.splits) {
+                        v[0] += a[j].x; v[1] += a[j].y; v[2] += a[j].z; v[3] += a[j].w;
+                        if (gated) { u[0] += b[j].x; u[1] += b[j].y; u[2] += b[j].z; u[3] += b[j].w; }
+                    }
                 }
             }
         } else {
@@ -65,9 +76,10 @@ hipError_t launch_splitk_reduce(const GemmArgs &args, hipStream_t stream)
 {
     const int nout = args.act == ACT_SILU_GATE ? args.N / 2 : args.N;
     const int64_t total = (int64_t)args.M * ((nout + 3) / 4);
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 256 * 64) blocks = 256 * 64;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, args);
+    // one-wave work-groups: even a 256 x 256 output spreads over all CUs
+    int64_t blocks = (total + 63) / 64;
+    if (blocks > 256 * 256) blocks = 256 * 256;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, args);
     return hipGetLastError();
 }
 

@@ -74,6 +74,17 @@ __device__ __forceinline__ float gelu_tanh(float z)
 
 __device__ __forceinline__ float silu(float z) { return z * sigmoid_fast(z); }
 
+// A pointer / integer that is the same in every lane of the wave, moved to scalar registers for
+// good (buffer descriptors must be scalar; a descriptor the compiler takes for lane-dependent is
+// applied lane group by lane group in a loop).
+__device__ __forceinline__ const char *wave_uniform(const char *ptr)
+{
+    const uint64_t v = (uint64_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const char *)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint32_t wave_uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h16) { return __uint_as_float(h16 << 16); }
 
 // fp32 -> bf16 bit pattern, round to nearest even; NaN -> quiet NaN.
@@ -305,7 +316,7 @@ gemm_kernel(const GemmArgs p)
     // A wave fills blocks wave*B_LD .. wave*B_LD + B_LD - 1: inside one half when B_LD <= G.
     const int b_seg0 = (wave * B_LD) / G;
     const bool b_wave_up = TRANS_B && gated && B_LD <= G && (b_seg0 & 1);
-    const __amdgpu_buffer_rsrc_t rsrc_bw = __builtin_amdgcn_make_buffer_rsrc((void *)(b_wave_up ? base_b_up : base_b), 0, nrec_b, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rsrc_bw = __builtin_amdgcn_make_buffer_rsrc((void *)wave_uniform(b_wave_up ? base_b_up : base_b), 0, wave_uniform(nrec_b), kBufferFlags);
 
     // ---- L2 prefetch ----------------------------------------------------------------------
     // The work-groups resident on one XCD at a time walk K in step, pf_sa of them sharing each A
@@ -356,7 +367,7 @@ gemm_kernel(const GemmArgs p)
         }
     }
     const __amdgpu_buffer_rsrc_t rsrc_pf = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(pf_is_a ? base_a : (pf_up ? base_b_up : base_b)), 0, pf_is_a ? nrec_a : nrec_b, kBufferFlags);
+        (void *)wave_uniform(pf_is_a ? base_a : (pf_up ? base_b_up : base_b)), 0, wave_uniform(pf_is_a ? nrec_a : nrec_b), kBufferFlags);
     char *pf_sink = smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES) + wave * 256;
     auto prefetch_step = [&](int step) __attribute__((always_inline)) {
         const uint32_t off = step < ksteps - 1 ? 0u : kOobOffset;
@@ -666,6 +677,8 @@ gemm_kernel(const GemmArgs p)
     // A lane's 8 columns are the same in every row-chunk it handles (64 is a multiple of the
     // lanes per row), so its bias values are loaded once.
     const bool fast = !partial && p.vec_store && m_wave + WTM <= p.M && n_wave + out_w <= nout;
+    // (8-wave work-groups have half the registers per wave: they keep to the general path here)
+    const bool fast_partial = NWAVES <= 4 && partial && (p.N & 3) == 0 && (nout & 3) == 0 && m_wave + WTM <= p.M && n_wave + out_w <= nout;
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
     auto fast_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
@@ -744,6 +757,20 @@ gemm_kernel(const GemmArgs p)
         if (pass < 2) dbg_e[1 + 2 * pass] = clock64();
 #endif
         const int total = EPI_ROWS * lanes_per_row;
+        if constexpr (NWAVES <= 4) if (fast_partial) {
+            // split-K partials of an interior tile: raw fp32, 16-byte stores, both halves of a gated
+            // tile at their contraction columns
+            constexpr int LPR4 = WTN / 4;                             // lanes per row, 4 columns each
+#pragma unroll
+            for (int base = 0; base < EPI_ROWS * LPR4; base += 64) {
+                const int idx = base + lane, row = idx / LPR4, c4 = idx % LPR4;
+                const f32x4_t x = *(const f32x4_t *)(region + row * EPI_PITCH + c4 * 16);
+                int nc = n0 + wn * WTN + c4 * 4;                       // plain: contraction column = output column
+                if (gated) nc = n0 + wn * (WTN / 2) + (c4 * 4) % (WTN / 2) + ((c4 * 4) / (WTN / 2)) * nout;
+                *(f32x4_t *)(P + (int64_t)(m_wave + pass * EPI_ROWS + row) * p.N + nc) = x;
+            }
+            return;
+        }
         if (fast) {
             if (gated) fast_pass(pass, std::true_type{}); else fast_pass(pass, std::false_type{});
 #ifdef FACT_DBG_TIMELINE
