@@ -122,7 +122,9 @@ int fact_gemm_splitk(int64_t M, int64_t N, int64_t K,
                      int split_k, void *ws, size_t ws_bytes, void *stream);
 
 /* Bytes of workspace fact_gemm_splitk needs for this shape and split_k (0 = the table's
- * choice).  Returns 0 when no workspace is needed or the arguments are invalid. */
+ * choice, which may also be a tail split, see fact_gemm_ex; negative = a forced tail split
+ * of -split_k ranges, largest need over the tile configurations).  Returns 0 when no
+ * workspace is needed or the arguments are invalid. */
 size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k);
 
 /*
@@ -137,8 +139,8 @@ size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int spl
  * W2 : bf16 [d_model][d_ff].     b2 : bf16 [d_model] or NULL.
  * R  : residual bf16 [T][d_model] or NULL (Y may alias R).
  * All matrices dense (leading dimension = row length).
- * ws : workspace for a split-K second GEMM, fact_block_mlp_workspace_bytes() bytes
- *      (may be NULL when that returns 0).
+ * ws : workspace for a split-K second GEMM or a tail split of either GEMM,
+ *      fact_block_mlp_workspace_bytes() bytes (may be NULL when that returns 0).
  */
 int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
                    const void *X, const void *W1, const void *W1u, const void *b1, int act,
@@ -157,7 +159,8 @@ int fact_num_configs(void);
 int fact_config_info(int id, int *tile_m, int *tile_n, int *waves_m, int *waves_n, int *lds_bytes);
 
 /* The table's choice for a shape (host logic only, no GPU needed): writes the tile
- * configuration id and the split-K factor (>= 1).  batch >= 1.  Returns FACT_OK, or an
+ * configuration id and the split-K factor (>= 1; -g for a tail split of g ranges, see
+ * fact_gemm_ex).  batch >= 1.  Returns FACT_OK, or an
  * error if the shape is invalid.  config_id is -1 when the shape can only run on the
  * guarded fallback kernel (unaligned dimensions). */
 int fact_select_config(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b, int act,
@@ -165,9 +168,17 @@ int fact_select_config(int64_t batch, int64_t M, int64_t N, int64_t K, int trans
 
 /*
  * fact_gemm_batched with the tile configuration, split factor and tile-row group size
- * forced: the entry point the on-device sweep uses.  config_id < 0, split_k <= 0 and
+ * forced: the entry point the on-device sweep uses.  config_id < 0, split_k == 0 and
  * group_m <= 0 mean "table's choice".  split_k > 1 needs ws (see fact_gemm_splitk) and
- * batch == 1.  A configuration whose LDS or alignment needs the shape cannot meet
+ * batch == 1.
+ * split_k = -g (g >= 2) asks for a tail split, this library's form of the paper's Stream-K
+ * fix-up (Section 4.2 Action 2, Section 5.2.3): tiles are computed whole as long as they fill
+ * all compute units; the tiles of the last, partly filled round are shared by g work-groups
+ * each, one K range apiece, which hand their fp32 partial tiles to the one holding the last
+ * range through ws; that one adds them in ascending range order (bit-reproducible) and runs
+ * the epilogue.  Needs batch == 1 and fact_gemm_splitk_workspace_bytes(M, N, K, -g) bytes of
+ * ws (contents are scratch and need no clearing).  FACT_ERR_UNSUPPORTED if the shape has no
+ * partly filled round or too little K per range.  A configuration whose LDS or alignment needs the shape cannot meet
  * returns FACT_ERR_UNSUPPORTED (recorded by the sweep as a launch failure, as in
  * Section 5.1 "Auto-tuning methodology").
  */

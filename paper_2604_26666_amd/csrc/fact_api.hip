@@ -4,6 +4,8 @@
 #include "../../include/fact.h"
 #include "launch.h"
 
+#include <atomic>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -95,8 +97,10 @@ static Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_
     if (!fast_dims_ok(M, N, K, trans_b)) return pl;
     for (const TableRow *r = g_table; r->cfg >= 0; ++r) {
         if (r->batch == batch && r->M == M && r->N == N && r->K == K && r->trans_b == trans_b &&
-            r->gated == (int)gated && (allow_split || r->split <= 1)) {
-            pl.cfg = r->cfg; pl.split = r->split < 1 ? 1 : r->split; pl.group_m = r->group_m > 0 ? r->group_m : 4;
+            r->gated == (int)gated && (allow_split || (r->split >= 0 && r->split <= 1))) {
+            pl.cfg = r->cfg;
+            pl.split = r->split == 0 ? 1 : r->split;       // negative: a tail split, which needs a workspace as well
+            pl.group_m = r->group_m > 0 ? r->group_m : 4;
             return pl;
         }
     }
@@ -165,6 +169,31 @@ static size_t splitk_ws_bytes(int64_t M, int64_t N, int split)
     return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
+// Tail split: the tiles of the last, partly filled round are shared by g work-groups each.
+struct TailPlan {
+    int64_t first = 0;      // tiles computed whole
+    int64_t rem = 0;        // tiles in the tail
+    int g = 0;              // K ranges per tail tile (0: no tail split)
+    size_t bytes() const { return g > 1 ? (size_t)rem * (g - 1) * sizeof(float) * tile_floats + ((size_t)rem * (g - 1) + 1) * 8 : 0; }
+    size_t flags_offset() const { return (size_t)rem * (g - 1) * sizeof(float) * tile_floats; }
+    size_t tile_floats = 0;
+};
+
+static int wgs_per_cu(const ConfigDesc &c);
+static TailPlan tail_plan(const ConfigDesc &c, int64_t tiles, int64_t K, int g)
+{
+    TailPlan t;
+    t.tile_floats = (size_t)c.bm * c.bn;
+    const int64_t slots = (int64_t)kNumCU * wgs_per_cu(c);
+    const int64_t ksteps = (K + 63) / 64;
+    if (g < 2 || ksteps / g < 4) return t;            // too little K per range to be worth a hand-over
+    t.first = tiles / slots * slots;
+    t.rem = tiles - t.first;
+    if (t.rem == 0) { t.first = 0; return t; }
+    t.g = g;
+    return t;
+}
+
 // ---- the one launch path every entry point goes through ----------------------------------------
 
 static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_table_split,
@@ -184,7 +213,11 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         if (split <= 0) pl.split = 1;
     }
     if (split > 0) pl.split = split;
+    if (split < 0) pl.split = split;                  // forced tail split, -split ranges per tail tile
     if (group_m > 0) pl.group_m = group_m;
+    int tail_g = 0;                                   // a negative split in a plan is a tail split
+    if (pl.split < 0) { tail_g = -pl.split; pl.split = 1; }
+    if (tail_g > 1 && q.batch != 1) { if (split < 0) return FACT_ERR_UNSUPPORTED; tail_g = 0; }
     if (pl.split > 1 && q.batch != 1) return FACT_ERR_UNSUPPORTED;
     if (pl.split > kMaxGridZ) return FACT_ERR_UNSUPPORTED;
 
@@ -231,6 +264,22 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
 
     a.pf_dist = 1;
+    a.tail_first = (int)(tiles_m * tiles_n);
+    if (tail_g > 1 && pl.split <= 1) {
+        const TailPlan t = tail_plan(c, tiles_m * tiles_n, q.K, tail_g);
+        if (t.g > 1 && ws && aligned16(ws) && ws_bytes >= t.bytes()) {
+            // flags carry a launch-unique 64-bit value, so the workspace needs no clearing
+            static std::atomic<unsigned long long> epoch{
+                (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
+            a.tail_first = (int)t.first;
+            a.tail_g = t.g;
+            a.tail_ws = (float *)ws;
+            a.tail_flags = (unsigned long long *)((char *)ws + t.flags_offset());
+            a.tail_epoch = ++epoch;
+        } else if (split < 0) {
+            return t.g > 1 ? FACT_ERR_WORKSPACE : FACT_ERR_UNSUPPORTED;
+        }
+    }
     if (pl.split > 1) {
         // K ranges are multiples of the 64-element staging step
         int64_t kps = (q.K + pl.split - 1) / pl.split;
@@ -319,10 +368,36 @@ int fact_gemm_splitk(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda
     return run(q, -1, split_k, 0, true, ws, ws_bytes, (hipStream_t)stream);
 }
 
+// workspace a plan needs: split-K partial planes, or the partial tiles and flags of a tail split
+static size_t plan_ws_bytes(const Plan &pl, int64_t M, int64_t N, int64_t K, bool gated)
+{
+    if (pl.cfg < 0) return 0;
+    if (pl.split > 1) return splitk_ws_bytes(M, N, pl.split);
+    if (pl.split < -1) {
+        const ConfigDesc &c = g_configs[pl.cfg];
+        const int64_t nout = gated ? N / 2 : N, bn_out = gated ? c.bn / 2 : c.bn;
+        const int64_t tiles = ((M + c.bm - 1) / c.bm) * ((nout + bn_out - 1) / bn_out);
+        return tail_plan(c, tiles, K, -pl.split).bytes();
+    }
+    return 0;
+}
+
 size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k)
 {
-    if (M <= 0 || N <= 0 || K <= 0 || split_k < 0) return 0;
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    if (split_k < 0) {
+        // forced tail split (fact_gemm_ex): the largest need over the tile configurations
+        size_t need = 0;
+        for (int i = 0; i < kNumConfigs; ++i)
+            for (int gated = 0; gated < 2; ++gated) {
+                Plan pl; pl.cfg = i; pl.split = split_k;
+                const size_t b = plan_ws_bytes(pl, M, N, K, gated != 0);
+                if (b > need) need = b;
+            }
+        return need;
+    }
     int s = split_k;
+    size_t tail_need = 0;
     if (s == 0) {
         // the table's choice may depend on layout and epilogue; report the largest over them
         for (int tb = 0; tb < 2; ++tb)
@@ -330,9 +405,12 @@ size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int spl
                 if (act == FACT_ACT_SILU_GATE && (!tb || N % 2)) continue;
                 Plan pl = make_plan(1, M, N, K, tb, act, true);
                 if (pl.cfg >= 0 && pl.split > s) s = pl.split;
+                const size_t b = pl.split < -1 ? plan_ws_bytes(pl, M, N, K, act == FACT_ACT_SILU_GATE) : 0;
+                if (b > tail_need) tail_need = b;
             }
     }
-    return splitk_ws_bytes(M, N, s);
+    const size_t sk = splitk_ws_bytes(M, N, s);
+    return sk > tail_need ? sk : tail_need;
 }
 
 int fact_gemm_ex(int64_t batch, int64_t M, int64_t N, int64_t K,
@@ -349,9 +427,13 @@ int fact_gemm_ex(int64_t batch, int64_t M, int64_t N, int64_t K,
 size_t fact_block_mlp_workspace_bytes(int64_t T, int64_t d_model, int64_t d_ff, int act)
 {
     if (T <= 0 || d_model <= 0 || d_ff <= 0) return 0;
-    (void)act;
-    Plan pl = make_plan(1, T, d_model, d_ff, 1, FACT_ACT_NONE, true);
-    return pl.cfg >= 0 ? splitk_ws_bytes(T, d_model, pl.split) : 0;
+    if (act < 0 || act > 2) return 0;
+    const bool gated = act == FACT_ACT_SILU_GATE;
+    const Plan p1 = make_plan(1, T, gated ? 2 * d_ff : d_ff, d_model, 1, act, true);
+    const Plan p2 = make_plan(1, T, d_model, d_ff, 1, FACT_ACT_NONE, true);
+    const size_t b1 = p1.split < -1 ? plan_ws_bytes(p1, T, gated ? 2 * d_ff : d_ff, d_model, gated) : 0;   // GEMM 1 never splits K
+    const size_t b2 = plan_ws_bytes(p2, T, d_model, d_ff, false);
+    return b1 > b2 ? b1 : b2;
 }
 
 int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
@@ -374,7 +456,11 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
     e1.act = act;
     Problem q1{1, T, gated ? 2 * d_ff : d_ff, d_model, X, d_model, 0, W1, d_model, 0, 1,
                gated ? W1u : nullptr, H, d_ff, 0, e1};
-    int rc = run(q1, -1, 1, 0, false, nullptr, 0, (hipStream_t)stream);
+    const size_t need = fact_block_mlp_workspace_bytes(T, d_model, d_ff, act);
+    if (need > 0 && (!ws || ws_bytes < need)) return FACT_ERR_WORKSPACE;
+    // (the first GEMM never splits K into planes, but its last round of tiles may be split)
+    const Plan p1 = make_plan(1, T, gated ? 2 * d_ff : d_ff, d_model, 1, act, true);
+    int rc = run(q1, -1, p1.split < -1 ? 0 : 1, 0, p1.split < -1, ws, ws_bytes, (hipStream_t)stream);
     if (rc != FACT_OK) return rc;
 
     // GEMM 2: Y = H W2^T + b2 + R  (may split K = d_ff when the table says so and ws allows)
@@ -385,8 +471,6 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
     e2.ldr = d_model;
     e2.act = FACT_ACT_NONE;
     Problem q2{1, T, d_model, d_ff, H, d_ff, 0, W2, d_ff, 0, 1, nullptr, Y, d_model, 0, e2};
-    const size_t need = fact_block_mlp_workspace_bytes(T, d_model, d_ff, act);
-    if (need > 0 && (!ws || ws_bytes < need)) return FACT_ERR_WORKSPACE;
     return run(q2, -1, 0, 0, need > 0, ws, ws_bytes, (hipStream_t)stream);
 }
 

@@ -53,6 +53,13 @@ struct GemmArgs {
     int vec_store;          // 1: C / residual / bias allow 16-byte vector access
     int pf_sa, pf_sb;       // L2 prefetch: work-groups that share an A row-panel / a B column-panel (0: off)
     int pf_dist;            // L2 prefetch: K steps ahead of the step being loaded into LDS (>= 1)
+    // Tail split (the last, partly filled round of tiles): work-groups [0, tail_first) own one tile
+    // each; the remaining tiles are shared by tail_g work-groups each, one K range apiece.
+    int tail_first;         // number of tiles computed whole (== tiles_m * tiles_n when tail_g <= 1)
+    int tail_g;             // K ranges per tail tile (0 or 1: off)
+    float *tail_ws;         // fp32 partial accumulators, (tail_g - 1) per tail tile
+    unsigned long long *tail_flags;   // one per partial, then one time-out counter
+    unsigned long long tail_epoch;    // value a flag takes when its partial of THIS launch is complete
 };
 
 constexpr uint32_t kBufferFlags = 0x00020000u;   // raw buffer descriptor word 3 (32-bit data format)
@@ -109,12 +116,17 @@ __device__ __forceinline__ u32x2_t pack4_bf16(float a, float b, float c, float d
 // gets one contiguous range of the tile order; inside that order tiles are walked
 // group_m tile-rows at a time, column by column, so that the tiles resident on one
 // XCD share A row-panels and B column-panels.
-__device__ __forceinline__ void tile_coords(const GemmArgs &p, int pid, int &tm, int &tn)
+__device__ __forceinline__ void tile_index_to_coords(const GemmArgs &p, int idx, int &tm, int &tn);
+__device__ __forceinline__ void tile_coords(const GemmArgs &p, int pid, int total, int &tm, int &tn)
 {
-    const int total = p.tiles_m * p.tiles_n;
     const int q = total >> 3, rem = total & 7;
     const int xcd = pid & 7, loc = pid >> 3;
     const int idx = xcd * q + (xcd < rem ? xcd : rem) + loc;
+    tile_index_to_coords(p, idx, tm, tn);
+}
+// position idx of the tile order -> tile coordinates
+__device__ __forceinline__ void tile_index_to_coords(const GemmArgs &p, int idx, int &tm, int &tn)
+{
     const int per_group = p.group_m * p.tiles_n;
     const int grp = idx / per_group;
     const int first_m = grp * p.group_m;
@@ -213,8 +225,21 @@ gemm_kernel(const GemmArgs p)
     const int wm = wave / WGN, wn = wave % WGN;
     const int r16 = lane & 15, q = lane >> 4;
 
+    // Work-group -> tile (and, for a tile of the split tail, K range).  Tail work-groups are
+    // numbered K range by K range, so that the work-groups holding a tile's last range - the ones
+    // that wait for the others' partial sums - are dispatched after all they wait for.
     int tm, tn;
-    tile_coords(p, blockIdx.x, tm, tn);
+    const bool tail_mode = p.tail_g > 1;
+    const bool in_tail = tail_mode && (int)blockIdx.x >= p.tail_first;
+    int tail_tile = 0, tail_seg = 0;                 // tile number within the tail, K range number
+    if (!in_tail) {
+        tile_coords(p, blockIdx.x, tail_mode ? p.tail_first : p.tiles_m * p.tiles_n, tm, tn);
+    } else {
+        const int t_rem = p.tiles_m * p.tiles_n - p.tail_first;
+        const int j = (int)blockIdx.x - p.tail_first;
+        tail_seg = j / t_rem; tail_tile = j - tail_seg * t_rem;
+        tile_index_to_coords(p, p.tail_first + tail_tile, tm, tn);
+    }
     const int z = blockIdx.z;
     const bool gated = (p.act == ACT_SILU_GATE);
     const int nout = gated ? (p.N >> 1) : p.N;
@@ -223,7 +248,12 @@ gemm_kernel(const GemmArgs p)
 
     int k_begin = 0, k_end = p.K;
     int64_t batch_a = 0, batch_b = 0, batch_c = 0, batch_r = 0;
-    if (p.splits > 1) {
+    if (in_tail) {
+        const int steps = (p.K + BK - 1) / BK;
+        k_begin = (int)((int64_t)tail_seg * steps / p.tail_g) * BK;
+        const int e = (int)((int64_t)(tail_seg + 1) * steps / p.tail_g) * BK;
+        k_end = e < p.K ? e : p.K;
+    } else if (p.splits > 1) {
         k_begin = z * p.k_per_split;
         k_end = k_begin + p.k_per_split < p.K ? k_begin + p.k_per_split : p.K;
     } else {
@@ -445,7 +475,7 @@ gemm_kernel(const GemmArgs p)
     //  supplies the address of K-row j, columns 4c..4c+3, and receives column (lane % 16) of
     //  K-rows 0..3: four consecutive K-values of its own column.  Sub-step and half select
     //  K-rows through constant offsets because the swizzle depends on k & 3 = j only.
-    uint32_t a_addr[KK], b_addr[KK], b_frag[NT];
+    uint32_t a_addr[KK], b_addr[KK], b_frag[NT / 2];        // trans_b=0: even tiles; an odd tile lies 32 bytes further
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
         const uint32_t ch = (uint32_t)(((4 * kk + q) ^ swz_k(r16)) << 4);
@@ -453,11 +483,13 @@ gemm_kernel(const GemmArgs p)
         b_addr[kk] = (uint32_t)(A_BYTES + (wn * WTN + r16) * ROWB) + ch;
     }
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
+    for (int t = 0; t < NT / 2; ++t) {
+        // the swizzle touches chunk-index bits 2 and up, a step from an even tile to the next odd
+        // one only bit 1: the odd tile's address is the even one's + 2 chunks
         const int j = (lane >> 2) & 3, c = lane & 3;
         const int k = 8 * q + j;                                     // + 32*kk + 4*half
-        const int n = wn * WTN + nt * 16 + 4 * c;
-        b_frag[nt] = (uint32_t)(A_BYTES + k * (BN * 2) + ((((n >> 3) ^ swz_n<BN>(k))) << 4) + (c & 1) * 8);
+        const int n = wn * WTN + 2 * t * 16 + 4 * c;
+        b_frag[t] = (uint32_t)(A_BYTES + k * (BN * 2) + ((((n >> 3) ^ swz_n<BN>(k))) << 4) + (c & 1) * 8);
     }
 
     f32x4_t acc[MT][NT];
@@ -486,15 +518,16 @@ gemm_kernel(const GemmArgs p)
 
     // Fragment read number t of unit u of the stage at s: its MTH A fragments, then (first part
     // of a sub-step only) the NT B fragments of the sub-step.
-    auto read_one = [&](const char *s, int u, int t) __attribute__((always_inline)) {
+    auto read_one = [&](const char *s, int u, auto t_) __attribute__((always_inline)) {
+        constexpr int t = decltype(t_)::value;                // compile-time: it selects an immediate offset
         const int kk = u / PH, h = u % PH;
 #ifdef FACT_DBG_NO_READS
         if (dbg_skip) return;
 #endif
-        if (t < MTH) {
+        if constexpr (t < MTH) {
             af[u & 1][t] = *(const bf16x8_t *)(s + a_addr[kk] + (h * MTH + t) * 16 * ROWB);
         } else {
-            const int nt = t - MTH;
+            constexpr int nt = t - MTH;
             if constexpr (TRANS_B) {
                 bf[kk & 1][nt] = *(const bf16x8_t *)(s + b_addr[kk] + nt * 16 * ROWB);
             } else {
@@ -504,10 +537,10 @@ gemm_kernel(const GemmArgs p)
                 // consumer waits explicitly (wait_frags below), and a build whose register
                 // allocation spills is refused (a spill could store a register before its data
                 // has arrived).
-                const uint32_t a = (uint32_t)(size_t)FACT_LDS_PTR(s + b_frag[nt]) + kk * 32 * (BN * 2);
+                const uint32_t a = (uint32_t)(size_t)FACT_LDS_PTR(s + b_frag[nt / 2]) + kk * 32 * (BN * 2);
                 s16x4_t lo, hi;
-                asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a));
-                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a), "n"(4 * (BN * 2)));
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a), "n"((nt % 2) * 32));
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a), "n"((nt % 2) * 32 + 4 * (BN * 2)));
                 typedef short s16x8_t __attribute__((ext_vector_type(8)));
                 const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 bf[kk & 1][nt] = __builtin_bit_cast(bf16x8_t, both);
@@ -584,7 +617,7 @@ gemm_kernel(const GemmArgs p)
                 constexpr int i = decltype(i_)::value;
                 static_for<nreads>([&](auto t_) __attribute__((always_inline)) {
                     constexpr int t = decltype(t_)::value;
-                    if constexpr ((t * SPAN) / nreads == i) read_one(s, j, t);
+                    if constexpr ((t * SPAN) / nreads == i) read_one(s, j, t_);
                 });
                 static_for<LOADS>([&](auto l_) __attribute__((always_inline)) {
                     constexpr int l = decltype(l_)::value;
@@ -641,6 +674,42 @@ gemm_kernel(const GemmArgs p)
     const long long dbg_t2 = wall_clock64();
     const long long dbg_c2 = clock64();
 #endif
+
+    // ---- split tail: hand over or collect partial sums ------------------------------------------
+    // A tile of the tail is accumulated by tail_g work-groups, one K range each.  All but the last
+    // store their accumulators as an fp32 tile (row-major, through the epilogue's LDS transpose)
+    // and then raise a flag; the last one waits for the flags and adds the partial tiles, in
+    // ascending K-range order, to its own sums as it reads them back in the epilogue.  The order is
+    // fixed, so the result is bit-reproducible.  Producers never wait and are dispatched before the
+    // work-group that waits for them; the wait is bounded all the same (a time-out is counted
+    // behind the flags and the tile is finished with what has arrived).
+    // The partners may sit on different XCDs, whose L2 caches are not coherent with each other.
+    // Partial tiles and flags therefore move with system-scope accesses (write-through stores,
+    // cache-bypassing loads): a cache-wide write-back and invalidate around the hand-over, which is
+    // what a device-scope fence amounts to here, was measured to cost more than the split saves.
+    const int tail_parts = in_tail ? p.tail_g - 1 : 0;
+    const bool tail_producer = in_tail && tail_seg < tail_parts;
+    constexpr int TILE_FLOATS = BM * BN;
+    constexpr int kSysScope = 17;                    // cache-policy bits sc0 | sc1 of buffer loads / stores
+    const __amdgpu_buffer_rsrc_t rsrc_part = __builtin_amdgcn_make_buffer_rsrc(      // this tile's partials
+        (void *)wave_uniform((const char *)(in_tail ? p.tail_ws + (int64_t)tail_tile * tail_parts * TILE_FLOATS : nullptr)), 0,
+        (uint32_t)(tail_parts * TILE_FLOATS * 4), kBufferFlags);
+    if (in_tail && !tail_producer) {
+        unsigned long long *flags = p.tail_flags + (int64_t)tail_tile * tail_parts;
+        if (tid == 0) {
+            int budget = 1 << 20;
+            for (int sgm = 0; sgm < tail_parts; ++sgm)
+                while (__hip_atomic_load(flags + sgm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != p.tail_epoch && budget > 0) {
+                    __builtin_amdgcn_s_sleep(8);
+                    --budget;
+                }
+            if (budget == 0) {
+                const int t_rem = p.tiles_m * p.tiles_n - p.tail_first;
+                __hip_atomic_fetch_add(p.tail_flags + (int64_t)t_rem * tail_parts, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+        }
+        __syncthreads();
+    }
 
     // ---- epilogue ---------------------------------------------------------------------------
     // Accumulator tile (mt, nt), lane (r16, q): output row mt*16 + r16, output columns
@@ -712,6 +781,13 @@ gemm_kernel(const GemmArgs p)
                     const char *src = region + row[j] * EPI_PITCH + c8 * 32;
                     x[j][0] = *(const f32x4_t *)src; x[j][1] = *(const f32x4_t *)(src + 16);
                     if constexpr (GATED) { y[j][0] = *(const f32x4_t *)(src + OUT_W * 4); y[j][1] = *(const f32x4_t *)(src + OUT_W * 4 + 16); }
+                    // last K range of a split tail tile: add the other ranges' partial sums, in range order
+                    for (int sgm = 0; sgm < tail_parts; ++sgm) {
+                        const int ps = ((wm * WTM + pass * EPI_ROWS + row[j]) * BN + wn * WTN + c8 * 8) * 4, so = sgm * TILE_FLOATS * 4;
+                        auto ld = [&](int off) { return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_part, ps + off, so, kSysScope)); };
+                        x[j][0] += ld(0); x[j][1] += ld(16);
+                        if constexpr (GATED) { y[j][0] += ld(OUT_W * 4); y[j][1] += ld(OUT_W * 4 + 16); }
+                    }
                 }
             }
 #pragma unroll
@@ -757,6 +833,24 @@ gemm_kernel(const GemmArgs p)
         if (pass < 2) dbg_e[1 + 2 * pass] = clock64();
 #endif
         const int total = EPI_ROWS * lanes_per_row;
+        if (tail_producer) {
+            // partial tile, fp32 row-major [BM][BN] in accumulator column order (gated: gate columns,
+            // then up columns, per wave); the wave's EPI_ROWS x WTN block of this pass, 16 bytes per lane
+            constexpr int LPR4 = WTN / 4;
+            const int dst = (tail_seg * TILE_FLOATS + (wm * WTM + pass * EPI_ROWS) * BN + wn * WTN) * 4;     // bytes
+#pragma unroll
+            for (int base = 0; base < EPI_ROWS * LPR4; base += 64) {
+                const int idx = base + lane, row = idx / LPR4, c4 = idx % LPR4;
+                const u32x4_t x = *(const u32x4_t *)(region + row * EPI_PITCH + c4 * 16);
+                // The whole offset goes into the per-lane operand, the scalar one stays the constant 0:
+                // with a scalar-register offset the compiler assumes that the data registers of a
+                // 16-byte buffer store may be overwritten in the very next cycle, and on this chip
+                // the last lanes of each 16 then stored the overwriting value (seen as the next
+                // store's offset inside the partial tile).  With a constant it keeps the wait states.
+                __builtin_amdgcn_raw_buffer_store_b128(x, rsrc_part, dst + (row * BN + c4 * 4) * 4, 0, kSysScope);
+            }
+            return;
+        }
         if constexpr (NWAVES <= 4) if (fast_partial) {
             // split-K partials of an interior tile: raw fp32, 16-byte stores, both halves of a gated
             // tile at their contraction columns
@@ -807,6 +901,18 @@ gemm_kernel(const GemmArgs p)
                         const f32x4_t u0 = *(const f32x4_t *)su, u1 = *(const f32x4_t *)(su + 16);
                         u[j][0] = u0.x; u[j][1] = u0.y; u[j][2] = u0.z; u[j][3] = u0.w;
                         u[j][4] = u1.x; u[j][5] = u1.y; u[j][6] = u1.z; u[j][7] = u1.w;
+                    }
+                    for (int sgm = 0; sgm < tail_parts && !tail_producer; ++sgm) {       // see the fast path
+                        const int ps = ((wm * WTM + pass * EPI_ROWS + row) * BN + wn * WTN + c8 * 8) * 4, so = sgm * TILE_FLOATS * 4;
+                        auto ld = [&](int off) { return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_part, ps + off, so, kSysScope)); };
+                        const f32x4_t a0 = ld(0), a1 = ld(16);
+                        v[j][0] += a0.x; v[j][1] += a0.y; v[j][2] += a0.z; v[j][3] += a0.w;
+                        v[j][4] += a1.x; v[j][5] += a1.y; v[j][6] += a1.z; v[j][7] += a1.w;
+                        if (gated) {
+                            const f32x4_t b0 = ld(out_w * 4), b1 = ld(out_w * 4 + 16);
+                            u[j][0] += b0.x; u[j][1] += b0.y; u[j][2] += b0.z; u[j][3] += b0.w;
+                            u[j][4] += b1.x; u[j][5] += b1.y; u[j][6] += b1.z; u[j][7] += b1.w;
+                        }
                     }
                 }
                 if (!partial && vec[j]) {
@@ -886,6 +992,12 @@ gemm_kernel(const GemmArgs p)
         if (pass < 2) dbg_e[2 + 2 * pass] = clock64();
 #endif
     });
+    if (tail_producer) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // this thread's write-through stores have reached memory
+        __syncthreads();
+        if (tid == 0)
+            __hip_atomic_store(p.tail_flags + (int64_t)tail_tile * tail_parts + tail_seg, p.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
 #ifdef FACT_DBG_TIMELINE
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     dbg_e[5] = clock64();

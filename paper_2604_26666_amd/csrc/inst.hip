@@ -22,7 +22,9 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
         if (e != hipSuccess) return e;
         attr_set[dev] = true;
     }
-    dim3 grid((unsigned)(args.tiles_m * args.tiles_n), 1, (unsigned)grid_z);
+    const int tiles = args.tiles_m * args.tiles_n;
+    const int grid_x = args.tail_g > 1 ? args.tail_first + (tiles - args.tail_first) * args.tail_g : tiles;
+    dim3 grid((unsigned)grid_x, 1, (unsigned)grid_z);
     dim3 block(FACT_WM * FACT_WN * 64, 1, 1);
     hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
     return hipGetLastError();

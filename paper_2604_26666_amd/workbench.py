@@ -62,8 +62,9 @@ class Case:
                            stride_r=self.M * self.nout if self.batch > 1 else 0, act=self.act)
         lda = self.K
         ldb = self.K if self.trans_b else self.N
-        if not self.splitk and split == 0:
+        if self.batch > 1 and split == 0:
             split = 1
+        # split 0 = the table's choice, which may be a split-K or a tail split: both need a workspace
         need = fact.fact_gemm_splitk_workspace_bytes(self.M, self.N, self.K, split) if split != 1 else 0
         ws = self._ws(need)
         return fact.fact_gemm_ex(self.batch, self.M, self.N, self.K, t["A"], lda, self.M * self.K,
@@ -176,7 +177,7 @@ def time_all(steps=30, warmup=30, names=None):
         ms = time_case(c, steps, warmup)
         rc, cfg, split = fact.fact_select_config(c.batch, c.M, c.N, c.K, c.trans_b, c.act)
         r = report(c, ms) if ms else {"error": "refused"}
-        r["config_id"], r["split_k"] = cfg, (split if c.splitk else 1)
+        r["config_id"], r["split_k"] = cfg, split          # split_k < 0: tail split of that many K ranges
         out[c.name] = r
         c.free()
     return out

@@ -33,7 +33,7 @@ def padded(t, pad):
 
 
 def gemm(A, B, trans_b, bias=None, residual=None, act=fact.ACT_NONE, cfg=-1, split=0, group_m=0,
-         pad=0, entry="auto", in_place=False):
+         pad=0, entry="auto", in_place=False, return_ws=None):
     """Runs one GEMM on the GPU; A, B, bias, residual are CPU bf16 tensors.  Returns the
     uint16 output [M, Nout] and checks that nothing outside it was written."""
     M, K = A.shape
@@ -58,8 +58,8 @@ def gemm(A, B, trans_b, bias=None, residual=None, act=fact.ACT_NONE, cfg=-1, spl
     if entry == "auto":
         entry = "ex" if (cfg >= 0 or group_m > 0) else ("splitk" if split != 0 else "gemm")
     if entry in ("ex", "splitk") and split != 1:
-        ws_bytes = max(fact.fact_gemm_splitk_workspace_bytes(M, N, K, max(split, 0)), 16)
-        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        ws_bytes = max(fact.fact_gemm_splitk_workspace_bytes(M, N, K, split), 16)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda").fill_(0xA5)      # contents are scratch: no clearing needed
     if entry == "gemm":
         rc = fact.fact_gemm(M, N, K, Ab, lda, Bb, ldb, trans_b, Cb, ldc, ep)
     elif entry == "splitk":
@@ -68,6 +68,8 @@ def gemm(A, B, trans_b, bias=None, residual=None, act=fact.ACT_NONE, cfg=-1, spl
         rc = fact.fact_gemm_ex(1, M, N, K, Ab, lda, 0, Bb, ldb, 0, trans_b, Cb, ldc, 0, ep, cfg, split, group_m,
                                ws, ws_bytes)
     fact.binding.check(rc, f"{entry} M={M} N={N} K={K} tb={trans_b} act={act} cfg={cfg} split={split}")
+    if return_ws is not None:
+        return_ws.append(ws)
     out = bits_of(Cb)
     assert (out[M, :] == POISON).all() and (out[:, nout:] == POISON).all(), "wrote outside C"
     return out[:M, :nout].copy()

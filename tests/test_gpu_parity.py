@@ -33,8 +33,7 @@ def ncfg():
 
 
 def gate_capable(cfg):
-    bm, bn, wm, wn, _ = fact.fact_config_info(cfg)
-    return (bn // wn // 32) % 2 == 0
+    return True          # every compiled configuration pairs gate and up tiles inside a wave
 
 
 # ---- exact: layouts, tile mapping, every configuration -------------------------------------
@@ -276,3 +275,80 @@ def test_errors_launch_nothing():
     assert fact.fact_gemm_splitk(64, 64, 4096, A, 4096, A, 64, 0, C, 64, None, 4, None, 0) == -6
     assert fact.fact_gemm_ex(1, 64, 64, 64, A, 64, 0, A, 64, 0, 0, C, 64, 0, None, 99, 0, 0, None, 0) == -7
     assert (G().bits_of(C) == G().POISON).all()
+
+
+# ---- tail split: the last, partly filled round of tiles shared along K ---------------------------
+
+def _tail_timeouts(ws, cfg, M, nout_tiles_cols, K, g, gated=False):
+    """How often a work-group gave up waiting for a partial tile: the counter behind the flags of a
+    tail-split workspace is only ever incremented, and the helper pre-fills the workspace with 0xA5."""
+    bm, bn, _, _, _ = fact.fact_config_info(cfg)
+    bn_out = bn // 2 if gated else bn
+    tiles = -(-M // bm) * -(-nout_tiles_cols // bn_out)
+    slots = 256 * (2 if bm * bn <= 128 * 128 else 1)
+    rem = tiles - tiles // slots * slots or tiles
+    off = rem * (g - 1) * bm * bn * 4 + rem * (g - 1) * 8
+    torch.cuda.synchronize()
+    return int(ws[off:off + 8].cpu().view(torch.int64)[0]) - int(np.array([0xA5] * 8, dtype=np.uint8).view(np.int64)[0])
+
+
+@pytest.mark.parametrize("trans_b", [0, 1])
+@pytest.mark.parametrize("g", [2, 3])
+def test_tail_split_every_tile_shared(trans_b, g):
+    # fewer tiles than compute units: every tile is a tail tile, shared by g work-groups.
+    # Ragged M and N (guarded epilogue path adds the partials), K not a multiple of the step.
+    M, N, K = 264, 328, 1000
+    A = wl.normal((M, K), 1.0, "ts.A")
+    B = wl.normal((N, K) if trans_b else (K, N), 1.0, "ts.B")
+    bias = wl.normal((N,), 1.0, "ts.b")
+    res = wl.normal((M, N), 1.0, "ts.R")
+    r = ref.gemm_epilogue(A, B, bool(trans_b), bias=bias, residual=res, act=fact.ACT_GELU_TANH)
+    for cfg in (0, 3, 6, 11):
+        keep = []
+        got = G().gemm(A, B, trans_b, bias=bias, residual=res, act=fact.ACT_GELU_TANH, cfg=cfg, split=-g, return_ws=keep)
+        s = check.assert_close(got, r, what=f"tail split g={g} cfg {cfg}")
+        assert s["bits_equal_frac"] >= 0.97, s
+        again = G().gemm(A, B, trans_b, bias=bias, residual=res, act=fact.ACT_GELU_TANH, cfg=cfg, split=-g)
+        assert np.array_equal(got, again), "tail split is not bit-reproducible"
+        assert _tail_timeouts(keep[0], cfg, M, N, K, g) == 0
+
+
+def test_tail_split_interior_and_gated():
+    # aligned shape (straight-line epilogue adds the partials); gated epilogue
+    M, K, I = 512, 1024, 512
+    X = wl.normal((M, K), 1.0, "tg.X")
+    W = wl.normal((2 * I, K), 0.1, "tg.W")
+    r = ref.gemm_epilogue(X, W, True, act=fact.ACT_SILU_GATE)
+    for cfg in (0, 3, 12):
+        for g in (2, 4):
+            got = G().gemm(X, W, 1, act=fact.ACT_SILU_GATE, cfg=cfg, split=-g)
+            s = check.assert_close(got, r, what=f"gated tail split g={g} cfg {cfg}")
+            assert s["bits_equal_frac"] >= 0.97, s
+    A = wl.normal((M, K), 1.0, "tg.A")
+    B = wl.normal((K, I), 1.0, "tg.B")
+    r = ref.gemm_epilogue(A, B, False)
+    for cfg in (0, 1, 3):
+        got = G().gemm(A, B, 0, cfg=cfg, split=-2)
+        check.assert_close(got, r, what=f"plain tail split cfg {cfg}")
+
+
+def test_tail_split_after_full_rounds():
+    # more tiles than work-group slots: 576 tiles of 64 x 64 on 512 slots -> 512 whole tiles + 64 shared
+    n, K = 1536, 512
+    A = wl.uniform((n, K), "tf.A")
+    B = wl.uniform((n, K), "tf.B")
+    r = ref.gemm_epilogue(A, B, True)
+    keep = []
+    got = G().gemm(A, B, 1, cfg=6, split=-2, return_ws=keep)
+    check.assert_close(got, r, what="tail split after full rounds")
+    assert _tail_timeouts(keep[0], 6, n, n, K, 2) == 0
+    plain = G().gemm(A, B, 1, cfg=6)
+    whole = 512 * 64 * 64            # outputs of tiles computed whole are identical to the plain launch's
+    assert (got != plain).sum() <= got.size - whole
+
+
+def test_tail_split_refusals():
+    A = wl.normal((256, 128), 1.0, "tr.A")
+    B = wl.normal((256, 128), 1.0, "tr.B")
+    with pytest.raises(Exception):
+        G().gemm(A, B, 1, cfg=3, split=-2)        # 2 K steps: too little K per range
