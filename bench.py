@@ -21,7 +21,7 @@ PEAK_HBM_GBS = 8000.0
 # L2-fill + write-back bytes per launch of the headline workload, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy) summarised in
 # profiles/gemm_kernel_config2_hbm_traffic.md.  Reported only for that workload.
-MEASURED_TRAFFIC_BYTES = {8192: 789661 * 1024 * 2.000 + 131072 * 1024 * 1.000}
+MEASURED_TRAFFIC_BYTES = {8192: 789838 * 1024 * 2.000 + 131072 * 1024 * 1.000}
 
 
 def time_calls(fn, steps, warmup):

@@ -164,6 +164,51 @@ def time_case(case, steps=30, warmup=30, cfg=-1, split=0, group_m=0, min_warm_ms
     return a.elapsed_time(b) / steps
 
 
+def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30):
+    """As time_case with the table's choice, but successive launches use different copies of A, B and
+    C, enough copies that a launch never finds its operands in the 256 MB memory-side cache from
+    the launch before: the figure for a GEMM whose operands come from HBM (the cases bound by
+    memory traffic).  Returns (ms per launch, number of copies)."""
+    base = case.alloc()
+    per_set = case.min_bytes
+    sets = max(2, int(-(-min_bytes_total // per_set)))
+    copies = [base]
+    for _ in range(sets - 1):
+        c = dict(base)
+        c["A"], c["B"], c["C"], c["ws"] = base["A"].clone(), base["B"].clone(), torch.empty_like(base["C"]), None
+        copies.append(c)
+
+    def launch(i):
+        case.t = copies[i % sets]
+        return case.run()
+
+    try:
+        if launch(0) != 0:
+            return None, sets
+        for i in range(sets):             # every copy gets its workspace before the clock starts
+            launch(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(4):
+            launch(i)
+        b.record()
+        torch.cuda.synchronize()
+        est = max(a.elapsed_time(b) / 4, 1e-3)
+        warmup = min(max(warmup, int(20.0 / est) + 1), 2000)
+        steps = min(max(steps, int(10.0 / est) + 1), 1000)
+        for i in range(warmup):
+            launch(i)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(steps):
+            launch(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps, sets
+    finally:
+        case.t = base
+
+
 def report(case, ms):
     tf = case.flops / (ms * 1e-3) / 1e12
     gbs = case.min_bytes / (ms * 1e-3) / 1e9
@@ -178,6 +223,12 @@ def time_all(steps=30, warmup=30, names=None):
         rc, cfg, split = fact.fact_select_config(c.batch, c.M, c.N, c.K, c.trans_b, c.act)
         r = report(c, ms) if ms else {"error": "refused"}
         r["config_id"], r["split_k"] = cfg, split          # split_k < 0: tail split of that many K ranges
+        if ms and c.name.startswith("c3"):                 # bound by memory traffic: also with operands that miss the memory-side cache
+            ms_rot, sets = time_case_rotating(c)
+            if ms_rot:
+                rr = report(c, ms_rot)
+                r["rotating_operands"] = {"copies": sets, "ms": rr["ms"], "tflops": rr["tflops"],
+                                          "min_traffic_GBs": rr["min_traffic_GBs"], "pct_hbm_peak": rr["pct_hbm_peak"]}
         out[c.name] = r
         c.free()
     return out
