@@ -149,6 +149,32 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
 
 size_t fact_block_mlp_workspace_bytes(int64_t T, int64_t d_model, int64_t d_ff, int act);
 
+/*
+ * Fused multi-head self-attention (pattern p1 of Sections 5.2.4 and 5.2.5; tiled over keys so
+ * that the score matrix stays on chip, Section 2.1), one launch:
+ *     O[b,i,h,:] = sum_j softmax_j( scale * Q[b,i,h,:] . K[b,j,g,:] ) V[b,j,g,:],   g = h / (n_q_heads / n_kv_heads)
+ * with j <= i only when causal == 1 (a query sees itself and earlier tokens) and all j < T when
+ * causal == 0.  Grouped-query attention (n_kv_heads < n_q_heads, Section 5.2.5) is read in place:
+ * consecutive query heads share a key/value head, nothing is expanded in memory.
+ * Q, O : bf16 [batch][T][n_q_heads][head_dim];  K, V : bf16 [batch][T][n_kv_heads][head_dim].
+ * Each tensor comes with three ELEMENT strides {batch entry, token, head} (host arrays of 3);
+ * the head_dim elements of one (batch, token, head) row are contiguous.  This takes the output
+ * of a fused QKV projection as it lies in memory: for rows of [q heads | k heads | v heads],
+ * pass Q = base, K = base + n_q_heads*head_dim, V = K + n_kv_heads*head_dim, token stride =
+ * (n_q_heads + 2 n_kv_heads) * head_dim, head stride = head_dim.
+ * head_dim must be 64 or 128 (else FACT_ERR_UNSUPPORTED).  Q, K, V: 16-byte aligned, strides
+ * multiples of 8, token stride >= head_dim, (T + 512) * token stride < 2^30; O: 8-byte aligned,
+ * strides multiples of 4.  n_q_heads must be a multiple of n_kv_heads.
+ * scale: the softmax scale; <= 0 selects 1 / sqrt(head_dim).
+ * Arithmetic: scores and softmax in fp32 (base-2 exponentials), probabilities rounded to bf16
+ * for the second contraction, fp32 accumulation, one rounding to bf16 at the store.
+ * O must not overlap Q, K or V.
+ */
+int fact_attention(int64_t batch, int64_t T, int64_t n_q_heads, int64_t n_kv_heads, int64_t head_dim,
+                   const void *Q, const int64_t *q_strides, const void *K, const int64_t *k_strides,
+                   const void *V, const int64_t *v_strides, void *O, const int64_t *o_strides,
+                   int causal, float scale, void *stream);
+
 /* ---- tile configurations: the auto-tuning surface (Section 4.2 Action 5) ---------------- */
 
 /* Number of compiled tile configurations; ids are 0 .. fact_num_configs()-1. */

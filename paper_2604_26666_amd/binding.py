@@ -69,6 +69,10 @@ def lib():
         L.fact_block_mlp_workspace_bytes.restype = _size
         L.fact_gemm_ex.argtypes = [_i64, _i64, _i64, _i64, _ptr, _i64, _i64, _ptr, _i64, _i64, _int,
                                    _ptr, _i64, _i64, ep, _int, _int, _int, _ptr, _size, _ptr]
+        i64p = ctypes.POINTER(_i64)
+        L.fact_attention.argtypes = [_i64, _i64, _i64, _i64, _i64, _ptr, i64p, _ptr, i64p, _ptr, i64p, _ptr, i64p,
+                                     _int, ctypes.c_float, _ptr]
+        L.fact_attention.restype = _int
         L.fact_num_configs.argtypes = []
         ip = ctypes.POINTER(_int)
         L.fact_config_info.argtypes = [_int, ip, ip, ip, ip, ip]
@@ -146,6 +150,14 @@ def fact_gemm_ex(batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, trans_b, C,
     return lib().fact_gemm_ex(batch, M, N, K, _addr(A), lda, stride_a, _addr(B), ldb, stride_b, int(trans_b),
                               _addr(C), ldc, stride_c, _ep(ep), int(config_id), int(split_k), int(group_m),
                               _addr(ws), int(ws_bytes), _stream(stream))
+
+
+def fact_attention(batch, T, n_q_heads, n_kv_heads, head_dim, Q, q_strides, K, k_strides, V, v_strides,
+                   O, o_strides, causal=1, scale=0.0, stream=None):
+    """Strides are sequences of three element strides (batch entry, token, head)."""
+    arr = lambda s: (_i64 * 3)(*[int(x) for x in s])
+    return lib().fact_attention(batch, T, n_q_heads, n_kv_heads, head_dim, _addr(Q), arr(q_strides), _addr(K), arr(k_strides),
+                                _addr(V), arr(v_strides), _addr(O), arr(o_strides), int(causal), float(scale), _stream(stream))
 
 
 def fact_num_configs():

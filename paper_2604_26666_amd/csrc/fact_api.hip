@@ -30,6 +30,7 @@ static int hip_fail(hipError_t e, const char *what)
     std::snprintf(g_last_error, sizeof g_last_error, "%s: %s", what, hipGetErrorString(e));
     return FACT_ERR_HIP;
 }
+int record_hip_failure(hipError_t e, const char *what) { return hip_fail(e, what); }    // for the other translation units
 
 // ---- the per-shape table (filled by the on-device sweep) and the model behind it -----------
 

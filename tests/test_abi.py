@@ -95,10 +95,10 @@ def test_select_config_host_logic():
               (1, 2048, 4096, 14336, 1, 0), (1, 512, 512, 512, 0, 0)]
     for s in shapes:
         rc, cfg, split = fact.fact_select_config(*s)
-        assert rc == 0 and 0 <= cfg < n and split >= 1, s
+        assert rc == 0 and 0 <= cfg < n and (split >= 1 or split <= -2), s      # -g: tail split of g K ranges
         if s[5] == fact.ACT_SILU_GATE:
             bm, bn, wm, wn, _ = fact.fact_config_info(cfg)
-            assert (bn // wn // 32) % 2 == 0       # gate and up tiles pair up inside a wave
+            assert (bn // wn // 16) % 2 == 0       # gate and up tiles pair up inside a wave
     # large K with few output tiles is split; a big square problem is not
     assert fact.fact_select_config(1, 256, 256, 131072, 0, 0)[2] > 1
     assert fact.fact_select_config(1, 8192, 8192, 8192, 0, 0)[2] == 1
