@@ -59,15 +59,16 @@ extern "C" int fact_attention(int64_t batch, int64_t T, int64_t n_q_heads, int64
         if (((uintptr_t)ptr[i] & 15u) || (sb & 7) || (st & 7) || (sh & 7)) return FACT_ERR_ALIGN;
     }
     if (o_strides[1] < head_dim || o_strides[0] < 0 || o_strides[2] < 0) return FACT_ERR_DIM;
+    if (o_strides[1] > 0x7FFFFFFF) return FACT_ERR_UNSUPPORTED;
     if (((uintptr_t)O & 7u) || (o_strides[0] & 3) || (o_strides[1] & 3) || (o_strides[2] & 3)) return FACT_ERR_ALIGN;
     if (batch * n_q_heads * ((T + 127) / 128) > 0x7FFFFFFF || T > 0x7FFFFFFF - 1024) return FACT_ERR_UNSUPPORTED;
 
     AttnArgs a;
     a.Q = (const __bf16 *)Q; a.K = (const __bf16 *)K; a.V = (const __bf16 *)V; a.O = (__bf16 *)O;
-    a.q_sb = q_strides[0]; a.q_st = q_strides[1]; a.q_sh = q_strides[2];
-    a.k_sb = k_strides[0]; a.k_st = k_strides[1]; a.k_sh = k_strides[2];
-    a.v_sb = v_strides[0]; a.v_st = v_strides[1]; a.v_sh = v_strides[2];
-    a.o_sb = o_strides[0]; a.o_st = o_strides[1]; a.o_sh = o_strides[2];
+    a.q_sb = q_strides[0]; a.q_st = (int)q_strides[1]; a.q_sh = q_strides[2];
+    a.k_sb = k_strides[0]; a.k_st = (int)k_strides[1]; a.k_sh = k_strides[2];
+    a.v_sb = v_strides[0]; a.v_st = (int)v_strides[1]; a.v_sh = v_strides[2];
+    a.o_sb = o_strides[0]; a.o_st = (int)o_strides[1]; a.o_sh = o_strides[2];
     a.B = (int)batch; a.T = (int)T; a.Hq = (int)n_q_heads; a.Hkv = (int)n_kv_heads;
     a.causal = causal;
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)head_dim);

@@ -53,7 +53,8 @@ struct AttnArgs {
     const __bf16 *Q, *K, *V;
     __bf16 *O;
     // element strides: batch entry, token, head (the head_dim elements of a row are contiguous)
-    int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh, v_sb, v_st, v_sh, o_sb, o_st, o_sh;
+    int64_t q_sb, k_sb, v_sb, o_sb, q_sh, k_sh, v_sh, o_sh;
+    int q_st, k_st, v_st, o_st;
     int B, T, Hq, Hkv;
     int causal;
     float scale_log2;       // softmax scale * log2(e)
@@ -77,6 +78,19 @@ __device__ __forceinline__ f32x4_t mfma_16x16x32(bf16x8_t a, bf16x8_t b, f32x4_t
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+// max over the four lanes lane, lane ^ 16, lane ^ 32, lane ^ 48, in every lane, without LDS:
+// v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second;
+// applied to two copies of x, the two results hold x and its partner's x in every lane.
+__device__ __forceinline__ float max_over_lane_quads(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = fmaxf(__builtin_bit_cast(float, (uint32_t)a[0]), __builtin_bit_cast(float, (uint32_t)a[1]));
+    const uint32_t w = __builtin_bit_cast(uint32_t, x);
+    auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)b[0]), __builtin_bit_cast(float, (uint32_t)b[1]));
+}
 // 16 bytes per lane from global memory straight into LDS at lds + 16 * lane (lds uniform over the wave)
 __device__ __forceinline__ void load_to_lds_16(__amdgpu_buffer_rsrc_t rsrc, char *lds, uint32_t voffset, uint32_t soffset)
 {
@@ -151,28 +165,38 @@ attn_fwd_kernel(const AttnArgs p)
     const __amdgpu_buffer_rsrc_t rsrc_k = make_rsrc(p.K + (int64_t)b * p.k_sb + (int64_t)hk * p.k_sh, p.k_st);
     const __amdgpu_buffer_rsrc_t rsrc_v = make_rsrc(p.V + (int64_t)b * p.v_sb + (int64_t)hk * p.v_sh, p.v_st);
 
-    // ---- K / V block loads: wave w fills 1 KB pieces w*L .. w*L+L-1 of each tile -------------
+    // ---- K / V block loads: wave w fills the 1 KB pieces w, w + NW, ... of each tile -------------
     // Lane l of a wave-wide load writes 16 bytes at piece + 16 l, i.e. row l / CPR of the piece,
     // chunk position l % CPR: it fetches the chunk that belongs there under the swizzle.  Rows at
-    // or beyond T lie outside the descriptor's range and arrive as zeros.
-    uint32_t k_off[L], v_off[L];
+    // or beyond T lie outside the descriptor's range and arrive as zeros.  A wave's pieces are
+    // NW * RPL rows apart, a multiple of the swizzles' periods except for 128-wide K rows with two
+    // waves (period 16, step 8): so one per-lane offset serves all of a wave's loads (two there),
+    // the piece and the key block go into the scalar offset.
+    // LDS: two K slots then two V slots; block j uses slot j % 2 of each.
+    constexpr int KALT = (D == 128 && NW == 2) ? 2 : 1;
+    uint32_t k_off[KALT], v_off;
+    {
+        const int row = wave * RPL + lane / CPR, pos = lane % CPR;
 #pragma unroll
-    for (int t = 0; t < L; ++t) {
-        const int row = (wave * L + t) * RPL + lane / CPR, pos = lane % CPR;
-        k_off[t] = (uint32_t)(row * (int)p.k_st * 2 + ((pos ^ swz_keys<D>(row)) << 4));
-        v_off[t] = (uint32_t)(row * (int)p.v_st * 2 + ((pos ^ swz_vals<D>(row)) << 4));
+        for (int a = 0; a < KALT; ++a)
+            k_off[a] = (uint32_t)(row * p.k_st * 2 + ((pos ^ swz_keys<D>(row + a * NW * RPL)) << 4));
+        v_off = (uint32_t)(row * p.v_st * 2 + ((pos ^ swz_vals<D>(row)) << 4));
     }
-    const uint32_t k_blk = (uint32_t)(BKV * (int)p.k_st * 2), v_blk = (uint32_t)(BKV * (int)p.v_st * 2);
-    auto issue_loads = [&](int j, int stage) __attribute__((always_inline)) {
-        char *sk = smem + stage * STAGE_BYTES + wave * L * 1024;
+    const uint32_t k_blk = (uint32_t)(BKV * p.k_st * 2), v_blk = (uint32_t)(BKV * p.v_st * 2);
+    const uint32_t k_piece = (uint32_t)(NW * RPL * p.k_st * 2), v_piece = (uint32_t)(NW * RPL * p.v_st * 2);
+    auto load_k = [&](int j) __attribute__((always_inline)) {
+        char *dst = smem + (j & 1) * TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int t = 0; t < L; ++t)
-            load_to_lds_16(rsrc_k, sk + t * 1024, k_off[t], j * k_blk);
-#pragma unroll
-        for (int t = 0; t < L; ++t)
-            load_to_lds_16(rsrc_v, sk + TILE_BYTES + t * 1024, v_off[t], j * v_blk);
+        for (int t = 0; t < L; ++t) load_to_lds_16(rsrc_k, dst + t * NW * 1024, k_off[t % KALT], j * k_blk + t * k_piece);
     };
-    issue_loads(0, 0);
+    auto load_v = [&](int j) __attribute__((always_inline)) {
+        char *dst = smem + (2 + (j & 1)) * TILE_BYTES + wave * 1024;
+#pragma unroll
+        for (int t = 0; t < L; ++t) load_to_lds_16(rsrc_v, dst + t * NW * 1024, v_off, j * v_blk + t * v_piece);
+    };
+    load_k(0);
+    load_v(0);
+    if (nb > 1) load_k(1);
 
     // ---- Q^T fragments: query 16 qt + r16 of the wave, d = 32 kb + 8 q4 .. + 7 ----------------
     bf16x8_t qf[QT][KB];
@@ -180,143 +204,238 @@ attn_fwd_kernel(const AttnArgs p)
     for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            const uint32_t off = (uint32_t)(((q0w + 16 * qt + r16) * (int)p.q_st + 32 * kb + 8 * q4) * 2);
+            const uint32_t off = (uint32_t)(((q0w + 16 * qt + r16) * p.q_st + 32 * kb + 8 * q4) * 2);
             qf[qt][kb] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_q, off, 0, 0));
         }
 
-    // ---- LDS fragment addresses ---------------------------------------------------------------
-    // K tile kt, group kb: row 16 kt + r16, chunk 4 kb + q4 (the swizzle depends on r16 only).
-    uint32_t k_addr[KB];
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-        k_addr[kb] = (uint32_t)(r16 * ROWB + (((4 * kb + q4) ^ swz_keys<D>(r16)) << 4));
+    // ---- LDS fragment addresses (relative to the slot) -----------------------------------------
+    // K tile kt, group kb: row 16 kt + r16, chunk (4 kb + q4) ^ swizzle(r16): kb sits in address bits
+    // 6 and up, which the XOR leaves to it, so group kb is the group-0 address ^ (kb << 6).
+    const uint32_t k_addr = (uint32_t)(r16 * ROWB + ((q4 ^ swz_keys<D>(r16)) << 4));
     // V^T tile dt, 32-key group u, half h: a transposing read hands lane i of a 16-lane group
     // column (= d) i of the 4 rows (= keys) whose addresses lanes 4 jj + cc supply for columns
-    // 4 cc .. 4 cc + 3.  Keys 32 u + 16 h + 4 q4 + jj: the permutation P^T comes in.
+    // 4 cc .. 4 cc + 3.  Keys 32 u + 16 h + 4 q4 + jj: the permutation P^T comes in.  Tile dt is the
+    // tile-0 address ^ (dt << 5) (chunk 2 dt + cc / 2, swizzled by XOR; slots are 256-byte aligned).
     const int jj = (lane >> 2) & 3, cc = lane & 3;
-    uint32_t v_addr[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-        v_addr[dt] = (uint32_t)(TILE_BYTES + (4 * q4 + jj) * ROWB + (((2 * dt + (cc >> 1)) ^ swz_vals<D>(4 * q4 + jj)) << 4) + (cc & 1) * 8);
+    const uint32_t v_addr = (uint32_t)((4 * q4 + jj) * ROWB + (((cc >> 1) ^ swz_vals<D>(4 * q4 + jj)) << 4) + (cc & 1) * 8);
+    const uint32_t lds0 = (uint32_t)(size_t)FACT_ATTN_LDS_PTR(smem);
 
+    // ---- state ------------------------------------------------------------------------------------
+    // The MFMAs are inline asm so that the register classes are fixed: O^T accumulators and the Q^T
+    // fragments live in the accumulation registers for the whole kernel, S^T goes straight to
+    // ordinary registers where the softmax works on it (through the builtin the compiler moved
+    // ~900 registers per key block between the two files).  The compiler does not know these are
+    // MFMAs, so the wait states between an MFMA and a vector-ALU read of its result are kept by
+    // construction (see the s_nop's) instead.
+    f32x4_t S[2][KT][QT];            // S^T of the block being consumed and of the one after it
     f32x4_t o[DT][QT];
+    u32x4_t pf[UB][QT];              // P^T, bf16 pairs, in MFMA B-operand order
+    bf16x8_t kf[4];                  // K fragments: ring, read two fragments ahead of their MFMAs
+    s16x4_t vlo[2][UB], vhi[2][UB];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) o[dt][qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m[QT], l[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) { m[qt] = -__builtin_inff(); l[qt] = 0.f; }
-    const float c = p.scale_log2;
-
-    for (int j = 0; j < nb; ++j) {
-        // the loads of block j (issued one iteration ago) have landed, for every wave; every wave
-        // is done reading the other stage, which block j+1 now overwrites
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (j + 1 < nb) issue_loads(j + 1, (j + 1) & 1);
-        if (j >= nbw) continue;                                  // nothing this wave's queries may see
-        const char *st = smem + (j & 1) * STAGE_BYTES;
-        const int j0 = j * BKV;
-
-        // ---- S^T = K Q^T ----------------------------------------------------------------------
-        f32x4_t s[KT][QT];
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) s[kt][qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                const bf16x8_t kf = *(const bf16x8_t *)(st + k_addr[kb] + kt * 16 * ROWB);
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    s[kt][qt] = mfma_16x16x32(kf, qf[qt][kb], s[kt][qt]);
-            }
-
-        // ---- mask: lane holds keys j0 + 16 kt + 4 q4 + r of query q0w + 16 qt + r16 -------------
-        const bool need_mask = p.causal ? (j0 + BKV - 1 > q0w) : (j0 + BKV > T);
-        if (need_mask) {
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                const int last = p.causal ? q0w + 16 * qt + r16 : T - 1;     // last key this query sees
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (j0 + 16 * kt + 4 * q4 + r > last) s[kt][qt][r] = -__builtin_inff();
-            }
-        }
-
-        // ---- online softmax, per query --------------------------------------------------------
-        bf16x8_t pf[UB][QT];
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
-            float mx = s[0][qt][0];
+            o[dt][qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            asm volatile("" : "+a"(o[dt][qt]));
+        }
+    float m[QT], l[QT], mx[QT], mc[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) { m[qt] = -__builtin_inff(); l[qt] = 0.f; mx[qt] = 0.f; mc[qt] = 0.f; }
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) pf[u][qt] = u32x4_t{0u, 0u, 0u, 0u};
+    const float c = p.scale_log2;
+
+    constexpr int NS = KT * KB * QT;                 // MFMAs of one S^T block
+    constexpr int EPM = KT * QT * 4 / NS;             // softmax elements worked off behind each of them
+    constexpr int NF = KT * KB;                      // K fragments of a block
+
+    // (lambdas that hold inline asm take plain integers, constant after inlining: asm operands
+    // inside a generic lambda cannot name the enclosing function's variables)
+    auto read_k = [&](int slot_off, int f) __attribute__((always_inline)) {
+        const int kt = f / KB, kb = f % KB;
+        kf[f & 3] = *(const bf16x8_t *)(smem + slot_off + (k_addr ^ (kb << 6)) + kt * 16 * ROWB);
+    };
+    // MFMA number i of S^T(block) into S[tb]: fragment f = i / QT (key tile kt, 32 d's kb), query tile i % QT
+    auto s_mfma = [&](int tb, int slot_off, int i) __attribute__((always_inline)) {
+        const int f = i / QT, qt = i % QT, kt = f / KB, kb = f % KB;
+        if (qt == 0 && f + 2 < NF) read_k(slot_off, f + 2);
+        // The softmax values worked off behind the previous MFMA (probabilities in place in the
+        // other S buffer, the row sum, the packed pairs) ride along as dummy in/out operands: that
+        // is what keeps the compiler from moving the softmax out from between the MFMAs.
+        const int ep = i > 0 ? (i - 1) * EPM : 0, pq = ep / (KT * 4), pk = (ep / 4) % KT;
+        if (kb == 0)
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %4, %5, 0"
+                         : "=&v"(S[tb][kt][qt]), "+v"(S[tb ^ 1][pk][pq]), "+v"(l[pq]), "+v"(pf[pk / 2][pq])
+                         : "v"(kf[f & 3]), "a"(qf[qt][kb]));
+        else
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %4, %5, %0"
+                         : "+v"(S[tb][kt][qt]), "+v"(S[tb ^ 1][pk][pq]), "+v"(l[pq]), "+v"(pf[pk / 2][pq])
+                         : "v"(kf[f & 3]), "a"(qf[qt][kb]));
+    };
+    // element e of the softmax of S[sb]: p = 2^(s c - m c); row sum; pack to bf16 pairs
+    auto softmax_elem = [&](auto sb_, auto e_) __attribute__((always_inline)) {
+        constexpr int sb = decltype(sb_)::value, e = decltype(e_)::value;
+        constexpr int qt = e / (KT * 4), kt = (e / 4) % KT, r = e % 4;
+        const float ev = exp2_fast(__builtin_fmaf(S[sb][kt][qt][r], c, -mc[qt]));
+        S[sb][kt][qt][r] = ev;
+        l[qt] += ev;
+        if constexpr (r & 1) {
+            const f32x2_t pr = {S[sb][kt][qt][r - 1], ev};
+            pf[kt / 2][qt][2 * (kt & 1) + r / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
+        }
+    };
+    auto mask_block = [&](auto sb_, int j) __attribute__((always_inline)) {
+        constexpr int sb = decltype(sb_)::value;
+        const int j0 = j * BKV;
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            const int last = p.causal ? q0w + 16 * qt + r16 : T - 1;         // last key this query sees
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[kt][qt][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m[qt], mx);
-            const float alpha = exp2_fast((m[qt] - m_new) * c);
-            const float mc = m_new * c;
-            m[qt] = m_new;
-            float sum = 0.f;
+                for (int r = 0; r < 4; ++r)
+                    if (j0 + 16 * kt + 4 * q4 + r > last) S[sb][kt][qt][r] = -__builtin_inff();
+        }
+    };
+    auto needs_mask = [&](int j) { return p.causal ? (j * BKV + BKV - 1 > q0w) : (j * BKV + BKV > T); };
+    // largest score of query tile qt in S[sb], over the four lanes that share a query
+    auto max_of = [&](auto sb_, auto qt_) __attribute__((always_inline)) {
+        constexpr int sb = decltype(sb_)::value, qt = decltype(qt_)::value;
+        float t = S[sb][0][qt][0];
 #pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
+        for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float e = exp2_fast(__builtin_fmaf(s[kt][qt][r], c, -mc));
-                    s[kt][qt][r] = e;
-                    sum += e;
+            for (int r = 0; r < 4; ++r) t = fmaxf(t, S[sb][kt][qt][r]);
+        mx[qt] = max_over_lane_quads(t);
+    };
+    // transposing reads of V^T tile dt (both 32-key groups) into fragment set `set`
+    auto read_v = [&](int set, uint32_t vbase, int dt) __attribute__((always_inline)) {
+        static_assert(UB == 2, "two 32-key groups");
+        const uint32_t va = (vbase + v_addr) ^ (uint32_t)(dt << 5);
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[set][0]) : "v"(va), "n"(0));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[set][0]) : "v"(va), "n"(16 * ROWB));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[set][1]) : "v"(va), "n"(32 * ROWB));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[set][1]) : "v"(va), "n"(48 * ROWB));
+    };
+    auto wait_v = [&](int set) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vlo[set][0]), "+v"(vhi[set][0]), "+v"(vlo[set][1]), "+v"(vhi[set][1]));
+    };
+    auto pv_mfma = [&](int set, int dt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(vlo[set][u], vhi[set][u], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)      // (the maximum found behind the previous tile rides along, as above)
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %2, %3, %0" : "+a"(o[dt][qt]), "+v"(mx[(dt + QT - 1) % QT]) : "v"(vf), "v"(pf[u][qt]));
+        }
+    };
+    auto nops = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); };
+
+    // One key block: softmax of S[PAR] (block j) while S[PAR ^ 1] (block j + 1) is being computed,
+    // then O^T += V_j^T P^T while the maxima of block j + 1 are found.
+    auto step = [&](auto par_, int j) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par_)::value;
+        typedef std::integral_constant<int, PAR> cur_t;
+        typedef std::integral_constant<int, PAR ^ 1> nxt_t;
+        // Loads issued one step ago (K of block j+1, V of block j) have landed, for every wave; every
+        // wave is done with K of block j and V of block j-1, whose slots the new loads overwrite.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (j + 2 < nb) load_k(j + 2);
+        if (j + 1 < nb) load_v(j + 1);
+        if (j >= nbw) return;                                    // nothing (more) this wave's queries may see
+
+        // m[qt] is the REFERENCE exponent of the query's running sums, not always its running
+        // maximum: it is raised (and the sums rescaled) only when a score exceeds it by more than
+        // 2^kSlack in the base-2 domain, so the probabilities handed to the second MFMA stay below
+        // 2^kSlack = 256 (harmless in bf16 and fp32) and the accumulators are left alone on most
+        // key blocks.  The branch is uniform over the wave.
+        constexpr float kSlack = 8.0f;
+        bool grow = false;
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) grow |= (mx[qt] - m[qt]) * c > kSlack;     // also true while m is still -inf
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            nops();                                              // the previous block's MFMAs have written O
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                const float m_new = fmaxf(m[qt], mx[qt]);
+                const float alpha = exp2_fast((m[qt] - m_new) * c);
+                m[qt] = m_new;
+                l[qt] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    asm volatile("" : "+a"(o[dt][qt]));           // (keeps the copy out of the registers inside this branch)
+                    o[dt][qt] *= alpha;
+                    asm volatile("" : "+a"(o[dt][qt]));           // back in the accumulation registers before the paths join
+                    __builtin_amdgcn_sched_barrier(0);            // one tile at a time: few registers in flight
                 }
-            l[qt] = l[qt] * alpha + sum;
+            }
+        }
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) o[dt][qt] *= alpha;
-#pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                u32x4_t w;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const f32x2_t a = {s[2 * u + h][qt][0], s[2 * u + h][qt][1]}, bq = {s[2 * u + h][qt][2], s[2 * u + h][qt][3]};
-                    w[2 * h] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2_t));
-                    w[2 * h + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(bq, bf16x2_t));
-                }
-                pf[u][qt] = __builtin_bit_cast(bf16x8_t, w);
+        for (int qt = 0; qt < QT; ++qt) mc[qt] = m[qt] * c;
+
+        // S^T of block j + 1, one softmax element of block j behind each MFMA.  On the wave's last
+        // block this still runs, on whatever the other K slot holds: the result is never used, and
+        // the softmax alone would take as long as the two together.
+        {
+            const int slot_off = ((j + 1) & 1) * TILE_BYTES;
+            read_k(slot_off, 0);
+            read_k(slot_off, 1);
+            unroll<NS>([&](auto i_) __attribute__((always_inline)) {
+                constexpr int i = decltype(i_)::value;
+                s_mfma(PAR ^ 1, slot_off, i);
+                unroll<EPM>([&](auto k_) __attribute__((always_inline)) {
+                    softmax_elem(cur_t{}, std::integral_constant<int, i * EPM + decltype(k_)::value>{});
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            if (needs_mask(j + 1)) {
+                nops();
+                mask_block(nxt_t{}, j + 1);
             }
         }
 
-        // ---- O^T += V^T P^T ---------------------------------------------------------------------
-        // Transposing reads through inline asm: the compiler would make each of them wait for the
-        // global->LDS loads in flight.  It does not track them, so the wait is explicit and takes
-        // the fragment registers as operands.
-        const uint32_t vb = (uint32_t)(size_t)FACT_ATTN_LDS_PTR(st);
+        const uint32_t vbase = lds0 + (2 + (j & 1)) * TILE_BYTES;
+        read_v(0, vbase, 0);
         unroll<DT>([&](auto dt_) __attribute__((always_inline)) {
             constexpr int dt = decltype(dt_)::value;
-            static_assert(UB == 2, "reads and operand list below");
-            const uint32_t va = vb + v_addr[dt];
-            s16x4_t lo0, hi0, lo1, hi1;
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo0) : "v"(va), "n"(0));
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi0) : "v"(va), "n"(16 * ROWB));
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo1) : "v"(va), "n"(32 * ROWB));
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi1) : "v"(va), "n"(48 * ROWB));
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo0), "+v"(hi0), "+v"(lo1), "+v"(hi1));
-            const s16x4_t lo[UB] = {lo0, lo1}, hi[UB] = {hi0, hi1};
-#pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo[u], hi[u], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    o[dt][qt] = mfma_16x16x32(vf, pf[u][qt], o[dt][qt]);
+            wait_v(dt & 1);
+            if constexpr (dt + 1 < DT) read_v((dt + 1) & 1, vbase, dt + 1);
+            pv_mfma(dt & 1, dt);
+            __builtin_amdgcn_sched_barrier(0);
+            // (by now the S^T MFMAs of this step are at least 8 MFMAs back: their results may be read)
+            if constexpr (dt < QT) {
+                max_of(nxt_t{}, dt_);
+                __builtin_amdgcn_sched_barrier(0);
             }
         });
+    };
+
+    // first block: S^T(0), its mask and maxima, nothing to overlap with yet
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (nbw > 0) {
+        read_k(0, 0);
+        read_k(0, 1);
+        unroll<NS>([&](auto i_) __attribute__((always_inline)) {
+            s_mfma(0, 0, decltype(i_)::value);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        nops();
+        if (needs_mask(0)) mask_block(std::integral_constant<int, 0>{}, 0);
+        unroll<QT>([&](auto qt_) __attribute__((always_inline)) { max_of(std::integral_constant<int, 0>{}, qt_); });
     }
+    for (int j = 0; j < nb; j += 2) {
+        step(std::integral_constant<int, 0>{}, j);
+        if (j + 1 < nb) step(std::integral_constant<int, 1>{}, j + 1);
+    }
+    if (nbw == 0) return;
+    nops();                                                      // the last MFMAs have written O
 
     // ---- normalise and store: lane holds d = 16 dt + 4 q4 .. + 3 of query q0w + 16 qt + r16 ------
-    if (nbw == 0) return;
     __bf16 *obase = p.O + (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh;
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
