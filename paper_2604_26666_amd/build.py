@@ -52,6 +52,78 @@ def resource_usage(text):
     return res
 
 
+_REG = re.compile(r"\b([va])(?:\[(\d+):(\d+)\]|(\d+))")
+
+
+def _regs(operand):
+    """Set of ('v'|'a', index) named by one assembly operand."""
+    out = set()
+    for m in _REG.finditer(operand):
+        kind = m.group(1)
+        if m.group(4) is not None:
+            out.add((kind, int(m.group(4))))
+        else:
+            out.update((kind, i) for i in range(int(m.group(2)), int(m.group(3)) + 1))
+    return out
+
+
+def check_asm_mfma_hazards(asm_text, kernel_filter="attn_fwd_kernel"):
+    """The attention kernel issues its MFMAs through inline asm, so the compiler keeps none of the
+    wait states the matrix pipe needs around them.  Two cases are checked in the generated code:
+    a vector-ALU instruction writing a register that one of the next two instructions, an asm
+    MFMA, reads as an operand (seen on the GPU: the MFMA used the register's old contents); and a
+    vector-ALU instruction reading an MFMA's result with fewer than 5 instructions or 20 s_nop
+    cycles in between.  Returns a list of findings (empty = fine)."""
+    findings = []
+    checked = 0
+    for m in re.finditer(r"^(_Z\w+):[^\n]*\n(.*?)^\s*s_endpgm", asm_text, re.S | re.M):
+        name, kern = m.group(1), m.group(2)
+        if kernel_filter not in name:
+            continue
+        checked += 1
+        insts = []                      # (text, is_asm_mfma, valu_dest_regs, src_regs)
+        in_asm = False
+        for line in kern.splitlines():
+            t = line.strip()
+            if t.startswith(";;#ASMSTART"):
+                in_asm = True
+                continue
+            if t.startswith(";;#ASMEND"):
+                in_asm = False
+                continue
+            if not t or t.startswith((";", ".", "//")) or t.endswith(":"):
+                continue
+            op, _, rest = t.partition(" ")
+            ops = [o.strip() for o in rest.split(",")]
+            is_mfma = op.startswith("v_mfma")
+            dest = _regs(ops[0]) if ops and op.startswith("v_") else set()
+            srcs = set().union(*[_regs(o) for o in ops[1:]]) if len(ops) > 1 else set()
+            nop_cycles = int(ops[0]) + 1 if op == "s_nop" and ops and ops[0].isdigit() else 0
+            insts.append((t, is_mfma and in_asm, dest, srcs, op, nop_cycles))
+        for i, (t, asm_mfma, dest, srcs, op, _) in enumerate(insts):
+            if asm_mfma:
+                for k in (1, 2):
+                    if i - k >= 0:
+                        pt, p_mfma, pdest, _, pop, _ = insts[i - k]
+                        if pop.startswith("v_") and not pop.startswith("v_mfma") and pdest & srcs:
+                            findings.append(f"{name}: '{pt}' writes an operand of '{t}' {k} instruction(s) before it")
+            elif op.startswith("v_") and not op.startswith("v_mfma"):
+                need = srcs | dest
+                cycles = 0
+                for k in range(1, 6):
+                    if i - k < 0:
+                        break
+                    pt, p_mfma, pdest, _, pop, pn = insts[i - k]
+                    if cycles >= 20:
+                        break
+                    if p_mfma and pdest & need:
+                        findings.append(f"{name}: '{t}' touches the result of '{pt}' {k} instruction(s) after it")
+                    cycles += pn
+    if checked == 0:
+        findings.append("no kernel matching '" + kernel_filter + "' found in the generated code: nothing was checked")
+    return findings
+
+
 def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     """extra_flags / lib / obj_dir exist for experiments (a variant library beside the product one)."""
     OBJ = obj_dir
@@ -85,7 +157,13 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     if bad and not os.environ.get("FACT_ALLOW_SPILLS"):
         raise RuntimeError("register spills in the main kernel (would break the untracked LDS reads): " +
                            "; ".join(f"{k}: {v}" for k, v in bad.items()))
-    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [u[0] for u in units])
+    # the attention kernel's inline-asm MFMAs: check the generated code for the wait-state cases
+    asm_path = os.path.join(obj_dir, "attention.s")
+    _run([HIPCC] + FLAGS + ["--cuda-device-only", "-S", os.path.join(CSRC, "attention.hip"), "-o", asm_path])
+    hazards = check_asm_mfma_hazards(open(asm_path).read())
+    if hazards:
+        raise RuntimeError("inline-asm MFMA hazards in the attention kernel:\n  " + "\n  ".join(hazards[:20]))
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + [u[0] for u in units])
     return LIB
 
 

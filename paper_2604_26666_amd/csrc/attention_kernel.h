@@ -60,6 +60,9 @@ struct AttnArgs {
     float scale_log2;       // softmax scale * log2(e)
     int q_blocks;           // ceil(T / BQ)
     int total;              // q_blocks * Hq * B work-groups
+#ifdef FACT_ATTN_DBG
+    long long *dbg;         // 8 counters per wave: cycles in total / waiting at the step top / S phase / PV phase, key blocks
+#endif
 };
 
 constexpr uint32_t kBufFlags = 0x00020000u;      // raw buffer descriptor word 3 (32-bit data format)
@@ -82,15 +85,19 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 // v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of
 // its second, v_permlane32_swap the upper half of the first with the lower half of the second;
 // applied to two copies of x, the two results hold x and its partner's x in every lane.
-__device__ __forceinline__ float max_over_lane_quads(float x)
+__device__ __forceinline__ float max_with_lane_xor16(float x)
 {
     const uint32_t u = __builtin_bit_cast(uint32_t, x);
     auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    x = fmaxf(__builtin_bit_cast(float, (uint32_t)a[0]), __builtin_bit_cast(float, (uint32_t)a[1]));
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)a[0]), __builtin_bit_cast(float, (uint32_t)a[1]));
+}
+__device__ __forceinline__ float max_with_lane_xor32(float x)
+{
     const uint32_t w = __builtin_bit_cast(uint32_t, x);
     auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
     return fmaxf(__builtin_bit_cast(float, (uint32_t)b[0]), __builtin_bit_cast(float, (uint32_t)b[1]));
 }
+__device__ __forceinline__ float max_over_lane_quads(float x) { return max_with_lane_xor32(max_with_lane_xor16(x)); }
 // 16 bytes per lane from global memory straight into LDS at lds + 16 * lane (lds uniform over the wave)
 __device__ __forceinline__ void load_to_lds_16(__amdgpu_buffer_rsrc_t rsrc, char *lds, uint32_t voffset, uint32_t soffset)
 {
@@ -184,15 +191,19 @@ attn_fwd_kernel(const AttnArgs p)
     }
     const uint32_t k_blk = (uint32_t)(BKV * p.k_st * 2), v_blk = (uint32_t)(BKV * p.v_st * 2);
     const uint32_t k_piece = (uint32_t)(NW * RPL * p.k_st * 2), v_piece = (uint32_t)(NW * RPL * p.v_st * 2);
+    auto load_k_piece = [&](int j, int t) __attribute__((always_inline)) {
+        load_to_lds_16(rsrc_k, smem + (j & 1) * TILE_BYTES + wave * 1024 + t * NW * 1024, k_off[t % KALT], j * k_blk + t * k_piece);
+    };
+    auto load_v_piece = [&](int j, int t) __attribute__((always_inline)) {
+        load_to_lds_16(rsrc_v, smem + (2 + (j & 1)) * TILE_BYTES + wave * 1024 + t * NW * 1024, v_off, j * v_blk + t * v_piece);
+    };
     auto load_k = [&](int j) __attribute__((always_inline)) {
-        char *dst = smem + (j & 1) * TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int t = 0; t < L; ++t) load_to_lds_16(rsrc_k, dst + t * NW * 1024, k_off[t % KALT], j * k_blk + t * k_piece);
+        for (int t = 0; t < L; ++t) load_k_piece(j, t);
     };
     auto load_v = [&](int j) __attribute__((always_inline)) {
-        char *dst = smem + (2 + (j & 1)) * TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int t = 0; t < L; ++t) load_to_lds_16(rsrc_v, dst + t * NW * 1024, v_off, j * v_blk + t * v_piece);
+        for (int t = 0; t < L; ++t) load_v_piece(j, t);
     };
     load_k(0);
     load_v(0);
@@ -231,7 +242,7 @@ attn_fwd_kernel(const AttnArgs p)
     f32x4_t o[DT][QT];
     u32x4_t pf[UB][QT];              // P^T, bf16 pairs, in MFMA B-operand order
     bf16x8_t kf[4];                  // K fragments: ring, read two fragments ahead of their MFMAs
-    s16x4_t vlo[2][UB], vhi[2][UB];
+    s16x4_t vlo[3][UB], vhi[3][UB];   // V^T fragments: ring of three tiles, read two tiles ahead of their MFMAs
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -239,18 +250,36 @@ attn_fwd_kernel(const AttnArgs p)
             o[dt][qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             asm volatile("" : "+a"(o[dt][qt]));
         }
-    float m[QT], l[QT], mx[QT], mc[QT];
+    f32x4_t lsum[QT];                // row sums of P, as a 17th..th MFMA tile: V^T extended by a tile of ones
+    float m[QT], mx[QT], mc[QT];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) { m[qt] = -__builtin_inff(); l[qt] = 0.f; mx[qt] = 0.f; mc[qt] = 0.f; }
+    for (int qt = 0; qt < QT; ++qt) {
+        m[qt] = -__builtin_inff(); mx[qt] = 0.f; mc[qt] = 0.f;
+        lsum[qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        asm volatile("" : "+a"(lsum[qt]));
+    }
+    // a V^T fragment of ones: with it as the A operand, every row of the result tile is the sum of P
+    // over the keys - the softmax denominator, from the same rounded probabilities the numerator
+    // uses, on the matrix pipe instead of 64 vector additions per key block, and already summed
+    // over the four lanes that share a query
+    // (kept in registers for good: written right before its MFMA - which the compiler, not knowing
+    // that the asm is an MFMA, did - the matrix pipe read the registers' previous contents)
+    u32x4_t ones_frag = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+    asm volatile("" : "+v"(ones_frag));
 #pragma unroll
     for (int u = 0; u < UB; ++u)
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) pf[u][qt] = u32x4_t{0u, 0u, 0u, 0u};
     const float c = p.scale_log2;
+#ifdef FACT_ATTN_DBG
+    long long dbg_wait = 0, dbg_s = 0, dbg_pv = 0, dbg_ld = 0, dbg_grow = 0;
+    const long long dbg_t0 = clock64();
+#endif
 
     constexpr int NS = KT * KB * QT;                 // MFMAs of one S^T block
     constexpr int EPM = KT * QT * 4 / NS;             // softmax elements worked off behind each of them
     constexpr int NF = KT * KB;                      // K fragments of a block
+    constexpr int NE = KT * QT * 4;                  // softmax elements per lane and block
 
     // (lambdas that hold inline asm take plain integers, constant after inlining: asm operands
     // inside a generic lambda cannot name the enclosing function's variables)
@@ -261,29 +290,50 @@ attn_fwd_kernel(const AttnArgs p)
     // MFMA number i of S^T(block) into S[tb]: fragment f = i / QT (key tile kt, 32 d's kb), query tile i % QT
     auto s_mfma = [&](int tb, int slot_off, int i) __attribute__((always_inline)) {
         const int f = i / QT, qt = i % QT, kt = f / KB, kb = f % KB;
+#ifndef FACT_ATTN_DBG_NOKREAD
         if (qt == 0 && f + 2 < NF) read_k(slot_off, f + 2);
-        // The softmax values worked off behind the previous MFMA (probabilities in place in the
-        // other S buffer, the row sum, the packed pairs) ride along as dummy in/out operands: that
-        // is what keeps the compiler from moving the softmax out from between the MFMAs.
-        const int ep = i > 0 ? (i - 1) * EPM : 0, pq = ep / (KT * 4), pk = (ep / 4) % KT;
+#endif
+        // The softmax values worked on behind the previous MFMA (the other S buffer's registers in
+        // their three stages, the row sum, the packed pairs) ride along as dummy operands:
+        // that is what keeps the compiler from moving the softmax out from between the MFMAs.
+        const int e1 = (i + 1) * EPM < NE ? (i + 1) * EPM : NE - 1;      // an element stage 1 touched in slot i - 1
+        const int e3 = i > 0 ? (i - 1) * EPM : 0;                        // an element stage 3 touched in slot i - 1
+        const int q1 = e1 / (KT * 4), k1 = (e1 / 4) % KT, q3 = e3 / (KT * 4), k3 = (e3 / 4) % KT;
+        // (inputs only: as outputs they would make the compiler put a wait state behind every MFMA,
+        // which costs this wave an issue slot like any instruction)
         if (kb == 0)
-            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %4, %5, 0"
-                         : "=&v"(S[tb][kt][qt]), "+v"(S[tb ^ 1][pk][pq]), "+v"(l[pq]), "+v"(pf[pk / 2][pq])
-                         : "v"(kf[f & 3]), "a"(qf[qt][kb]));
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0"
+                         : "=&v"(S[tb][kt][qt])
+                         : "v"(kf[f & 3]), "a"(qf[qt][kb]), "v"(S[tb ^ 1][k1][q1]), "v"(S[tb ^ 1][k3][q3]), "v"(pf[k3 / 2][q3]));
         else
-            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %4, %5, %0"
-                         : "+v"(S[tb][kt][qt]), "+v"(S[tb ^ 1][pk][pq]), "+v"(l[pq]), "+v"(pf[pk / 2][pq])
-                         : "v"(kf[f & 3]), "a"(qf[qt][kb]));
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                         : "+v"(S[tb][kt][qt])
+                         : "v"(kf[f & 3]), "a"(qf[qt][kb]), "v"(S[tb ^ 1][k1][q1]), "v"(S[tb ^ 1][k3][q3]), "v"(pf[k3 / 2][q3]));
     };
-    // element e of the softmax of S[sb]: p = 2^(s c - m c); row sum; pack to bf16 pairs
-    auto softmax_elem = [&](auto sb_, auto e_) __attribute__((always_inline)) {
+    // Softmax of S[sb], element e (query tile e / 16, key tile, register), in three stages that run
+    // in consecutive MFMA slots for one element and side by side for three different elements: a
+    // single wave per SIMD has nothing else to cover the latency of a dependent vector instruction
+    // (measured: fma -> exp -> add back to back take 29 cycles, the same three independent 17).
+    //   stage 1: t = s c - m c      stage 2: p = 2^t      stage 3: row sum, pack pairs to bf16
+    auto sm1 = [&](auto sb_, auto e_) __attribute__((always_inline)) {
+        constexpr int sb = decltype(sb_)::value, e = decltype(e_)::value;
+        if constexpr (e < NE) {
+            constexpr int qt = e / (KT * 4), kt = (e / 4) % KT, r = e % 4;
+            S[sb][kt][qt][r] = __builtin_fmaf(S[sb][kt][qt][r], c, -mc[qt]);
+        }
+    };
+    auto sm2 = [&](auto sb_, auto e_) __attribute__((always_inline)) {
+        constexpr int sb = decltype(sb_)::value, e = decltype(e_)::value;
+        if constexpr (e < NE) {
+            constexpr int qt = e / (KT * 4), kt = (e / 4) % KT, r = e % 4;
+            S[sb][kt][qt][r] = exp2_fast(S[sb][kt][qt][r]);
+        }
+    };
+    auto sm3 = [&](auto sb_, auto e_) __attribute__((always_inline)) {
         constexpr int sb = decltype(sb_)::value, e = decltype(e_)::value;
         constexpr int qt = e / (KT * 4), kt = (e / 4) % KT, r = e % 4;
-        const float ev = exp2_fast(__builtin_fmaf(S[sb][kt][qt][r], c, -mc[qt]));
-        S[sb][kt][qt][r] = ev;
-        l[qt] += ev;
         if constexpr (r & 1) {
-            const f32x2_t pr = {S[sb][kt][qt][r - 1], ev};
+            const f32x2_t pr = {S[sb][kt][qt][r - 1], S[sb][kt][qt][r]};
             pf[kt / 2][qt][2 * (kt & 1) + r / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2_t));
         }
     };
@@ -298,6 +348,7 @@ attn_fwd_kernel(const AttnArgs p)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     if (j0 + 16 * kt + 4 * q4 + r > last) S[sb][kt][qt][r] = -__builtin_inff();
+            __builtin_amdgcn_sched_barrier(0);        // (16 compare masks at a time: all 64 at once spill scalar registers everywhere)
         }
     };
     auto needs_mask = [&](int j) { return p.causal ? (j * BKV + BKV - 1 > q0w) : (j * BKV + BKV > T); };
@@ -311,26 +362,53 @@ attn_fwd_kernel(const AttnArgs p)
             for (int r = 0; r < 4; ++r) t = fmaxf(t, S[sb][kt][qt][r]);
         mx[qt] = max_over_lane_quads(t);
     };
-    // transposing reads of V^T tile dt (both 32-key groups) into fragment set `set`
-    auto read_v = [&](int set, uint32_t vbase, int dt) __attribute__((always_inline)) {
+    // the same in pieces, to go between the MFMAs of the second contraction: piece p < KT folds in
+    // key tile p, pieces KT and KT + 1 exchange with the lanes that share the query
+    float mt = 0.f;
+    auto max_piece = [&](auto sb_, auto qt_, auto p_) __attribute__((always_inline)) {
+        constexpr int sb = decltype(sb_)::value, qt = decltype(qt_)::value, pc = decltype(p_)::value;
+        if constexpr (pc < KT) {
+            const f32x4_t x = S[sb][pc][qt];
+            if constexpr (pc == 0) mt = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+            else mt = fmaxf(fmaxf(mt, x[0]), fmaxf(fmaxf(x[1], x[2]), x[3]));
+        } else if constexpr (pc == KT) {
+            mt = max_with_lane_xor16(mt);
+        } else if constexpr (pc == KT + 1) {
+            mt = max_with_lane_xor32(mt);
+            mx[qt] = mt;
+        }
+    };
+    // transposing reads of V^T tile dt into fragment set `set`: 32-key group u (both 16-key halves)
+    auto read_v = [&](int set, uint32_t vbase, int dt, int u) __attribute__((always_inline)) {
         static_assert(UB == 2, "two 32-key groups");
         const uint32_t va = (vbase + v_addr) ^ (uint32_t)(dt << 5);
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[set][0]) : "v"(va), "n"(0));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[set][0]) : "v"(va), "n"(16 * ROWB));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[set][1]) : "v"(va), "n"(32 * ROWB));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[set][1]) : "v"(va), "n"(48 * ROWB));
+        if (u == 0) {
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[set][0]) : "v"(va), "n"(0));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[set][0]) : "v"(va), "n"(16 * ROWB));
+        } else {
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vlo[set][1]) : "v"(va), "n"(32 * ROWB));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vhi[set][1]) : "v"(va), "n"(48 * ROWB));
+        }
+    };
+    auto wait_v4 = [&](int set) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(vlo[set][0]), "+v"(vhi[set][0]), "+v"(vlo[set][1]), "+v"(vhi[set][1]));
     };
     auto wait_v = [&](int set) __attribute__((always_inline)) {
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vlo[set][0]), "+v"(vhi[set][0]), "+v"(vlo[set][1]), "+v"(vhi[set][1]));
     };
-    auto pv_mfma = [&](int set, int dt) __attribute__((always_inline)) {
+    // MFMA number mi of O^T tile dt: 32-key group mi / QT, query tile mi % QT (the running maximum
+    // of the piece worked off behind the previous MFMA rides along as a dummy operand, as above)
+    auto pv_mfma = [&](int set, int dt, int mi) __attribute__((always_inline)) {
+        const int u = mi / QT, qt = mi % QT;
+        const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(vlo[set][u], vhi[set][u], 0, 1, 2, 3, 4, 5, 6, 7));
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(o[dt][qt]) : "v"(vf), "v"(pf[u][qt]), "v"(mt), "v"(mx[(dt + QT - 1) % QT]));
+    };
+    auto sum_mfma = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < UB; ++u) {
-            const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(vlo[set][u], vhi[set][u], 0, 1, 2, 3, 4, 5, 6, 7));
+        for (int u = 0; u < UB; ++u)
 #pragma unroll
-            for (int qt = 0; qt < QT; ++qt)      // (the maximum found behind the previous tile rides along, as above)
-                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %2, %3, %0" : "+a"(o[dt][qt]), "+v"(mx[(dt + QT - 1) % QT]) : "v"(vf), "v"(pf[u][qt]));
-        }
+            for (int qt = 0; qt < QT; ++qt)
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(lsum[qt]) : "v"(ones_frag), "v"(pf[u][qt]));
     };
     auto nops = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); };
 
@@ -342,11 +420,22 @@ attn_fwd_kernel(const AttnArgs p)
         typedef std::integral_constant<int, PAR ^ 1> nxt_t;
         // Loads issued one step ago (K of block j+1, V of block j) have landed, for every wave; every
         // wave is done with K of block j and V of block j-1, whose slots the new loads overwrite.
+#ifdef FACT_ATTN_DBG
+        const long long d0 = clock64();
+#endif
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+#ifdef FACT_ATTN_DBG
+        const long long d1 = clock64();
+        dbg_wait += d1 - d0;
+#endif
         if (j + 2 < nb) load_k(j + 2);
         if (j + 1 < nb) load_v(j + 1);
         if (j >= nbw) return;                                    // nothing (more) this wave's queries may see
+#ifdef FACT_ATTN_DBG
+        const long long d1b = clock64();
+        dbg_ld += d1b - d1;
+#endif
 
         // m[qt] is the REFERENCE exponent of the query's running sums, not always its running
         // maximum: it is raised (and the sums rescaled) only when a score exceeds it by more than
@@ -364,7 +453,9 @@ attn_fwd_kernel(const AttnArgs p)
                 const float m_new = fmaxf(m[qt], mx[qt]);
                 const float alpha = exp2_fast((m[qt] - m_new) * c);
                 m[qt] = m_new;
-                l[qt] *= alpha;
+                asm volatile("" : "+a"(lsum[qt]));
+                lsum[qt] *= alpha;
+                asm volatile("" : "+a"(lsum[qt]));
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
                     asm volatile("" : "+a"(o[dt][qt]));           // (keeps the copy out of the registers inside this branch)
@@ -376,6 +467,10 @@ attn_fwd_kernel(const AttnArgs p)
         }
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) mc[qt] = m[qt] * c;
+#ifdef FACT_ATTN_DBG
+        const long long d1c = clock64();
+        dbg_grow += d1c - d1b;
+#endif
 
         // S^T of block j + 1, one softmax element of block j behind each MFMA.  On the wave's last
         // block this still runs, on whatever the other K slot holds: the result is never used, and
@@ -384,11 +479,24 @@ attn_fwd_kernel(const AttnArgs p)
             const int slot_off = ((j + 1) & 1) * TILE_BYTES;
             read_k(slot_off, 0);
             read_k(slot_off, 1);
+            unroll<EPM>([&](auto k_) __attribute__((always_inline)) {          // fill the softmax pipeline
+                constexpr int k = decltype(k_)::value;
+                sm1(cur_t{}, std::integral_constant<int, k>{});
+                sm1(cur_t{}, std::integral_constant<int, EPM + k>{});
+            });
+            unroll<EPM>([&](auto k_) __attribute__((always_inline)) { sm2(cur_t{}, k_); });
+            __builtin_amdgcn_sched_barrier(0);
             unroll<NS>([&](auto i_) __attribute__((always_inline)) {
                 constexpr int i = decltype(i_)::value;
                 s_mfma(PAR ^ 1, slot_off, i);
                 unroll<EPM>([&](auto k_) __attribute__((always_inline)) {
-                    softmax_elem(cur_t{}, std::integral_constant<int, i * EPM + decltype(k_)::value>{});
+                    constexpr int k = decltype(k_)::value;
+#ifndef FACT_ATTN_DBG_NOSM
+                    sm1(cur_t{}, std::integral_constant<int, (i + 2) * EPM + k>{});
+                    __builtin_amdgcn_sched_barrier(0);      // fma first: an exponential right behind the asm gets a wait state
+                    sm2(cur_t{}, std::integral_constant<int, (i + 1) * EPM + k>{});
+                    sm3(cur_t{}, std::integral_constant<int, i * EPM + k>{});
+#endif
                 });
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -397,21 +505,37 @@ attn_fwd_kernel(const AttnArgs p)
                 mask_block(nxt_t{}, j + 1);
             }
         }
+#ifdef FACT_ATTN_DBG
+        const long long d2 = clock64();
+        dbg_s += d2 - d1;
+#endif
 
         const uint32_t vbase = lds0 + (2 + (j & 1)) * TILE_BYTES;
-        read_v(0, vbase, 0);
+        read_v(0, vbase, 0, 0);
+        read_v(0, vbase, 0, 1);
+        read_v(1, vbase, 1, 0);
+        read_v(1, vbase, 1, 1);
         unroll<DT>([&](auto dt_) __attribute__((always_inline)) {
             constexpr int dt = decltype(dt_)::value;
-            wait_v(dt & 1);
-            if constexpr (dt + 1 < DT) read_v((dt + 1) & 1, vbase, dt + 1);
-            pv_mfma(dt & 1, dt);
-            __builtin_amdgcn_sched_barrier(0);
-            // (by now the S^T MFMAs of this step are at least 8 MFMAs back: their results may be read)
-            if constexpr (dt < QT) {
-                max_of(nxt_t{}, dt_);
+            // tile dt has arrived when at most the 4 reads of tile dt + 1 are still in flight
+            if constexpr (dt + 1 < DT) wait_v4(dt % 3); else wait_v(dt % 3);
+            // 2 QT MFMAs; behind each: half of the reads of tile dt + 2, or a piece of the maximum of
+            // query tile dt of block j + 1 (the S^T MFMAs of this step are >= 8 MFMAs back by then)
+            unroll<UB * QT>([&](auto mi_) __attribute__((always_inline)) {
+                constexpr int mi = decltype(mi_)::value;
+                pv_mfma(dt % 3, dt, mi);
+                if constexpr (mi < 2) {
+                    if constexpr (dt + 2 < DT) read_v((dt + 2) % 3, vbase, dt + 2, mi);
+                } else if constexpr (dt < QT && mi - 2 < KT + 2) {
+                    max_piece(nxt_t{}, dt_, std::integral_constant<int, mi - 2>{});
+                }
                 __builtin_amdgcn_sched_barrier(0);
-            }
+            });
         });
+        sum_mfma();
+#ifdef FACT_ATTN_DBG
+        dbg_pv += clock64() - d2;
+#endif
     };
 
     // first block: S^T(0), its mask and maxima, nothing to overlap with yet
@@ -432,17 +556,27 @@ attn_fwd_kernel(const AttnArgs p)
         step(std::integral_constant<int, 0>{}, j);
         if (j + 1 < nb) step(std::integral_constant<int, 1>{}, j + 1);
     }
+#ifdef FACT_ATTN_DBG
+    if (p.dbg && lane == 0) {
+        long long *d = p.dbg + ((int64_t)blockIdx.x * NW + wave) * 8;
+        d[0] = clock64() - dbg_t0; d[1] = dbg_wait; d[2] = dbg_s; d[3] = dbg_pv; d[4] = nbw; d[5] = nb; d[6] = dbg_ld; d[7] = dbg_grow;
+    }
+#endif
     if (nbw == 0) return;
     nops();                                                      // the last MFMAs have written O
+    // (new values for the compiler, so that it cannot read the registers before the wait states)
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        asm volatile("" : "+a"(lsum[qt]));
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) asm volatile("" : "+a"(o[dt][qt]));
+    }
 
     // ---- normalise and store: lane holds d = 16 dt + 4 q4 .. + 3 of query q0w + 16 qt + r16 ------
     __bf16 *obase = p.O + (int64_t)b * p.o_sb + (int64_t)hq * p.o_sh;
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        float lt = l[qt];
-        lt += __shfl_xor(lt, 16);
-        lt += __shfl_xor(lt, 32);
-        const float inv = 1.0f / lt;
+        const float inv = 1.0f / lsum[qt][0];
         const int query = q0w + 16 * qt + r16;
         if (query < T) {
             __bf16 *row = obase + (int64_t)query * p.o_st + 4 * q4;

@@ -1,0 +1,36 @@
+"""Host-side checks the build applies to the generated code (CPU only)."""
+from paper_2604_26666_amd import build
+
+KERNEL = """
+_ZN4fact4attn15attn_fwd_kernelILi128ELi4EEEvNS0_8AttnArgsE: ; @x
+\tv_add_f32_e32 v40, v1, v2
+{first}
+\t;;#ASMSTART
+\tv_mfma_f32_16x16x32_bf16 a[0:3], v[4:7], v[8:11], a[0:3]
+\t;;#ASMEND
+{second}
+\ts_endpgm
+"""
+
+
+def findings(first="\ts_nop 0", second="\ts_nop 0"):
+    return build.check_asm_mfma_hazards(KERNEL.format(first=first, second=second))
+
+
+def test_clean_code_has_no_findings():
+    assert findings("\tv_add_f32_e32 v20, v1, v2\n\tv_add_f32_e32 v21, v1, v2") == []
+
+
+def test_vector_write_right_before_an_asm_mfma_operand_is_found():
+    assert len(findings("\tv_mov_b32_e32 v5, 0")) == 1                       # one instruction before
+    assert len(findings("\tv_mov_b64_e32 v[10:11], v[0:1]\n\ts_nop 0")) == 1   # two before
+    assert findings("\tv_mov_b32_e32 v5, 0\n\ts_nop 0\n\ts_nop 0") == []     # three before: accepted
+
+
+def test_vector_read_of_a_fresh_mfma_result_is_found():
+    assert len(findings(second="\tv_accvgpr_read_b32 v30, a1")) == 1
+    assert findings(second="\ts_nop 15\n\ts_nop 15\n\tv_accvgpr_read_b32 v30, a1") == []
+
+
+def test_a_missing_kernel_is_reported():
+    assert build.check_asm_mfma_hazards("_ZN4fact11gemm_kernelE: ; @y\n\ts_endpgm\n") != []
