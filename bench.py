@@ -120,6 +120,7 @@ def main():
     if args.all:
         from paper_2604_26666_amd import workbench
         out["others"] = workbench.time_all(args.steps, args.warmup)
+        out["attention"] = workbench.time_attention(args.steps, args.warmup)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

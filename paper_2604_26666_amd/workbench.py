@@ -209,6 +209,81 @@ def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30):
         case.t = base
 
 
+class AttnCase:
+    """Causal attention on a packed QKV projection output, through fact_attention."""
+
+    def __init__(self, name, maker):
+        self.name, self.maker, self.t = name, maker, None
+
+    def alloc(self):
+        if self.t is None:
+            w = self.maker()
+            self.B, self.T, self.Hq, self.Hkv, self.D = w["batch"], w["tokens"], w["q_heads"], w["kv_heads"], w["head_dim"]
+            self.t = {"qkv": w["qkv"].cuda(),
+                      "O": torch.empty((self.B, self.T, self.Hq * self.D), dtype=torch.bfloat16, device="cuda")}
+        return self.t
+
+    def free(self):
+        self.t = None
+
+    @property
+    def flops(self):
+        """Multiply-adds of the unmasked half only: 2 contractions x 2 x D per (query, visible key) pair."""
+        return 4.0 * self.B * self.Hq * self.D * (self.T * (self.T + 1) / 2.0)
+
+    @property
+    def min_bytes(self):
+        return 2.0 * self.B * self.T * (self.Hq + 2 * self.Hkv) * self.D + 2.0 * self.B * self.T * self.Hq * self.D
+
+    def run(self):
+        t = self.alloc()
+        W = (self.Hq + 2 * self.Hkv) * self.D
+        st = (self.T * W, W, self.D)
+        base = t["qkv"].data_ptr()
+        return fact.fact_attention(self.B, self.T, self.Hq, self.Hkv, self.D, base, st, base + 2 * self.Hq * self.D, st,
+                                   base + 2 * (self.Hq + self.Hkv) * self.D, st, t["O"],
+                                   (self.T * self.Hq * self.D, self.Hq * self.D, self.D), 1, 0.0)
+
+
+def attention_cases():
+    import workloads as wl
+    return [AttnCase("att4.gpt_8x1024_12h64", lambda: wl.attention4()),
+            AttnCase("att5.llama_1x2048_32q8kv128", lambda: wl.attention5(1)),
+            AttnCase("att5.llama_16x2048_32q8kv128", lambda: wl.attention5(16))]
+
+
+def time_attention(steps=30, warmup=30):
+    out = {}
+    for c in attention_cases():
+        c.alloc()
+        if c.run() != 0:
+            out[c.name] = {"error": "refused"}
+            continue
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(4):
+            c.run()
+        b.record()
+        torch.cuda.synchronize()
+        est = max(a.elapsed_time(b) / 4, 1e-3)
+        w = min(max(warmup, int(20.0 / est) + 1), 2000)
+        n = min(max(steps, int(10.0 / est) + 1), 1000)
+        for _ in range(w):
+            c.run()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            c.run()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / n
+        r = report(c, ms)
+        r["flops_counted"] = "causal half: 4 B Hq D T(T+1)/2"
+        out[c.name] = r
+        c.free()
+    return out
+
+
 def report(case, ms):
     tf = case.flops / (ms * 1e-3) / 1e12
     gbs = case.min_bytes / (ms * 1e-3) / 1e9

@@ -127,3 +127,38 @@ def test_config5_llama_block():
     _, y2 = ref.block_mlp(c["X"], c["Wg"], c["Wu"], None, ref.ACT_SILU_GATE, c["Wd"], None, c["R"], rows=rows, H_bits=Hg)
     s = check.assert_close(Yg, y2, rows="full", what="config 5 Y stage-wise")
     assert s["bits_equal_frac"] > 0.97, s
+
+
+# ---- attention at the two block configurations' shapes ------------------------------------------
+
+def _attention_full(w, heads):
+    from oracle import attention as att
+    B, T, Hq, Hkv, D = w["batch"], w["tokens"], w["q_heads"], w["kv_heads"], w["head_dim"]
+    W = (Hq + 2 * Hkv) * D
+    dev = w["qkv"].cuda()
+    O = torch.empty((B, T, Hq * D), dtype=torch.bfloat16, device="cuda")
+    base = dev.data_ptr()
+    st = (T * W, W, D)
+    fact.binding.check(fact.fact_attention(B, T, Hq, Hkv, D, base, st, base + 2 * Hq * D, st, base + 2 * (Hq + Hkv) * D, st,
+                                           O, (T * Hq * D, Hq * D, D), 1, 0.0))
+    got = bits_of(O).reshape(B, T, Hq, D)
+    q, k, v = wl.split_qkv(w)
+    G = Hq // Hkv
+    worst = 0.0
+    for (b, h) in heads:                       # the oracle one (batch entry, query head) at a time
+        r = att.attention(q[b:b + 1, :, h:h + 1], k[b:b + 1, :, h // G:h // G + 1], v[b:b + 1, :, h // G:h // G + 1])
+        s = check.assert_close(np.ascontiguousarray(got[b, :, h]), r, what=f"attention batch {b} head {h}")
+        worst = max(worst, s["rel_frobenius"])
+    assert worst < 3e-3, worst
+    O2 = torch.empty_like(O)                   # same call again: identical bits
+    fact.binding.check(fact.fact_attention(B, T, Hq, Hkv, D, base, st, base + 2 * Hq * D, st, base + 2 * (Hq + Hkv) * D, st,
+                                           O2, (T * Hq * D, Hq * D, D), 1, 0.0))
+    assert torch.equal(O.view(torch.int16), O2.view(torch.int16))
+
+
+def test_attention_llama_shape_2048_tokens():
+    _attention_full(wl.attention5(1), [(0, h) for h in (0, 1, 3, 4, 13, 30, 31)])
+
+
+def test_attention_gpt_shape_8x1024():
+    _attention_full(wl.attention4(), [(0, 0), (0, 11), (3, 5), (7, 0), (7, 11)])

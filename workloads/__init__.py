@@ -114,3 +114,37 @@ def config5(tokens=2048, d=4096, dff=14336, q_heads=32, kv_heads=8, head_dim=128
         "Wd": normal((d, dff), 0.02, "c5.Wd"),
         "R": normal((tokens, d), 1.0, "c5.R"),
     }
+
+
+# ---- attention inputs of the two block configurations ---------------------------------------
+
+def attention_qkv(batch, tokens, q_heads, kv_heads, head_dim, std, name):
+    """A packed projection output [batch, tokens, (q_heads + 2 kv_heads) * head_dim]: per token the
+    query heads, then the key heads, then the value heads.  Entries ~ N(0, std): a stand-in with
+    the scale of X Wqkv^T for X ~ N(0,1) and weights ~ N(0, 0.02) (std = 0.02 sqrt(d_model))."""
+    width = (q_heads + 2 * kv_heads) * head_dim
+    return normal((batch, tokens, width), std, name)
+
+
+def attention4(batch=8, tokens=1024):
+    """GPT-small-shaped attention: 12 heads of 64 (d_model 768), batch x tokens = the 8192 tokens of
+    configuration 4."""
+    return {"qkv": attention_qkv(batch, tokens, 12, 12, 64, 0.02 * 768 ** 0.5, f"att4.qkv.{batch}.{tokens}"),
+            "batch": batch, "tokens": tokens, "q_heads": 12, "kv_heads": 12, "head_dim": 64}
+
+
+def attention5(batch=1, tokens=2048):
+    """Llama-3-8B-shaped attention (Section 5.2.5): 32 query / 8 key-value heads of 128; batch 1 is
+    configuration 5's 2048 tokens, batch 16 the block shape the paper measures."""
+    return {"qkv": attention_qkv(batch, tokens, 32, 8, 128, 0.02 * 4096 ** 0.5, f"att5.qkv.{batch}.{tokens}"),
+            "batch": batch, "tokens": tokens, "q_heads": 32, "kv_heads": 8, "head_dim": 128}
+
+
+def split_qkv(w):
+    """uint16 views (Q [B,T,Hq,D], K [B,T,Hkv,D], V [B,T,Hkv,D]) of a packed attention workload."""
+    b = bits(w["qkv"])
+    B, T, Hq, Hkv, D = w["batch"], w["tokens"], w["q_heads"], w["kv_heads"], w["head_dim"]
+    q = b[:, :, : Hq * D].reshape(B, T, Hq, D)
+    k = b[:, :, Hq * D: (Hq + Hkv) * D].reshape(B, T, Hkv, D)
+    v = b[:, :, (Hq + Hkv) * D:].reshape(B, T, Hkv, D)
+    return q, k, v
