@@ -161,7 +161,7 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     asm_path = os.path.join(obj_dir, "attention.s")
     _run([HIPCC] + FLAGS + ["--cuda-device-only", "-S", os.path.join(CSRC, "attention.hip"), "-o", asm_path])
     hazards = check_asm_mfma_hazards(open(asm_path).read())
-    if hazards:
+    if hazards and not os.environ.get("FACT_ALLOW_ASM_HAZARDS"):      # (override for timing experiments only)
         raise RuntimeError("inline-asm MFMA hazards in the attention kernel:\n  " + "\n  ".join(hazards[:20]))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + [u[0] for u in units])
     return LIB

@@ -191,11 +191,24 @@ attn_fwd_kernel(const AttnArgs p)
     }
     const uint32_t k_blk = (uint32_t)(BKV * p.k_st * 2), v_blk = (uint32_t)(BKV * p.v_st * 2);
     const uint32_t k_piece = (uint32_t)(NW * RPL * p.k_st * 2), v_piece = (uint32_t)(NW * RPL * p.v_st * 2);
+    // (block j >= nb does not exist: its loads still run, with a scalar offset beyond every descriptor's
+    // range, and bring zeros into a slot nobody reads - no branch around a load in the middle of the MFMAs)
+    constexpr uint32_t kBeyond = 0x80000000u;
+    // (per piece only one scalar addition for the offset and one for the LDS address: scalar
+    // instructions take issue slots of this wave like any others)
+    auto k_block_off = [&](int j) { return j < nb ? (uint32_t)j * k_blk : kBeyond; };
+    auto v_block_off = [&](int j) { return j < nb ? (uint32_t)j * v_blk : kBeyond; };
+    auto load_k_piece2 = [&](char *slot, uint32_t blk_off, int t) __attribute__((always_inline)) {
+        load_to_lds_16(rsrc_k, slot + t * NW * 1024, k_off[t % KALT], blk_off + t * k_piece);
+    };
+    auto load_v_piece2 = [&](char *slot, uint32_t blk_off, int t) __attribute__((always_inline)) {
+        load_to_lds_16(rsrc_v, slot + t * NW * 1024, v_off, blk_off + t * v_piece);
+    };
     auto load_k_piece = [&](int j, int t) __attribute__((always_inline)) {
-        load_to_lds_16(rsrc_k, smem + (j & 1) * TILE_BYTES + wave * 1024 + t * NW * 1024, k_off[t % KALT], j * k_blk + t * k_piece);
+        load_k_piece2(smem + (j & 1) * TILE_BYTES + wave * 1024, k_block_off(j), t);
     };
     auto load_v_piece = [&](int j, int t) __attribute__((always_inline)) {
-        load_to_lds_16(rsrc_v, smem + (2 + (j & 1)) * TILE_BYTES + wave * 1024 + t * NW * 1024, v_off, j * v_blk + t * v_piece);
+        load_v_piece2(smem + (2 + (j & 1)) * TILE_BYTES + wave * 1024, v_block_off(j), t);
     };
     auto load_k = [&](int j) __attribute__((always_inline)) {
 #pragma unroll
@@ -403,12 +416,9 @@ attn_fwd_kernel(const AttnArgs p)
         const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(vlo[set][u], vhi[set][u], 0, 1, 2, 3, 4, 5, 6, 7));
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(o[dt][qt]) : "v"(vf), "v"(pf[u][qt]), "v"(mt), "v"(mx[(dt + QT - 1) % QT]));
     };
-    auto sum_mfma = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int u = 0; u < UB; ++u)
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt)
-                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(lsum[qt]) : "v"(ones_frag), "v"(pf[u][qt]));
+    float gmax = __builtin_inff();
+    auto sum_mfma = [&](int u, int qt) __attribute__((always_inline)) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(lsum[qt]) : "v"(ones_frag), "v"(pf[u][qt]), "v"(gmax));
     };
     auto nops = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); };
 
@@ -429,9 +439,14 @@ attn_fwd_kernel(const AttnArgs p)
         const long long d1 = clock64();
         dbg_wait += d1 - d0;
 #endif
-        if (j + 2 < nb) load_k(j + 2);
-        if (j + 1 < nb) load_v(j + 1);
-        if (j >= nbw) return;                                    // nothing (more) this wave's queries may see
+        // The new loads: a wave with work issues them one by one between the MFMAs below (in a burst
+        // right here, 4 waves x 2 L loads queue up at the compute unit's address unit and every wave
+        // loses ~400 cycles of issue time).
+        if (j >= nbw) {                                          // nothing (more) this wave's queries may see
+            if (j + 2 < nb) load_k(j + 2);
+            if (j + 1 < nb) load_v(j + 1);
+            return;
+        }
 #ifdef FACT_ATTN_DBG
         const long long d1b = clock64();
         dbg_ld += d1b - d1;
@@ -443,10 +458,9 @@ attn_fwd_kernel(const AttnArgs p)
         // 2^kSlack = 256 (harmless in bf16 and fp32) and the accumulators are left alone on most
         // key blocks.  The branch is uniform over the wave.
         constexpr float kSlack = 8.0f;
-        bool grow = false;
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) grow |= (mx[qt] - m[qt]) * c > kSlack;     // also true while m is still -inf
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        // (gmax = largest (mx - m) c over the query tiles, found behind the previous step's last MFMAs;
+        // +inf before the first block)
+        if (__builtin_amdgcn_ballot_w64(gmax > kSlack) != 0) {
             nops();                                              // the previous block's MFMAs have written O
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) {
@@ -477,6 +491,8 @@ attn_fwd_kernel(const AttnArgs p)
         // the softmax alone would take as long as the two together.
         {
             const int slot_off = ((j + 1) & 1) * TILE_BYTES;
+            char *const k_dst = smem + (j & 1) * TILE_BYTES + wave * 1024, *const v_dst = smem + (2 + ((j + 1) & 1)) * TILE_BYTES + wave * 1024;
+            const uint32_t k_src = k_block_off(j + 2), v_src = v_block_off(j + 1);
             read_k(slot_off, 0);
             read_k(slot_off, 1);
             unroll<EPM>([&](auto k_) __attribute__((always_inline)) {          // fill the softmax pipeline
@@ -489,6 +505,11 @@ attn_fwd_kernel(const AttnArgs p)
             unroll<NS>([&](auto i_) __attribute__((always_inline)) {
                 constexpr int i = decltype(i_)::value;
                 s_mfma(PAR ^ 1, slot_off, i);
+                constexpr int LOAD_EVERY = NS / (2 * L);
+                if constexpr (i % LOAD_EVERY == LOAD_EVERY - 1) {
+                    constexpr int t = i / LOAD_EVERY;
+                    if constexpr (t < L) load_k_piece2(k_dst, k_src, t); else load_v_piece2(v_dst, v_src, t - L);
+                }
                 unroll<EPM>([&](auto k_) __attribute__((always_inline)) {
                     constexpr int k = decltype(k_)::value;
 #ifndef FACT_ATTN_DBG_NOSM
@@ -532,7 +553,16 @@ attn_fwd_kernel(const AttnArgs p)
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
-        sum_mfma();
+        // the row-sum tile; behind its first MFMAs: how far the new maxima exceed the reference
+        unroll<UB * QT>([&](auto mi_) __attribute__((always_inline)) {
+            constexpr int mi = decltype(mi_)::value;
+            sum_mfma(mi / QT, mi % QT);
+            if constexpr (mi < QT) {
+                const float g = (mx[mi] - m[mi]) * c;
+                gmax = mi == 0 ? g : fmaxf(gmax, g);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
 #ifdef FACT_ATTN_DBG
         dbg_pv += clock64() - d2;
 #endif
