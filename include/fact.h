@@ -1,5 +1,6 @@
 /*
- * fact.h - C ABI of the MI355X (gfx950) bf16 GEMM + fused-epilogue library.
+ * fact.h - C ABI of the MI355X (gfx950) bf16 GEMM + fused-epilogue library
+ *          (with the transformer block's fused attention, fact_attention).
  *
  * The library computes what the paper's synthesized kernels compute: dense
  * GEMMs (square, batched, large-K; paper Section 5.1 "Benchmark problems") and
