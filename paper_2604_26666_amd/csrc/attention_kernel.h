@@ -16,8 +16,8 @@
 //   D[4 q4 + r][r16]: rows come from the A operand, the column is the lane's query.  Hence
 //   * the running maximum of a query needs its 16 in-lane values per key block and one exchange
 //     with the three other lanes that hold the same query (lane ^ 16, lane ^ 32);
-//   * the running sum stays per lane (the four lanes share the maximum, so their partial sums
-//     have the same scale) and is added up once at the end;
+//   * the softmax denominator is one more tile of the second contraction (V^T extended by a tile
+//     of ones), which also adds up the four lanes;
 //   * P^T in registers already IS the B operand of the second MFMA: a B operand lane holds 8
 //     K-values (here: keys) of one column (query).  The 8 keys a lane holds after two S^T tiles are
 //     {32u + 4 q4 + 0..3} and {32u + 16 + 4 q4 + 0..3}, not 8 consecutive ones, so the A operand
@@ -26,7 +26,10 @@
 //   Q^T fragments (the B operand of the first MFMA: 8 consecutive d of one query) are 16-byte
 //   pieces of Q rows: loaded once from global memory straight into registers.
 //   Softmax runs in base 2: p = 2^(s * c - m * c) with c = scale * log2(e), fp32.  P is rounded to
-//   bf16 (RNE) for the second MFMA; the row sum adds the unrounded values.
+//   bf16 (RNE) for the second MFMA; numerator and denominator sum the same rounded values.
+//   One wave per SIMD (the accumulators take most of the 512 registers), so nothing hides a stall:
+//   the key blocks are software-pipelined (scores of block j+1 under the softmax of block j, see
+//   `step` below) and every instruction is placed by hand between the MFMAs.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -263,7 +266,7 @@ attn_fwd_kernel(const AttnArgs p)
             o[dt][qt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             asm volatile("" : "+a"(o[dt][qt]));
         }
-    f32x4_t lsum[QT];                // row sums of P, as a 17th..th MFMA tile: V^T extended by a tile of ones
+    f32x4_t lsum[QT];                // row sums of P: one more tile of O^T, from a V^T tile of ones
     float m[QT], mx[QT], mc[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
@@ -307,7 +310,7 @@ attn_fwd_kernel(const AttnArgs p)
         if (qt == 0 && f + 2 < NF) read_k(slot_off, f + 2);
 #endif
         // The softmax values worked on behind the previous MFMA (the other S buffer's registers in
-        // their three stages, the row sum, the packed pairs) ride along as dummy operands:
+        // their three stages, the packed pairs) ride along as dummy operands:
         // that is what keeps the compiler from moving the softmax out from between the MFMAs.
         const int e1 = (i + 1) * EPM < NE ? (i + 1) * EPM : NE - 1;      // an element stage 1 touched in slot i - 1
         const int e3 = i > 0 ? (i - 1) * EPM : 0;                        // an element stage 3 touched in slot i - 1
@@ -327,7 +330,7 @@ attn_fwd_kernel(const AttnArgs p)
     // in consecutive MFMA slots for one element and side by side for three different elements: a
     // single wave per SIMD has nothing else to cover the latency of a dependent vector instruction
     // (measured: fma -> exp -> add back to back take 29 cycles, the same three independent 17).
-    //   stage 1: t = s c - m c      stage 2: p = 2^t      stage 3: row sum, pack pairs to bf16
+    //   stage 1: t = s c - m c      stage 2: p = 2^t      stage 3: pack pairs to bf16
     auto sm1 = [&](auto sb_, auto e_) __attribute__((always_inline)) {
         constexpr int sb = decltype(sb_)::value, e = decltype(e_)::value;
         if constexpr (e < NE) {
