@@ -130,8 +130,35 @@ def cases(names=None):
         Case("c5.down+res", 2048, 4096, 14336, 1, residual=True,
              maker=lambda: {"A": h5(), "B": g5()["Wd"], "R": g5()["R"]}),
     ]
+    # the paper's own problem shapes (Section 5.1), a second workload: "p*" = the three GEMM
+    # problems, "pb.*" = the blocks' projections at the token counts the paper measures
+    pg, pl = {}, {}
+
+    def bg():
+        if not pg:
+            pg.update(wl.paper_block("gpt"))
+        return pg
+
+    def bl():
+        if not pl:
+            pl.update(wl.paper_block("llama"))
+        return pl
+
+    paper = [
+        Case("p1.square4096", 4096, 4096, 4096, 0, maker=lambda: dict(wl.paper_square())),
+        Case("p3.batched128x512x2048x1024", 512, 2048, 1024, 0, batch=128, maker=lambda: dict(wl.paper_batched())),
+        Case("p6.largeK524288", 256, 256, 524288, 0, splitk=True, maker=lambda: dict(wl.paper_large_k())),
+        Case("pb.gpt.qkv+bias", 65536, 2304, 768, 1, bias=True, maker=lambda: {"A": bg()["X"], "B": bg()["Wqkv"], "bias": bg()["bqkv"]}),
+        Case("pb.gpt.up+bias+gelu", 65536, 3072, 768, 1, act=G, bias=True, maker=lambda: {"A": bg()["X"], "B": bg()["W1"], "bias": bg()["b1"]}),
+        Case("pb.gpt.down+bias+res", 65536, 768, 3072, 1, bias=True, residual=True,
+             maker=lambda: {"A": wl.normal((65536, 3072), 0.5, "pb.gpt.Hstandin"), "B": bg()["W2"], "bias": bg()["b2"], "R": bg()["R"]}),
+        Case("pb.llama.qkv", 32768, 6144, 4096, 1, maker=lambda: {"A": bl()["X"], "B": bl()["Wqkv"]}),
+        Case("pb.llama.gate_up_silu", 32768, 28672, 4096, 1, act=S, maker=lambda: {"A": bl()["X"], "B": _t.cat([bl()["W1"], bl()["Wu"]])}),
+        Case("pb.llama.down+res", 32768, 4096, 14336, 1, residual=True,
+             maker=lambda: {"A": wl.normal((32768, 14336), 0.3, "pb.llama.Hstandin"), "B": bl()["W2"], "R": bl()["R"]}),
+    ]
     if names:
-        allc = [c for c in allc if any(c.name.startswith(n) for n in names)]
+        return [c for c in allc + paper if any(c.name.startswith(n) for n in names)]
     return allc
 
 

@@ -162,3 +162,51 @@ def test_attention_llama_shape_2048_tokens():
 
 def test_attention_gpt_shape_8x1024():
     _attention_full(wl.attention4(), [(0, 0), (0, 11), (3, 5), (7, 0), (7, 11)])
+
+
+# ---- the paper's own problem shapes (Section 5.1), the second workload ----------------------------
+
+def test_paper_square_4096():
+    c = wl.paper_square()
+    n = 4096
+    C = torch.empty(n, n, dtype=torch.bfloat16, device="cuda")
+    fact.binding.check(fact.fact_gemm(n, n, n, c["A"].cuda(), n, c["B"].cuda(), n, 0, C, n, None))
+    rows = rows_for(n, 60, "full.p1")
+    s = check.assert_close(bits_of(C), ref.gemm_epilogue(c["A"], c["B"], False, rows=rows), rows="full", what="paper problem 1")
+    assert s["bits_equal_frac"] > 0.95, s
+
+
+def test_paper_batched_128x512x2048x1024():
+    c = wl.paper_batched()
+    batch, m, k, n = 128, 512, 1024, 2048
+    C = torch.empty(batch, m, n, dtype=torch.bfloat16, device="cuda")
+    fact.binding.check(fact.fact_gemm_batched(batch, m, n, k, c["A"].cuda(), k, m * k, c["B"].cuda(), n, k * n, 0, C, n, m * n, None))
+    got = bits_of(C)
+    for b in (0, 63, 127):
+        check.assert_close(got[b], ref.gemm_epilogue(c["A"][b], c["B"][b]), what=f"paper problem 3 batch {b}")
+
+
+def test_paper_large_k_524288():
+    c = wl.paper_large_k()
+    m, n, k = 256, 256, 524288
+    need = fact.fact_gemm_splitk_workspace_bytes(m, n, k, 0)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    C = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    fact.binding.check(fact.fact_gemm_splitk(m, n, k, c["A"].cuda(), k, c["B"].cuda(), n, 0, C, n, None, 0, ws, need))
+    rows = rows_for(m, 24, "full.p6", tile=128)
+    s = check.assert_close(bits_of(C), ref.gemm_epilogue(c["A"], c["B"], False, rows=rows), rows="full", what="paper problem 6")
+    assert s["rel_frobenius"] < 3e-3, s
+
+
+def test_paper_llama_block_gate_up_32768_tokens():
+    c = wl.paper_block("llama")
+    t, d, dff = c["tokens"], c["d"], c["dff"]
+    W = torch.cat([c["W1"], c["Wu"]])
+    need = fact.fact_gemm_splitk_workspace_bytes(t, 2 * dff, d, 0)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    H = torch.empty(t, dff, dtype=torch.bfloat16, device="cuda")
+    ep = fact.Epilogue(act=fact.ACT_SILU_GATE)
+    fact.binding.check(fact.fact_gemm_splitk(t, 2 * dff, d, c["X"].cuda(), d, W.cuda(), d, 1, H, dff, ep, 0, ws, need))
+    rows = rows_for(t, 40, "full.pb.llama")
+    r = ref.gemm_epilogue(c["X"], W, True, act=ref.ACT_SILU_GATE, rows=rows)
+    check.assert_close(bits_of(H), r, rows="full", what="paper Llama block gate+up")

@@ -148,3 +148,38 @@ def split_qkv(w):
     k = b[:, :, Hq * D: (Hq + Hkv) * D].reshape(B, T, Hkv, D)
     v = b[:, :, (Hq + Hkv) * D:].reshape(B, T, Hkv, D)
     return q, k, v
+
+
+# ---- the paper's own problem shapes (Section 5.1 "Benchmark problems"), as a second workload -----
+# Shapes only: the benchmark suite's files and the model's weights are not available and are not
+# reconstructed; inputs are seeded draws as above, in bf16 (the paper runs them in tf32 / fp16).
+
+def paper_square(n=4096):
+    """Problem 1 of Section 5.1: C = A B, 4096 x 4096."""
+    return {"A": normal((n, n), 1.0, f"p1.A.{n}"), "B": normal((n, n), 1.0, f"p1.B.{n}")}
+
+
+def paper_batched(batch=128, m=512, k=1024, n=2048):
+    """Problem 3: 128 x ([512, 1024] x [1024, 2048])."""
+    return {"A": normal((batch, m, k), 1.0, "p3.A"), "B": normal((batch, k, n), 1.0, "p3.B")}
+
+
+def paper_large_k(m=256, n=256, k=524288):
+    """Problem 6: [256, 524288] x [524288, 256]; entries ~ N(0, variance 1/K) as in configuration 3b."""
+    std = float(k) ** -0.5
+    return {"A": normal((m, k), std, "p6.A"), "B": normal((k, n), std, "p6.B")}
+
+
+def paper_block(kind):
+    """Projection GEMMs of the two blocks at the token counts the paper measures: (128, 512, 768) and
+    (16, 2048, 4096) with intermediate 14336.  Weights ~ N(0, 0.02), activations ~ N(0, 1)."""
+    if kind == "gpt":
+        t, d, dff, nqkv = 128 * 512, 768, 3072, 3 * 768
+    else:
+        t, d, dff, nqkv = 16 * 2048, 4096, 14336, 6144
+    return {"tokens": t, "d": d, "dff": dff, "nqkv": nqkv,
+            "X": normal((t, d), 1.0, f"pb.{kind}.X"), "Wqkv": normal((nqkv, d), 0.02, f"pb.{kind}.Wqkv"),
+            "W1": normal((dff, d), 0.02, f"pb.{kind}.W1"), "Wu": normal((dff, d), 0.02, f"pb.{kind}.Wu") if kind != "gpt" else None,
+            "W2": normal((d, dff), 0.02, f"pb.{kind}.W2"), "R": normal((t, d), 1.0, f"pb.{kind}.R"),
+            "bqkv": normal((nqkv,), 0.02, f"pb.{kind}.bqkv"), "b1": normal((dff,), 0.02, f"pb.{kind}.b1"),
+            "b2": normal((d,), 0.02, f"pb.{kind}.b2")}
