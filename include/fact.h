@@ -176,6 +176,58 @@ int fact_attention(int64_t batch, int64_t T, int64_t n_q_heads, int64_t n_kv_hea
                    const void *V, const int64_t *v_strides, void *O, const int64_t *o_strides,
                    int causal, float scale, void *stream);
 
+/*
+ * Row normalisation, one memory-bound launch (the blocks of Section 5.1: LayerNorm in the GPT-style
+ * block, RMSNorm in the Llama block):
+ *   rms == 0 (LayerNorm): y = (x - mean(x)) / sqrt(var(x) + eps) * gamma + beta   (beta may be NULL)
+ *   rms == 1 (RMSNorm):   y = x / sqrt(mean(x^2) + eps) * gamma                   (beta must be NULL)
+ * X, Y: bf16 [T][d] with leading dimensions ldx, ldy (elements); gamma, beta: bf16 [d].  Statistics
+ * in fp32 (two passes over the row held in registers), one rounding to bf16.  d must be a multiple
+ * of 8 and <= 8192, pointers 16-byte aligned, leading dimensions multiples of 8
+ * (FACT_ERR_UNSUPPORTED / FACT_ERR_ALIGN otherwise).  Y may alias X.
+ */
+int fact_norm(int64_t T, int64_t d, const void *X, int64_t ldx, const void *gamma, const void *beta, float eps, int rms,
+              void *Y, int64_t ldy, void *stream);
+
+/*
+ * Rotary position embedding, in place, "rotate-half" pairing (the Llama block of Section 5.1):
+ * for head width D, i < D/2 and token position t (0-based in its batch entry),
+ *   angle = t * base^(-2 i / D),  (x_i, x_{i+D/2}) <- (x_i cos - x_{i+D/2} sin, x_{i+D/2} cos + x_i sin).
+ * X: bf16 [batch][T][n_heads][head_dim] with element strides {batch, token, head} (host array of 3);
+ * for a packed QKV buffer pass n_heads = query heads + key heads (they are adjacent).  head_dim a
+ * multiple of 16, 16-byte aligned, strides multiples of 8, base > 1.  fp32 arithmetic, one rounding.
+ */
+int fact_rope(int64_t batch, int64_t T, int64_t n_heads, int64_t head_dim, void *X, const int64_t *strides, float base,
+              void *stream);
+
+/*
+ * A whole pre-norm decoder block from this library's entry points (the composition step of
+ * Section 4.3 applied to the two blocks of Section 5.1; every stage runs on the GPU):
+ *     N1  = norm(X);  QKV = N1 Wqkv^T + bqkv;  rotary on the q and k heads (if rope);
+ *     A   = causal attention(QKV);  X1 = A Wo^T + bo + X;
+ *     N2  = norm(X1);  H = act(N2 W1^T + b1)  [or SiLU(N2 W1^T) * (N2 W1u^T)];  Y = H W2^T + b2 + X1.
+ * X, Y: bf16 [batch * tokens][d_model], dense.  Wqkv: [(n_q_heads + 2 n_kv_heads) head_dim][d_model],
+ * rows ordered query heads, key heads, value heads; Wo: [d_model][n_q_heads head_dim]; W1 (and
+ * W1u with FACT_ACT_SILU_GATE): [d_ff][d_model]; W2: [d_model][d_ff].  Biases and norm1_b / norm2_b may
+ * be NULL; norm_rms == 1 ignores them.  eps <= 0 selects 1e-5, rope_base <= 1 selects 500000.
+ * Every intermediate is stored as bf16 in `scratch` (fact_block_scratch_bytes() bytes, 256-byte
+ * aligned, contents scratch); fact_block_scratch_offsets() writes the byte offsets of
+ * {N1, QKV (after the rotary step), A, X1, N2, H, GEMM workspace} for inspection.
+ * Nine launches on `stream` (ten with the rotary step), no synchronisation.
+ */
+typedef struct fact_block {
+    int64_t batch, tokens, d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
+    int32_t norm_rms;            /* 1: RMSNorm, 0: LayerNorm */
+    int32_t act;                 /* FACT_ACT_GELU_TANH, FACT_ACT_SILU_GATE or FACT_ACT_NONE */
+    int32_t rope;                /* 1: rotary embedding on q and k */
+    float eps, rope_base;
+    const void *norm1_g, *norm1_b, *Wqkv, *bqkv, *Wo, *bo, *norm2_g, *norm2_b, *W1, *W1u, *b1, *W2, *b2;
+} fact_block;
+
+size_t fact_block_scratch_bytes(const fact_block *blk);                  /* 0 if the description is invalid */
+int fact_block_scratch_offsets(const fact_block *blk, size_t *offsets /* [7] */);
+int fact_block_forward(const fact_block *blk, const void *X, void *Y, void *scratch, size_t scratch_bytes, void *stream);
+
 /* ---- tile configurations: the auto-tuning surface (Section 4.2 Action 5) ---------------- */
 
 /* Number of compiled tile configurations; ids are 0 .. fact_num_configs()-1. */

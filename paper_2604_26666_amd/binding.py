@@ -30,6 +30,34 @@ class _CEpilogue(ctypes.Structure):
     _fields_ = [("bias", _ptr), ("residual", _ptr), ("ldr", _i64), ("stride_r", _i64), ("act", ctypes.c_int32)]
 
 
+class _CBlock(ctypes.Structure):
+    _fields_ = ([(n, _i64) for n in ("batch", "tokens", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ff")] +
+                [("norm_rms", ctypes.c_int32), ("act", ctypes.c_int32), ("rope", ctypes.c_int32),
+                 ("eps", ctypes.c_float), ("rope_base", ctypes.c_float)] +
+                [(n, _ptr) for n in ("norm1_g", "norm1_b", "Wqkv", "bqkv", "Wo", "bo", "norm2_g", "norm2_b", "W1", "W1u", "b1", "W2", "b2")])
+
+
+class Block:
+    """Mirror of the C struct fact_block; pointer fields take tensors, ints or None."""
+    _PTRS = ("norm1_g", "norm1_b", "Wqkv", "bqkv", "Wo", "bo", "norm2_g", "norm2_b", "W1", "W1u", "b1", "W2", "b2")
+
+    def __init__(self, batch, tokens, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, norm_rms, act, rope=0, eps=0.0,
+                 rope_base=0.0, **weights):
+        self.dims = (batch, tokens, d_model, n_q_heads, n_kv_heads, head_dim, d_ff)
+        self.norm_rms, self.act, self.rope, self.eps, self.rope_base = norm_rms, act, rope, eps, rope_base
+        unknown = set(weights) - set(self._PTRS)
+        if unknown:
+            raise TypeError(f"unknown block fields {sorted(unknown)}")
+        self.weights = weights                      # keeps the tensors alive
+
+    def _c(self):
+        c = _CBlock(*[int(v) for v in self.dims], int(self.norm_rms), int(self.act), int(self.rope), float(self.eps),
+                    float(self.rope_base))
+        for n in self._PTRS:
+            setattr(c, n, _addr(self.weights.get(n)))
+        return c
+
+
 class Epilogue:
     """Mirror of the C struct fact_epilogue."""
 
@@ -73,6 +101,17 @@ def lib():
         L.fact_attention.argtypes = [_i64, _i64, _i64, _i64, _i64, _ptr, i64p, _ptr, i64p, _ptr, i64p, _ptr, i64p,
                                      _int, ctypes.c_float, _ptr]
         L.fact_attention.restype = _int
+        L.fact_norm.argtypes = [_i64, _i64, _ptr, _i64, _ptr, _ptr, ctypes.c_float, _int, _ptr, _i64, _ptr]
+        L.fact_norm.restype = _int
+        L.fact_rope.argtypes = [_i64, _i64, _i64, _i64, _ptr, i64p, ctypes.c_float, _ptr]
+        L.fact_rope.restype = _int
+        bp = ctypes.POINTER(_CBlock)
+        L.fact_block_scratch_bytes.argtypes = [bp]
+        L.fact_block_scratch_bytes.restype = _size
+        L.fact_block_scratch_offsets.argtypes = [bp, ctypes.POINTER(_size)]
+        L.fact_block_scratch_offsets.restype = _int
+        L.fact_block_forward.argtypes = [bp, _ptr, _ptr, _ptr, _size, _ptr]
+        L.fact_block_forward.restype = _int
         L.fact_num_configs.argtypes = []
         ip = ctypes.POINTER(_int)
         L.fact_config_info.argtypes = [_int, ip, ip, ip, ip, ip]
@@ -158,6 +197,30 @@ def fact_attention(batch, T, n_q_heads, n_kv_heads, head_dim, Q, q_strides, K, k
     arr = lambda s: (_i64 * 3)(*[int(x) for x in s])
     return lib().fact_attention(batch, T, n_q_heads, n_kv_heads, head_dim, _addr(Q), arr(q_strides), _addr(K), arr(k_strides),
                                 _addr(V), arr(v_strides), _addr(O), arr(o_strides), int(causal), float(scale), _stream(stream))
+
+
+def fact_norm(T, d, X, ldx, gamma, beta, eps, rms, Y, ldy, stream=None):
+    return lib().fact_norm(T, d, _addr(X), ldx, _addr(gamma), _addr(beta), float(eps), int(rms), _addr(Y), ldy, _stream(stream))
+
+
+def fact_rope(batch, T, n_heads, head_dim, X, strides, base, stream=None):
+    return lib().fact_rope(batch, T, n_heads, head_dim, _addr(X), (_i64 * 3)(*[int(x) for x in strides]), float(base), _stream(stream))
+
+
+def fact_block_scratch_bytes(blk):
+    return int(lib().fact_block_scratch_bytes(ctypes.byref(blk._c())))
+
+
+def fact_block_scratch_offsets(blk):
+    """Byte offsets of (N1, QKV, A, X1, N2, H, workspace) inside the scratch buffer."""
+    offs = (_size * 7)()
+    rc = lib().fact_block_scratch_offsets(ctypes.byref(blk._c()), offs)
+    check(rc, "fact_block_scratch_offsets")
+    return [int(v) for v in offs]
+
+
+def fact_block_forward(blk, X, Y, scratch, scratch_bytes, stream=None):
+    return lib().fact_block_forward(ctypes.byref(blk._c()), _addr(X), _addr(Y), _addr(scratch), int(scratch_bytes), _stream(stream))
 
 
 def fact_num_configs():

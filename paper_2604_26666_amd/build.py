@@ -137,7 +137,7 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
         units.append((obj, [HIPCC] + FLAGS + ["-Rpass-analysis=kernel-resource-usage", f"-DFACT_ID={cid}", f"-DFACT_BM={bm}", f"-DFACT_BN={bn}",
                                               f"-DFACT_WM={wm}", f"-DFACT_WN={wn}", f"-DFACT_BK={bk}", f"-DFACT_STAGES={st}",
                                               "-c", os.path.join(CSRC, "inst.hip"), "-o", obj]))
-    for name in ("aux_kernels", "fact_api", "attention"):
+    for name in ("aux_kernels", "fact_api", "attention", "block"):
         obj = os.path.join(OBJ, name + ".o")
         units.append((obj, [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, name + ".hip"), "-o", obj]))
     usage = {}
