@@ -121,6 +121,7 @@ def main():
         from paper_2604_26666_amd import workbench
         out["others"] = workbench.time_all(args.steps, args.warmup)
         out["attention"] = workbench.time_attention(args.steps, args.warmup)
+        out["blocks"] = workbench.time_blocks()
         out["paper_shapes"] = workbench.time_all(args.steps, args.warmup, names=["p1.", "p3.", "p6.", "pb."])
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()

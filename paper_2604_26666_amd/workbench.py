@@ -311,6 +311,45 @@ def time_attention(steps=30, warmup=30):
     return out
 
 
+def time_blocks(steps=20, warmup=10):
+    """Whole decoder blocks through fact_block_forward: ms per block and the TFLOP/s of its matrix
+    work (the four projections' 2 M N K plus the attention's causal half)."""
+    import workloads as wl
+    out = {}
+    for name, kind, B, T in (("blk.gpt_8x1024", "gpt", 8, 1024), ("blk.gpt_128x512", "gpt", 128, 512),
+                             ("blk.llama_1x2048", "llama", 1, 2048), ("blk.llama_16x2048", "llama", 16, 2048)):
+        desc, t, X = wl.block_weights(kind, B, T)
+        act = fact.ACT_SILU_GATE if desc["act_gated"] else fact.ACT_GELU_TANH
+        b = fact.Block(B, T, desc["d_model"], desc["q_heads"], desc["kv_heads"], desc["head_dim"], desc["d_ff"], int(desc["rms"]),
+                       act, int(desc["rope"]), desc["eps"], desc["rope_base"], **{k: v.cuda() for k, v in t.items()})
+        need = fact.fact_block_scratch_bytes(b)
+        scratch = torch.empty(need, dtype=torch.uint8, device="cuda")
+        Xd = X.cuda()
+        Y = torch.empty_like(Xd)
+        run = lambda: fact.fact_block_forward(b, Xd, Y, scratch, need)
+        if run() != 0:
+            out[name] = {"error": "refused"}
+            continue
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            run()
+        e.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(e) / steps
+        Tt, d, dff = B * T, desc["d_model"], desc["d_ff"]
+        nq, nkv = desc["q_heads"] * desc["head_dim"], desc["kv_heads"] * desc["head_dim"]
+        flops = 2.0 * Tt * d * (nq + 2 * nkv) + 2.0 * Tt * nq * d + 2.0 * Tt * d * dff * (3 if desc["act_gated"] else 2) \
+            + 4.0 * B * desc["q_heads"] * desc["head_dim"] * (T * (T + 1) / 2.0)
+        out[name] = {"ms": round(ms, 4), "tflops": round(flops / ms / 1e9, 1), "pct_mfma_peak": round(100 * flops / ms / 1e9 / PEAK_BF16_TFLOPS, 2),
+                     "launches": 10 if desc["rope"] else 9, "scratch_MB": round(need / 2 ** 20, 1)}
+        del scratch, Xd, Y, b
+    return out
+
+
 def report(case, ms):
     tf = case.flops / (ms * 1e-3) / 1e12
     gbs = case.min_bytes / (ms * 1e-3) / 1e9

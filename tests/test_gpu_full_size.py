@@ -210,3 +210,51 @@ def test_paper_llama_block_gate_up_32768_tokens():
     rows = rows_for(t, 40, "full.pb.llama")
     r = ref.gemm_epilogue(c["X"], W, True, act=ref.ACT_SILU_GATE, rows=rows)
     check.assert_close(bits_of(H), r, rows="full", what="paper Llama block gate+up")
+
+
+# ---- a whole Llama-3-8B-shaped block at configuration 5's 2048 tokens, stage by stage -----------
+
+def test_whole_llama_block_2048_tokens_sampled_stage_by_stage():
+    """Every stage is checked against its oracle fed the GPU's own previous tensor, on sampled rows
+    (GEMM stages), sampled heads (attention) or in full (norms, rotary)."""
+    from oracle import attention as att
+    from oracle import block as blk
+    desc, t, X = wl.block_weights("llama", 1, 2048)
+    B, T, d, Hq, Hkv, D, dff = 1, 2048, desc["d_model"], desc["q_heads"], desc["kv_heads"], desc["head_dim"], desc["d_ff"]
+    b = fact.Block(B, T, d, Hq, Hkv, D, dff, 1, fact.ACT_SILU_GATE, 1, 1e-5, 500000.0, **{k: v.cuda() for k, v in t.items()})
+    need = fact.fact_block_scratch_bytes(b)
+    scratch = torch.empty(need, dtype=torch.uint8, device="cuda")
+    Y = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")
+    fact.binding.check(fact.fact_block_forward(b, X.cuda(), Y, scratch, need))
+    torch.cuda.synchronize()
+    offs = fact.fact_block_scratch_offsets(b)
+    raw = scratch.cpu().numpy()
+    n = (Hq + 2 * Hkv) * D
+    view = lambda i, r, c: raw[offs[i]: offs[i] + r * c * 2].view(np.uint16).reshape(r, c)
+    N1, QKVR, A, X1, N2, H = view(0, T, d), view(1, T, n), view(2, T, Hq * D), view(3, T, d), view(4, T, d), view(5, T, dff)
+    Yb = bits_of(Y)
+    W = {k: wl.bits(v) for k, v in t.items()}
+    rows = rows_for(T, 24, "full.blk")
+    check.assert_close(N1, blk.rmsnorm(wl.bits(X), W["norm1_g"]), what="block N1")
+    # QKV projection rows, then the rotary step on those rows' q and k heads (positions = row numbers)
+    qkv = ref.gemm_epilogue(N1, W["Wqkv"], True, rows=rows)
+    qk = qkv.bits[:, : (Hq + Hkv) * D].reshape(1, len(rows), Hq + Hkv, D)
+    full = np.zeros((1, T, Hq + Hkv, D), dtype=np.uint16); full[0, rows] = qk[0]
+    rot = blk.rotary(full)
+    rz = rot.z.reshape(T, (Hq + Hkv) * D)[rows]; rb = rot.bound.reshape(T, (Hq + Hkv) * D)[rows]
+    r_qk = ref.Ref(z=rz, bound=rb, bits=ref.round_bf16(rz), rows=rows)
+    check.assert_close(np.ascontiguousarray(QKVR[:, : (Hq + Hkv) * D]), r_qk, rows="full", what="block q, k after rotary")
+    assert np.array_equal(QKVR[rows][:, (Hq + Hkv) * D:], qkv.bits[:, (Hq + Hkv) * D:]) or \
+        check.compare(np.ascontiguousarray(QKVR[:, (Hq + Hkv) * D:]), ref.Ref(z=qkv.z[:, (Hq + Hkv) * D:], bound=qkv.bound[:, (Hq + Hkv) * D:],
+                      bits=qkv.bits[:, (Hq + Hkv) * D:], rows=rows), rows="full")["ok"]
+    q4 = QKVR[:, : Hq * D].reshape(1, T, Hq, D); k4 = QKVR[:, Hq * D: (Hq + Hkv) * D].reshape(1, T, Hkv, D)
+    v4 = QKVR[:, (Hq + Hkv) * D:].reshape(1, T, Hkv, D)
+    for h in (0, 5, 31):
+        g = h // (Hq // Hkv)
+        r = att.attention(q4[:, :, h:h + 1], k4[:, :, g:g + 1], v4[:, :, g:g + 1])
+        check.assert_close(np.ascontiguousarray(A.reshape(T, Hq, D)[:, h]), r, what=f"block attention head {h}")
+    check.assert_close(X1, ref.gemm_epilogue(A, W["Wo"], True, residual=wl.bits(X), rows=rows), rows="full", what="block X1")
+    check.assert_close(N2, blk.rmsnorm(X1, W["norm2_g"]), what="block N2")
+    Wgu = np.concatenate([W["W1"], W["W1u"]], axis=0)
+    check.assert_close(H, ref.gemm_epilogue(N2, Wgu, True, act=ref.ACT_SILU_GATE, rows=rows), rows="full", what="block H")
+    check.assert_close(Yb, ref.gemm_epilogue(H, W["W2"], True, residual=X1, rows=rows), rows="full", what="block Y")

@@ -183,3 +183,32 @@ def paper_block(kind):
             "W2": normal((d, dff), 0.02, f"pb.{kind}.W2"), "R": normal((t, d), 1.0, f"pb.{kind}.R"),
             "bqkv": normal((nqkv,), 0.02, f"pb.{kind}.bqkv"), "b1": normal((dff,), 0.02, f"pb.{kind}.b1"),
             "b2": normal((d,), 0.02, f"pb.{kind}.b2")}
+
+
+# ---- whole blocks ---------------------------------------------------------------------------------
+
+def block_weights(kind, batch, tokens):
+    """Seeded weights and input of a whole block: "gpt" = GPT-small shape (d 768, 12 heads of 64, d_ff
+    3072, LayerNorm, biases, GELU), "llama" = Llama-3-8B shape (d 4096, 32 query / 8 key-value heads of
+    128, d_ff 14336, RMSNorm, rotary embedding, SwiGLU, no biases).  Projection weights ~ N(0, 0.02), norm
+    gains ~ N(1, 0.1), biases ~ N(0, 0.02), input ~ N(0, 1).  Returns (description dict, tensors dict, X)."""
+    if kind == "gpt":
+        d, Hq, Hkv, D, dff = 768, 12, 12, 64, 3072
+    else:
+        d, Hq, Hkv, D, dff = 4096, 32, 8, 128, 14336
+    n = (Hq + 2 * Hkv) * D
+    tag = f"blk.{kind}"
+    gain = lambda name: (normal((d,), 0.1, f"{tag}.{name}").float() + 1.0).to(torch.bfloat16)
+    t = {"norm1_g": gain("n1g"), "norm2_g": gain("n2g"),
+         "Wqkv": normal((n, d), 0.02, f"{tag}.Wqkv"), "Wo": normal((d, Hq * D), 0.02, f"{tag}.Wo"),
+         "W1": normal((dff, d), 0.02, f"{tag}.W1"), "W2": normal((d, dff), 0.02, f"{tag}.W2")}
+    if kind == "gpt":
+        t.update({"norm1_b": normal((d,), 0.02, f"{tag}.n1b"), "norm2_b": normal((d,), 0.02, f"{tag}.n2b"),
+                  "bqkv": normal((n,), 0.02, f"{tag}.bqkv"), "bo": normal((d,), 0.02, f"{tag}.bo"),
+                  "b1": normal((dff,), 0.02, f"{tag}.b1"), "b2": normal((d,), 0.02, f"{tag}.b2")})
+    else:
+        t["W1u"] = normal((dff, d), 0.02, f"{tag}.W1u")
+    desc = {"batch": batch, "tokens": tokens, "d_model": d, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "d_ff": dff,
+            "rms": kind != "gpt", "rope": kind != "gpt", "rope_base": 500000.0, "eps": 1e-5, "act_gated": kind != "gpt"}
+    X = normal((batch * tokens, d), 1.0, f"{tag}.X.{batch}.{tokens}")
+    return desc, t, X
