@@ -75,12 +75,6 @@ extern "C" int fact_attention(int64_t batch, int64_t T, int64_t n_q_heads, int64
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)head_dim);
     a.scale_log2 = sc * 1.4426950408889634f;
     a.q_blocks = 0; a.total = 0;
-#ifdef FACT_ATTN_DBG
-    {
-        const char *e = std::getenv("FACT_ATTN_DBG_PTR");
-        a.dbg = e ? (long long *)std::strtoull(e, nullptr, 0) : nullptr;
-    }
-#endif
 
     // 256 queries per work-group when that still gives every compute unit two work-groups;
     // otherwise 128 (two of those fit on a compute unit)

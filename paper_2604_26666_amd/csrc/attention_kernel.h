@@ -63,9 +63,6 @@ struct AttnArgs {
     float scale_log2;       // softmax scale * log2(e)
     int q_blocks;           // ceil(T / BQ)
     int total;              // q_blocks * Hq * B work-groups
-#ifdef FACT_ATTN_DBG
-    long long *dbg;         // 8 counters per wave: cycles in total / waiting at the step top / S phase / PV phase, key blocks
-#endif
 };
 
 constexpr uint32_t kBufFlags = 0x00020000u;      // raw buffer descriptor word 3 (32-bit data format)
@@ -287,10 +284,6 @@ attn_fwd_kernel(const AttnArgs p)
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) pf[u][qt] = u32x4_t{0u, 0u, 0u, 0u};
     const float c = p.scale_log2;
-#ifdef FACT_ATTN_DBG
-    long long dbg_wait = 0, dbg_s = 0, dbg_pv = 0, dbg_ld = 0, dbg_grow = 0;
-    const long long dbg_t0 = clock64();
-#endif
 
     constexpr int NS = KT * KB * QT;                 // MFMAs of one S^T block
     constexpr int EPM = KT * QT * 4 / NS;             // softmax elements worked off behind each of them
@@ -306,9 +299,7 @@ attn_fwd_kernel(const AttnArgs p)
     // MFMA number i of S^T(block) into S[tb]: fragment f = i / QT (key tile kt, 32 d's kb), query tile i % QT
     auto s_mfma = [&](int tb, int slot_off, int i) __attribute__((always_inline)) {
         const int f = i / QT, qt = i % QT, kt = f / KB, kb = f % KB;
-#ifndef FACT_ATTN_DBG_NOKREAD
         if (qt == 0 && f + 2 < NF) read_k(slot_off, f + 2);
-#endif
         // The softmax values worked on behind the previous MFMA (the other S buffer's registers in
         // their three stages, the packed pairs) ride along as dummy operands:
         // that is what keeps the compiler from moving the softmax out from between the MFMAs.
@@ -433,15 +424,8 @@ attn_fwd_kernel(const AttnArgs p)
         typedef std::integral_constant<int, PAR ^ 1> nxt_t;
         // Loads issued one step ago (K of block j+1, V of block j) have landed, for every wave; every
         // wave is done with K of block j and V of block j-1, whose slots the new loads overwrite.
-#ifdef FACT_ATTN_DBG
-        const long long d0 = clock64();
-#endif
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-#ifdef FACT_ATTN_DBG
-        const long long d1 = clock64();
-        dbg_wait += d1 - d0;
-#endif
         // The new loads: a wave with work issues them one by one between the MFMAs below (in a burst
         // right here, 4 waves x 2 L loads queue up at the compute unit's address unit and every wave
         // loses ~400 cycles of issue time).
@@ -450,10 +434,6 @@ attn_fwd_kernel(const AttnArgs p)
             if (j + 1 < nb) load_v(j + 1);
             return;
         }
-#ifdef FACT_ATTN_DBG
-        const long long d1b = clock64();
-        dbg_ld += d1b - d1;
-#endif
 
         // m[qt] is the REFERENCE exponent of the query's running sums, not always its running
         // maximum: it is raised (and the sums rescaled) only when a score exceeds it by more than
@@ -484,10 +464,6 @@ attn_fwd_kernel(const AttnArgs p)
         }
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) mc[qt] = m[qt] * c;
-#ifdef FACT_ATTN_DBG
-        const long long d1c = clock64();
-        dbg_grow += d1c - d1b;
-#endif
 
         // S^T of block j + 1, one softmax element of block j behind each MFMA.  On the wave's last
         // block this still runs, on whatever the other K slot holds: the result is never used, and
@@ -515,12 +491,10 @@ attn_fwd_kernel(const AttnArgs p)
                 }
                 unroll<EPM>([&](auto k_) __attribute__((always_inline)) {
                     constexpr int k = decltype(k_)::value;
-#ifndef FACT_ATTN_DBG_NOSM
                     sm1(cur_t{}, std::integral_constant<int, (i + 2) * EPM + k>{});
                     __builtin_amdgcn_sched_barrier(0);      // fma first: an exponential right behind the asm gets a wait state
                     sm2(cur_t{}, std::integral_constant<int, (i + 1) * EPM + k>{});
                     sm3(cur_t{}, std::integral_constant<int, i * EPM + k>{});
-#endif
                 });
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -529,10 +503,6 @@ attn_fwd_kernel(const AttnArgs p)
                 mask_block(nxt_t{}, j + 1);
             }
         }
-#ifdef FACT_ATTN_DBG
-        const long long d2 = clock64();
-        dbg_s += d2 - d1;
-#endif
 
         const uint32_t vbase = lds0 + (2 + (j & 1)) * TILE_BYTES;
         read_v(0, vbase, 0, 0);
@@ -566,9 +536,6 @@ attn_fwd_kernel(const AttnArgs p)
             }
             __builtin_amdgcn_sched_barrier(0);
         });
-#ifdef FACT_ATTN_DBG
-        dbg_pv += clock64() - d2;
-#endif
     };
 
     // first block: S^T(0), its mask and maxima, nothing to overlap with yet
@@ -589,12 +556,6 @@ attn_fwd_kernel(const AttnArgs p)
         step(std::integral_constant<int, 0>{}, j);
         if (j + 1 < nb) step(std::integral_constant<int, 1>{}, j + 1);
     }
-#ifdef FACT_ATTN_DBG
-    if (p.dbg && lane == 0) {
-        long long *d = p.dbg + ((int64_t)blockIdx.x * NW + wave) * 8;
-        d[0] = clock64() - dbg_t0; d[1] = dbg_wait; d[2] = dbg_s; d[3] = dbg_pv; d[4] = nbw; d[5] = nb; d[6] = dbg_ld; d[7] = dbg_grow;
-    }
-#endif
     if (nbw == 0) return;
     nops();                                                      // the last MFMAs have written O
     // (new values for the compiler, so that it cannot read the registers before the wait states)

@@ -317,9 +317,6 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
             }
         }
     }
-#ifdef FACT_DBG_TIMELINE
-    if (a.splits <= 1) a.P = (float *)ws;      // experiments only: per-work-group timestamps
-#endif
     e = c.launch(a, q.trans_b != 0, a.splits > 1 ? a.splits : (int)q.batch, stream);
     if (e != hipSuccess) return hip_fail(e, "gemm launch");
     if (a.splits > 1) {

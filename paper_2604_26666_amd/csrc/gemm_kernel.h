@@ -166,11 +166,7 @@ template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier()
 {
     __builtin_amdgcn_sched_barrier(0);       // nothing is scheduled across the barrier
-#ifdef FACT_DBG_NO_BARRIER
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory");
-#else
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
-#endif
     __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -214,10 +210,6 @@ gemm_kernel(const GemmArgs p)
     static_assert((STAGES - 2) * (LOADS + 1) + 1 <= 63 && STAGES >= 2 && STAGES <= 4, "vmcnt range");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
-#ifdef FACT_DBG_TIMELINE
-    const long long dbg_t0 = wall_clock64();
-    long long dbg_wait = 0;
-#endif
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -410,9 +402,6 @@ gemm_kernel(const GemmArgs p)
     // ksteps read nothing but zeros, so a phantom step adds exactly 0 to the accumulators and
     // the main loop needs no tail code.  Branch-free: setting the top offset bit puts a lane out
     // of the descriptor's range.
-#ifdef FACT_DBG_SKIP_LOADS
-    bool dbg_skip = false;      // experiments only: no loads after the prologue
-#endif
     struct StepCtx {
         char *s;
         uint32_t mask_k;          // per lane: out-of-range bit for K-contiguous operands
@@ -441,9 +430,6 @@ gemm_kernel(const GemmArgs p)
     // of a wave fills LDS block wave * LD + i of the operand: run i / RUN, member i % RUN.
     auto issue_one = [&](const StepCtx &c, auto idx_) __attribute__((always_inline)) {
         constexpr int idx = decltype(idx_)::value;             // compile-time: it selects the immediate offset
-#ifdef FACT_DBG_SKIP_LOADS
-        if (c.beyond || dbg_skip) return;
-#endif
         if constexpr (idx < A_LD) {
             constexpr int i = idx, run0 = (i / A_RUN) * A_RUN, t = i % A_RUN;
             const int blk = wave * A_LD + i;
@@ -521,9 +507,6 @@ gemm_kernel(const GemmArgs p)
     auto read_one = [&](const char *s, int u, auto t_) __attribute__((always_inline)) {
         constexpr int t = decltype(t_)::value;                // compile-time: it selects an immediate offset
         const int kk = u / PH, h = u % PH;
-#ifdef FACT_DBG_NO_READS
-        if (dbg_skip) return;
-#endif
         if constexpr (t < MTH) {
             af[u & 1][t] = *(const bf16x8_t *)(s + a_addr[kk] + (h * MTH + t) * 16 * ROWB);
         } else {
@@ -594,14 +577,10 @@ gemm_kernel(const GemmArgs p)
     // newest STAGES-2 such groups and the prefetch behind the group it waits for
     constexpr int WAIT_N = (STAGES - 2) * (LOADS + 1) + 1;
     // The address unit is shared by the CU's waves and takes one wave-wide load per 16 cycles, so a
-    // step's loads are spread evenly: over the first LOAD_FRAC of the step's MFMAs with a two-slot
+    // step's loads are spread evenly: over the first 3/4 of the step's MFMAs with a two-slot
     // ring (they must have landed by its end), over nearly all of it with a deeper ring.
-#ifndef FACT_LOAD_FRAC_NUM
-#define FACT_LOAD_FRAC_NUM 3
-#define FACT_LOAD_FRAC_DEN 4
-#endif
     constexpr int TG = U * NMFMA;                        // MFMAs (= gaps) per K step
-    constexpr int LOAD_SPAN = STAGES > 2 ? (TG * 15) / 16 : (TG * FACT_LOAD_FRAC_NUM) / FACT_LOAD_FRAC_DEN;
+    constexpr int LOAD_SPAN = STAGES > 2 ? (TG * 15) / 16 : (TG * 3) / 4;
     auto load_gap = [](int l) constexpr { const int g = 1 + (l * LOAD_SPAN) / LOADS; return g < TG ? g : TG - 1; };
     constexpr int SPAN = (NMFMA * 7) / 8 > 0 ? (NMFMA * 7) / 8 : 1;
     auto body = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
@@ -628,13 +607,7 @@ gemm_kernel(const GemmArgs p)
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
-#ifdef FACT_DBG_WAITCLK
-        const long long dbg_w0 = clock64();
-#endif
         wait_loads_and_barrier<WAIT_N>();
-#ifdef FACT_DBG_WAITCLK
-        dbg_wait += clock64() - dbg_w0;
-#endif
     };
 
     // The prefetch behind the loads of step x covers step x + pf_dist; the steps between the
@@ -647,14 +620,7 @@ gemm_kernel(const GemmArgs p)
         static_for<LOADS>([&](auto i_) __attribute__((always_inline)) { issue_one(c, i_); });
         prefetch_step(s + p.pf_dist);
     });
-#ifdef FACT_DBG_SKIP_LOADS
-    dbg_skip = true;
-#endif
     wait_loads_and_barrier<WAIT_N>();
-#ifdef FACT_DBG_TIMELINE
-    const long long dbg_t1 = wall_clock64();
-    const long long dbg_c1 = clock64();
-#endif
     // unrolled over the ring so that each body knows its slot; an incomplete last round runs
     // phantom (all-zero) steps
     for (int kt = 0; kt < ksteps; kt += STAGES) {
@@ -670,10 +636,6 @@ gemm_kernel(const GemmArgs p)
     // hardware needs between a matrix instruction and the first ordinary read of its result.
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // phantom loads still target LDS
-#ifdef FACT_DBG_TIMELINE
-    const long long dbg_t2 = wall_clock64();
-    const long long dbg_c2 = clock64();
-#endif
 
     // ---- split tail: hand over or collect partial sums ------------------------------------------
     // A tile of the tail is accumulated by tail_g work-groups, one K range each.  All but the last
@@ -728,9 +690,6 @@ gemm_kernel(const GemmArgs p)
     constexpr int EPI_REGION = EPI_ROWS * EPI_PITCH;
     static_assert(lds_total(BM, BN, WGM, WGN, BK, STAGES) <= 160 * 1024 && NWAVES * EPI_REGION <= lds_bytes(BM, BN, WGM, WGN, BK, STAGES) && WTM % EPI_ROWS == 0, "LDS budget");
     __syncthreads();                                            // every wave is done with the operand stages
-#ifdef FACT_DBG_TIMELINE
-    long long dbg_e[6] = {clock64(), 0, 0, 0, 0, 0};
-#endif
     char *region = smem + wave * EPI_REGION;
     const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns
     const int lanes_per_row = out_w / 8;
@@ -829,9 +788,6 @@ gemm_kernel(const GemmArgs p)
             for (int nt = 0; nt < NT; ++nt)
                 *(f32x4_t *)(region + (i * 16 + r16) * EPI_PITCH + (nt * 16 + q * 4) * 4) = acc[pass * EPI_TR + i][nt];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
-#ifdef FACT_DBG_TIMELINE
-        if (pass < 2) dbg_e[1 + 2 * pass] = clock64();
-#endif
         const int total = EPI_ROWS * lanes_per_row;
         if (tail_producer) {
             // partial tile, fp32 row-major [BM][BN] in accumulator column order (gated: gate columns,
@@ -867,9 +823,6 @@ gemm_kernel(const GemmArgs p)
         }
         if (fast) {
             if (gated) fast_pass(pass, std::true_type{}); else fast_pass(pass, std::false_type{});
-#ifdef FACT_DBG_TIMELINE
-            if (pass < 2) dbg_e[2 + 2 * pass] = clock64();
-#endif
             return;
         }
         // General path (tile edges, unaligned C / bias / residual, split-K partials), every access
@@ -988,9 +941,6 @@ gemm_kernel(const GemmArgs p)
                 }
             }
         }
-#ifdef FACT_DBG_TIMELINE
-        if (pass < 2) dbg_e[2 + 2 * pass] = clock64();
-#endif
     });
     if (tail_producer) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // this thread's write-through stores have reached memory
@@ -998,19 +948,6 @@ gemm_kernel(const GemmArgs p)
         if (tid == 0)
             __hip_atomic_store(p.tail_flags + (int64_t)tail_tile * tail_parts + tail_seg, p.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
-#ifdef FACT_DBG_TIMELINE
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    dbg_e[5] = clock64();
-    if (p.P && p.splits <= 1 && tid == 0) {
-        long long *o = (long long *)p.P + (int64_t)(blockIdx.x + gridDim.x * blockIdx.z) * 16;
-        uint32_t hwid;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-        uint32_t xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        o[0] = dbg_t0; o[1] = dbg_t1; o[2] = dbg_t2; o[3] = wall_clock64(); o[4] = hwid; o[5] = xcc; o[6] = dbg_wait; o[7] = dbg_c2 - dbg_c1;
-        for (int e = 0; e < 5; ++e) o[8 + e] = dbg_e[e + 1] - dbg_e[e];
-    }
-#endif
 #else
     (void)p;
 #endif
