@@ -38,8 +38,10 @@ __device__ __forceinline__ float wave_sum(float v)
 
 // One wave per row: the row is read once (16 bytes per lane and piece), kept in registers in fp32,
 // reduced across the wave, normalised and written once.  d <= 8192, a multiple of 8.
+// The number of 512-element pieces is a template parameter: a short row takes few registers, so
+// many waves fit on a SIMD and cover each other's memory latency.
 constexpr int kMaxPieces = 16;           // 16 pieces x 64 lanes x 8 elements
-template <bool RMS>
+template <bool RMS, int PIECES>
 __global__ void __launch_bounds__(256)
 norm_kernel(const uint16_t *X, int64_t ldx, const uint16_t *gamma, const uint16_t *beta, float eps,
             uint16_t *Y, int64_t ldy, int T, int d)
@@ -48,13 +50,12 @@ norm_kernel(const uint16_t *X, int64_t ldx, const uint16_t *gamma, const uint16_
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= T) return;
     const uint16_t *x = X + (int64_t)row * ldx;
-    float v[kMaxPieces][8];
-    const int pieces = (d + 511) / 512;
+    float v[PIECES][8];
     float s = 0.f;
 #pragma unroll
-    for (int p = 0; p < kMaxPieces; ++p) {
+    for (int p = 0; p < PIECES; ++p) {
         const int c = p * 512 + lane * 8;
-        if (p < pieces && c < d) {
+        if (c < d) {
             const u32x4_t w = *(const u32x4_t *)(x + c);
 #pragma unroll
             for (int e = 0; e < 4; ++e) { v[p][2 * e] = lo16(w[e]); v[p][2 * e + 1] = hi16(w[e]); }
@@ -71,9 +72,9 @@ norm_kernel(const uint16_t *X, int64_t ldx, const uint16_t *gamma, const uint16_
     if (!RMS) mean = wave_sum(s) / (float)d;
     float q = 0.f;
 #pragma unroll
-    for (int p = 0; p < kMaxPieces; ++p) {
+    for (int p = 0; p < PIECES; ++p) {
         const int c = p * 512 + lane * 8;
-        if (p < pieces && c < d) {
+        if (c < d) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) { const float t = v[p][e] - mean; q += t * t; }
         }
@@ -81,9 +82,9 @@ norm_kernel(const uint16_t *X, int64_t ldx, const uint16_t *gamma, const uint16_
     const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
     uint16_t *y = Y + (int64_t)row * ldy;
 #pragma unroll
-    for (int p = 0; p < kMaxPieces; ++p) {
+    for (int p = 0; p < PIECES; ++p) {
         const int c = p * 512 + lane * 8;
-        if (p < pieces && c < d) {
+        if (c < d) {
             const u32x4_t g = *(const u32x4_t *)(gamma + c);
             u32x4_t b = {0u, 0u, 0u, 0u};
             if (!RMS && beta) b = *(const u32x4_t *)(beta + c);
@@ -98,39 +99,40 @@ norm_kernel(const uint16_t *X, int64_t ldx, const uint16_t *gamma, const uint16_
 }
 
 // Rotary embedding in place, "rotate-half" pairing: one thread takes 8 consecutive i < D/2 of one
-// (batch entry, token, head): the 16-byte piece at i and the one at i + D/2.
+// (batch entry, token) - the 16-byte piece at i and the one at i + D/2 - and walks a group of up to
+// kRopeHeads heads (blockIdx.y), so the eight sines and cosines are computed once per group.
+constexpr int kRopeHeads = 8;
 __global__ void __launch_bounds__(256)
 rope_kernel(uint16_t *X, int64_t sb, int64_t st, int64_t sh, int B, int T, int H, int D, float log2_base)
 {
     const int per_head = D / 16;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t total = (int64_t)B * T * H * per_head;
+    const int64_t total = (int64_t)B * T * per_head;
     if (gid >= total) return;
     const int piece = (int)(gid % per_head);
-    const int64_t r = gid / per_head;
-    const int h = (int)(r % H);
-    const int64_t bt = r / H;
+    const int64_t bt = gid / per_head;
     const int t = (int)(bt % T), b = (int)(bt / T);
-    uint16_t *p = X + (int64_t)b * sb + (int64_t)t * st + (int64_t)h * sh + piece * 8;
-    const u32x4_t lo = *(const u32x4_t *)p, hi = *(const u32x4_t *)(p + D / 2);
-    float a[8], c[8];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { a[2 * e] = lo16(lo[e]); a[2 * e + 1] = hi16(lo[e]); c[2 * e] = lo16(hi[e]); c[2 * e + 1] = hi16(hi[e]); }
-    float ya[8], yc[8];
+    float sn[8], cs[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int i = piece * 8 + e;
         const float inv_freq = exp2f(-2.0f * (float)i / (float)D * log2_base);
-        float sn, cs;
-        sincosf((float)t * inv_freq, &sn, &cs);
-        ya[e] = a[e] * cs - c[e] * sn;
-        yc[e] = c[e] * cs + a[e] * sn;
+        sincosf((float)t * inv_freq, &sn[e], &cs[e]);
     }
-    u32x4_t olo, ohi;
+    const int h0 = blockIdx.y * kRopeHeads, h1 = h0 + kRopeHeads < H ? h0 + kRopeHeads : H;
+    uint16_t *p = X + (int64_t)b * sb + (int64_t)t * st + (int64_t)h0 * sh + piece * 8;
+    for (int h = h0; h < h1; ++h, p += sh) {
+        const u32x4_t lo = *(const u32x4_t *)p, hi = *(const u32x4_t *)(p + D / 2);
+        u32x4_t olo, ohi;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { olo[e] = pack2(ya[2 * e], ya[2 * e + 1]); ohi[e] = pack2(yc[2 * e], yc[2 * e + 1]); }
-    *(u32x4_t *)p = olo;
-    *(u32x4_t *)(p + D / 2) = ohi;
+        for (int e = 0; e < 4; ++e) {
+            const float a0 = lo16(lo[e]), a1 = hi16(lo[e]), c0 = lo16(hi[e]), c1 = hi16(hi[e]);
+            olo[e] = pack2(a0 * cs[2 * e] - c0 * sn[2 * e], a1 * cs[2 * e + 1] - c1 * sn[2 * e + 1]);
+            ohi[e] = pack2(c0 * cs[2 * e] + a0 * sn[2 * e], c1 * cs[2 * e + 1] + a1 * sn[2 * e + 1]);
+        }
+        *(u32x4_t *)p = olo;
+        *(u32x4_t *)(p + D / 2) = ohi;
+    }
 }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -187,12 +189,14 @@ int fact_norm(int64_t T, int64_t d, const void *X, int64_t ldx, const void *gamm
     if (!(eps >= 0.f)) return FACT_ERR_DIM;
     const unsigned grid = (unsigned)((T + 3) / 4);
     hipStream_t s = (hipStream_t)stream;
-    if (rms)
-        hipLaunchKernelGGL(norm_kernel<true>, dim3(grid), dim3(256), 0, s, (const uint16_t *)X, ldx, (const uint16_t *)gamma,
-                           (const uint16_t *)nullptr, eps, (uint16_t *)Y, ldy, (int)T, (int)d);
-    else
-        hipLaunchKernelGGL(norm_kernel<false>, dim3(grid), dim3(256), 0, s, (const uint16_t *)X, ldx, (const uint16_t *)gamma,
-                           (const uint16_t *)beta, eps, (uint16_t *)Y, ldy, (int)T, (int)d);
+    const int pieces = (int)((d + 511) / 512);
+#define FACT_NORM_LAUNCH(R, P) hipLaunchKernelGGL((norm_kernel<R, P>), dim3(grid), dim3(256), 0, s, (const uint16_t *)X, ldx, \
+        (const uint16_t *)gamma, (const uint16_t *)(R ? nullptr : beta), eps, (uint16_t *)Y, ldy, (int)T, (int)d)
+#define FACT_NORM_PICK(R) do { if (pieces <= 1) FACT_NORM_LAUNCH(R, 1); else if (pieces <= 2) FACT_NORM_LAUNCH(R, 2); \
+        else if (pieces <= 4) FACT_NORM_LAUNCH(R, 4); else if (pieces <= 8) FACT_NORM_LAUNCH(R, 8); else FACT_NORM_LAUNCH(R, 16); } while (0)
+    if (rms) FACT_NORM_PICK(true); else FACT_NORM_PICK(false);
+#undef FACT_NORM_PICK
+#undef FACT_NORM_LAUNCH
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? FACT_OK : fact::record_hip_failure(e, "norm launch");
 }
@@ -205,9 +209,9 @@ int fact_rope(int64_t batch, int64_t T, int64_t n_heads, int64_t head_dim, void 
     if (head_dim <= 0 || head_dim % 16) return FACT_ERR_UNSUPPORTED;
     if (!aligned16(X) || (strides[0] & 7) || (strides[1] & 7) || (strides[2] & 7)) return FACT_ERR_ALIGN;
     if (!(base > 1.0f)) return FACT_ERR_DIM;
-    const int64_t total = batch * T * n_heads * (head_dim / 16);
-    if (batch > 0x7FFFFFFF || T > 0x7FFFFFFF || n_heads > 0x7FFFFFFF || (total + 255) / 256 > 0x7FFFFFFF) return FACT_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (uint16_t *)X,
+    const int64_t total = batch * T * (head_dim / 16);
+    if (batch > 0x7FFFFFFF || T > 0x7FFFFFFF || n_heads > 65535 * kRopeHeads || (total + 255) / 256 > 0x7FFFFFFF) return FACT_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((total + 255) / 256), (unsigned)((n_heads + kRopeHeads - 1) / kRopeHeads)), dim3(256), 0, (hipStream_t)stream, (uint16_t *)X,
                        strides[0], strides[1], strides[2], (int)batch, (int)T, (int)n_heads, (int)head_dim, std::log2(base));
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? FACT_OK : fact::record_hip_failure(e, "rope launch");
