@@ -5,7 +5,7 @@ arguments.  There is no CPU or PyTorch fallback: if the library is not built, lo
 """
 from .binding import (  # noqa: F401
     ACT_GELU_TANH, ACT_NONE, ACT_SILU_GATE, FactError, Epilogue, lib, lib_path,
-    fact_gemm, fact_gemm_batched, fact_gemm_splitk, fact_gemm_splitk_workspace_bytes,
+    fact_gemm, fact_gemm_batched, fact_gemm_splitk, fact_gemm_splitk_workspace_bytes, fact_gemm_f32out_workspace_bytes,
     fact_block_mlp, fact_block_mlp_workspace_bytes, fact_gemm_ex, fact_attention,
     fact_norm, fact_rope, Block, fact_block_scratch_bytes, fact_block_scratch_offsets, fact_block_forward,
     fact_num_configs, fact_config_info, fact_select_config,

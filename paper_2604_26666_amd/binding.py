@@ -27,7 +27,8 @@ class FactError(RuntimeError):
 
 
 class _CEpilogue(ctypes.Structure):
-    _fields_ = [("bias", _ptr), ("residual", _ptr), ("ldr", _i64), ("stride_r", _i64), ("act", ctypes.c_int32)]
+    _fields_ = [("bias", _ptr), ("residual", _ptr), ("ldr", _i64), ("stride_r", _i64), ("act", ctypes.c_int32),
+                ("out_f32", ctypes.c_int32)]
 
 
 class _CBlock(ctypes.Structure):
@@ -61,11 +62,11 @@ class Block:
 class Epilogue:
     """Mirror of the C struct fact_epilogue."""
 
-    def __init__(self, bias=None, residual=None, ldr=0, stride_r=0, act=ACT_NONE):
-        self.bias, self.residual, self.ldr, self.stride_r, self.act = bias, residual, ldr, stride_r, act
+    def __init__(self, bias=None, residual=None, ldr=0, stride_r=0, act=ACT_NONE, out_f32=0):
+        self.bias, self.residual, self.ldr, self.stride_r, self.act, self.out_f32 = bias, residual, ldr, stride_r, act, out_f32
 
     def _c(self):
-        return _CEpilogue(_addr(self.bias), _addr(self.residual), int(self.ldr), int(self.stride_r), int(self.act))
+        return _CEpilogue(_addr(self.bias), _addr(self.residual), int(self.ldr), int(self.stride_r), int(self.act), int(self.out_f32))
 
 
 _lib = None
@@ -91,6 +92,8 @@ def lib():
                                        _int, _ptr, _size, _ptr]
         L.fact_gemm_splitk_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
         L.fact_gemm_splitk_workspace_bytes.restype = _size
+        L.fact_gemm_f32out_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+        L.fact_gemm_f32out_workspace_bytes.restype = _size
         L.fact_block_mlp.argtypes = [_i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr, _int, _ptr, _ptr, _ptr,
                                      _ptr, _ptr, _ptr, _size, _ptr]
         L.fact_block_mlp_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
@@ -172,6 +175,10 @@ def fact_gemm_splitk(M, N, K, A, lda, B, ldb, trans_b, C, ldc, ep, split_k, ws, 
 
 def fact_gemm_splitk_workspace_bytes(M, N, K, split_k):
     return int(lib().fact_gemm_splitk_workspace_bytes(M, N, K, int(split_k)))
+
+
+def fact_gemm_f32out_workspace_bytes(M, N, K, split_k):
+    return int(lib().fact_gemm_f32out_workspace_bytes(M, N, K, split_k))
 
 
 def fact_block_mlp(T, d_model, d_ff, X, W1, W1u, b1, act, W2, b2, R, H, Y, ws, ws_bytes, stream=None):

@@ -61,6 +61,16 @@ __global__ void __launch_bounds__(64) splitk_reduce_kernel(const GemmArgs p)
             if (p.res) zv += (float)p.res[(int64_t)m * p.ldr + n + e];
             v[e] = zv;
         }
+        if (p.out_f32) {                                   // fp32 output: no rounding at all
+            float *cf = (float *)p.C + (int64_t)m * p.ldc + n;
+            if (full && p.vec_store) {
+                *(f32x4_t *)cf = f32x4_t{v[0], v[1], v[2], v[3]};
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (n + e < nout) cf[e] = v[e];
+            }
+            continue;
+        }
         __bf16 *cp = p.C + (int64_t)m * p.ldc + n;
         if (full && p.vec_store) {
             *(u32x2_t *)cp = pack4_bf16(v[0], v[1], v[2], v[3]);

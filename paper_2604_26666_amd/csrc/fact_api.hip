@@ -162,6 +162,8 @@ static int validate(const Problem &q)
     const uintptr_t two = (uintptr_t)q.A | (uintptr_t)q.B | (uintptr_t)q.C | (uintptr_t)q.ep.bias |
                           (uintptr_t)q.ep.residual | (uintptr_t)q.B_up;
     if (two & 1u) return FACT_ERR_ALIGN;
+    if (q.ep.out_f32 != 0 && q.ep.out_f32 != 1) return FACT_ERR_EPILOGUE;
+    if (q.ep.out_f32 && ((uintptr_t)q.C & 3u)) return FACT_ERR_ALIGN;
     return FACT_OK;
 }
 
@@ -232,6 +234,14 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         pl.cfg = -1;
     }
     if (pl.cfg < 0) pl.split = 1;     // the fallback never splits
+    const bool out_f32 = q.ep.out_f32 != 0;
+    if (out_f32) {
+        // fp32 output is written by the reduction pass, so the GEMM always goes through fp32 partials
+        // (one plane when K is not split); no tail split, no batch, no fallback kernel
+        if (q.batch != 1 || pl.cfg < 0 || !allow_table_split) return FACT_ERR_UNSUPPORTED;
+        tail_g = 0;
+        if (pl.split < 1) pl.split = 1;
+    }
 
     GemmArgs a;
     std::memset(&a, 0, sizeof a);
@@ -248,6 +258,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     a.splits = 1;
     a.group_m = pl.group_m;
     // 16-byte vector access to C / residual / bias in the epilogue
+    a.out_f32 = out_f32 ? 1 : 0;
     a.vec_store = (nout % 8 == 0) && q.ldc % 8 == 0 && aligned16(q.C) && q.stride_c % 8 == 0 &&
                   (!q.ep.bias || aligned16(q.ep.bias)) &&
                   (!q.ep.residual || (aligned16(q.ep.residual) && q.ep.ldr % 8 == 0 && q.ep.stride_r % 8 == 0));
@@ -317,9 +328,16 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
             }
         }
     }
+    if (out_f32 && a.splits <= 1) {                   // one fp32 plane
+        const size_t need = (size_t)q.M * (size_t)q.N * sizeof(float);
+        if (!ws) return FACT_ERR_WORKSPACE;
+        if (!aligned16(ws)) return FACT_ERR_ALIGN;
+        if (ws_bytes < need) return FACT_ERR_WORKSPACE;
+        a.P = (float *)ws;
+    }
     e = c.launch(a, q.trans_b != 0, a.splits > 1 ? a.splits : (int)q.batch, stream);
     if (e != hipSuccess) return hip_fail(e, "gemm launch");
-    if (a.splits > 1) {
+    if (a.splits > 1 || out_f32) {
         e = launch_splitk_reduce(a, stream);
         if (e != hipSuccess) return hip_fail(e, "split-K reduce launch");
     }
@@ -409,6 +427,13 @@ size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int spl
     }
     const size_t sk = splitk_ws_bytes(M, N, s);
     return sk > tail_need ? sk : tail_need;
+}
+
+size_t fact_gemm_f32out_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    const size_t a = fact_gemm_splitk_workspace_bytes(M, N, K, split_k < 0 ? 0 : split_k), b = (size_t)M * (size_t)N * sizeof(float);
+    return a > b ? a : b;
 }
 
 int fact_gemm_ex(int64_t batch, int64_t M, int64_t N, int64_t K,

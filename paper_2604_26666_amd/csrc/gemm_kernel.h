@@ -55,6 +55,7 @@ struct GemmArgs {
     int pf_dist;            // L2 prefetch: K steps ahead of the step being loaded into LDS (>= 1)
     // Tail split (the last, partly filled round of tiles): work-groups [0, tail_first) own one tile
     // each; the remaining tiles are shared by tail_g work-groups each, one K range apiece.
+    int out_f32;            // fp32 output (written by the reduce pass; the main kernel then always stores partials)
     int tail_first;         // number of tiles computed whole (== tiles_m * tiles_n when tail_g <= 1)
     int tail_g;             // K ranges per tail tile (0 or 1: off)
     float *tail_ws;         // fp32 partial accumulators, (tail_g - 1) per tail tile
@@ -695,7 +696,7 @@ gemm_kernel(const GemmArgs p)
     const int lanes_per_row = out_w / 8;
     const int n_wave = n0 + wn * out_w;                         // first output column of this wave
     const int m_wave = m0 + wm * WTM;
-    const bool partial = p.splits > 1;
+    const bool partial = p.splits > 1 || p.out_f32;
     float *P = partial ? p.P + (int64_t)z * p.M * p.N : nullptr;
     __bf16 *C = p.C + batch_c;
     const __bf16 *R = p.res ? p.res + batch_r : nullptr;

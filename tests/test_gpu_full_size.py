@@ -198,6 +198,24 @@ def test_paper_large_k_524288():
     assert s["rel_frobenius"] < 3e-3, s
 
 
+def test_paper_large_k_524288_fp32_output():
+    """The paper runs this problem with an fp32 accumulator and an fp32 output (Section 5.2.3)."""
+    c = wl.paper_large_k()
+    m, n, k = 256, 256, 524288
+    need = fact.fact_gemm_f32out_workspace_bytes(m, n, k, 0)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    C = torch.empty(m, n, dtype=torch.float32, device="cuda")
+    ep = fact.Epilogue(out_f32=1)
+    fact.binding.check(fact.fact_gemm_splitk(m, n, k, c["A"].cuda(), k, c["B"].cuda(), n, 0, C, n, ep, 0, ws, need))
+    torch.cuda.synchronize()
+    rows = rows_for(m, 24, "full.p6f", tile=128)
+    r = ref.gemm_epilogue(c["A"], c["B"], False, rows=rows)
+    got = C.cpu().numpy().astype(np.float64)[rows]
+    err = np.abs(got - r.z)
+    assert (err <= 1e-5 + 1e-3 * np.abs(r.z)).all(), float(err.max())             # the paper's criterion (Section 5.1)
+    assert np.linalg.norm(got - r.z) <= 5e-6 * np.linalg.norm(r.z)
+
+
 def test_paper_llama_block_gate_up_32768_tokens():
     c = wl.paper_block("llama")
     t, d, dff = c["tokens"], c["d"], c["dff"]

@@ -352,3 +352,63 @@ def test_tail_split_refusals():
     B = wl.normal((256, 128), 1.0, "tr.B")
     with pytest.raises(Exception):
         G().gemm(A, B, 1, cfg=3, split=-2)        # 2 K steps: too little K per range
+
+
+# ---- fp32 output (written by the reduction pass) -----------------------------------------------------
+
+def _f32_call(A, B, trans_b, split, bias=None, residual=None, act=fact.ACT_NONE, cfg=-1):
+    M, K = A.shape
+    N = B.shape[0] if trans_b else B.shape[1]
+    nout = N // 2 if act == fact.ACT_SILU_GATE else N
+    C = torch.full((M + 1, nout + 4), float("nan"), dtype=torch.float32, device="cuda")
+    need = fact.fact_gemm_f32out_workspace_bytes(M, N, K, split)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda").fill_(0xA5)
+    ep = fact.Epilogue(bias=G().to_dev(bias), residual=G().to_dev(residual), ldr=nout, act=act, out_f32=1)
+    Ad, Bd = A.cuda(), B.cuda()
+    if cfg >= 0:
+        rc = fact.fact_gemm_ex(1, M, N, K, Ad, K, 0, Bd, B.shape[1], 0, trans_b, C, nout + 4, 0, ep, cfg, split, 0, ws, need)
+    else:
+        rc = fact.fact_gemm_splitk(M, N, K, Ad, K, Bd, B.shape[1], trans_b, C, nout + 4, ep, split, ws, need)
+    fact.binding.check(rc, f"fp32-output GEMM split={split}")
+    torch.cuda.synchronize()
+    out = C.cpu().numpy()
+    assert np.isnan(out[M]).all() and np.isnan(out[:, nout:]).all(), "wrote outside C"
+    return out[:M, :nout].astype(np.float64)
+
+
+def _assert_f32_close(got, r, what):
+    # the paper's own criterion for an fp32 result (Section 5.1: rtol 1e-3, atol 1e-5), and far tighter in norm
+    err = np.abs(got - r.z)
+    assert (err <= 1e-5 + 1e-3 * np.abs(r.z)).all(), (what, float(err.max()))
+    assert np.linalg.norm(got - r.z) <= 2e-6 * np.linalg.norm(r.z) + 1e-12, (what, float(np.linalg.norm(got - r.z) / np.linalg.norm(r.z)))
+
+
+@pytest.mark.parametrize("split", [1, 4, 0])
+def test_fp32_output_large_k(split):
+    M, N, K = 256, 264, 16384
+    A = wl.normal((M, K), K ** -0.5, "f32.A")
+    B = wl.normal((K, N), K ** -0.5, "f32.B")
+    r = ref.gemm_epilogue(A, B, False)
+    _assert_f32_close(_f32_call(A, B, 0, split), r, f"fp32 out split {split}")
+
+
+def test_fp32_output_with_epilogue_and_exact_integers():
+    M, N, K = 200, 256, 512
+    A = wl.small_int((M, K), -2, 2, "f32.Ai")
+    W = wl.small_int((N, K), -2, 2, "f32.Wi")
+    bias = wl.normal((N,), 1.0, "f32.b")
+    res = wl.normal((M, N), 1.0, "f32.R")
+    r = ref.gemm_epilogue(A, W, True, bias=bias, residual=res)
+    got = _f32_call(A, W, 1, 2, bias=bias, residual=res, cfg=3)
+    assert np.array_equal(got, r.z.astype(np.float32).astype(np.float64))      # integers + bf16 bias + bf16 residual: exact in fp32
+    r = ref.gemm_epilogue(A, W, True, bias=bias, act=fact.ACT_GELU_TANH)
+    _assert_f32_close(_f32_call(A, W, 1, 1, bias=bias, act=fact.ACT_GELU_TANH), r, "fp32 out GELU")
+    assert np.abs(_f32_call(A, W, 1, 1, bias=bias, act=fact.ACT_GELU_TANH) - r.z).max() < 5e-4     # fast-math GELU, not a rounding to bf16
+
+
+def test_fp32_output_refusals():
+    A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    C = torch.zeros(64, 64, dtype=torch.float32, device="cuda")
+    ep = fact.Epilogue(out_f32=1)
+    assert fact.fact_gemm(64, 64, 64, A, 64, A, 64, 0, C, 64, ep) == -7                      # only with a workspace
+    assert fact.fact_gemm_splitk(64, 64, 64, A, 64, A, 64, 0, C, 64, ep, 1, None, 0) == -6
