@@ -68,7 +68,7 @@ def _regs(operand):
 
 
 def check_asm_mfma_hazards(asm_text, kernel_filter="attn_fwd_kernel"):
-    """The attention kernel issues its MFMAs through inline asm, so the compiler keeps none of the
+    """The GEMM and attention kernels issue their MFMAs through inline asm, so the compiler keeps none of the
     wait states the matrix pipe needs around them.  Two cases are checked in the generated code:
     a vector-ALU instruction writing a register that one of the next two instructions, an asm
     MFMA, reads as an operand (seen on the GPU: the MFMA used the register's old contents); and a
@@ -139,9 +139,19 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
                                               "-c", os.path.join(CSRC, "inst.hip"), "-o", obj]))
     for name in ("aux_kernels", "fact_api", "attention", "block"):
         obj = os.path.join(OBJ, name + ".o")
-        units.append((obj, [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, name + ".hip"), "-o", obj]))
+        units.append((obj, [HIPCC] + FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, name + ".hip"), "-o", obj]))
+    # the same kernels once more as assembly text, for the check of the inline-asm MFMAs below
+    asm_units = []
+    for (cid, bm, bn, wm, wn, bk, st) in configs():
+        asm_units.append((os.path.join(OBJ, f"inst{cid}.s"), "gemm_kernel",
+                          [HIPCC] + FLAGS + [f"-DFACT_ID={cid}", f"-DFACT_BM={bm}", f"-DFACT_BN={bn}", f"-DFACT_WM={wm}", f"-DFACT_WN={wn}",
+                                             f"-DFACT_BK={bk}", f"-DFACT_STAGES={st}", "--cuda-device-only", "-S",
+                                             os.path.join(CSRC, "inst.hip"), "-o", os.path.join(OBJ, f"inst{cid}.s")]))
+    asm_units.append((os.path.join(OBJ, "attention.s"), "attn_fwd_kernel",
+                      [HIPCC] + FLAGS + ["--cuda-device-only", "-S", os.path.join(CSRC, "attention.hip"), "-o", os.path.join(OBJ, "attention.s")]))
     usage = {}
     with ThreadPoolExecutor(max_workers=jobs) as ex:
+        asm_jobs = [ex.submit(_run, u[2]) for u in asm_units]
         for out in ex.map(lambda u: _run(u[1]), units):
             usage.update(resource_usage(out))
             rest = "\n".join(l for l in out.splitlines() if "kernel-resource-usage" not in l and not re.match(r"\s*(\d+ \| |\| |In file included)", l))
@@ -149,22 +159,25 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
                 print(rest)
     # The main kernel issues LDS reads through inline asm the compiler does not track: a spilled
     # fragment register would be stored before its data has arrived.  Refuse such a build.
-    bad = {k: v for k, v in usage.items() if "gemm_kernel" in k and (v.get("ScratchSize [bytes/lane]", 0) or v.get("VGPRs Spill", 0))}
+        for j in asm_jobs:
+            j.result()
+    bad = {k: v for k, v in usage.items() if ("gemm_kernel" in k or "attn_fwd_kernel" in k)
+           and (v.get("ScratchSize [bytes/lane]", 0) or v.get("VGPRs Spill", 0))}
     if verbose:
         for k, v in sorted(usage.items()):
-            if "gemm_kernel" in k:
+            if "gemm_kernel" in k or "attn_fwd_kernel" in k:
                 print(f"{k}: VGPRs {v.get('VGPRs')} AGPRs {v.get('AGPRs')} SGPR spills {v.get('SGPRs Spill')} scratch {v.get('ScratchSize [bytes/lane]')}")
     if bad and not os.environ.get("FACT_ALLOW_SPILLS"):
-        raise RuntimeError("register spills in the main kernel (would break the untracked LDS reads): " +
+        raise RuntimeError("register spills in a kernel with untracked LDS reads (a spill could store a register before its data arrives): " +
                            "; ".join(f"{k}: {v}" for k, v in bad.items()))
-    # the attention kernel's inline-asm MFMAs: check the generated code for the wait-state cases
-    asm_path = os.path.join(obj_dir, "attention.s")
-    _run([HIPCC] + FLAGS + ["--cuda-device-only", "-S", os.path.join(CSRC, "attention.hip"), "-o", asm_path])
-    hazards = check_asm_mfma_hazards(open(asm_path).read())
+    # inline-asm MFMAs (GEMM and attention kernels): check the generated code for the wait-state cases
+    hazards = []
+    for path, kernel, _ in asm_units:
+        hazards += check_asm_mfma_hazards(open(path).read(), kernel_filter=kernel)
     if hazards and not os.environ.get("FACT_ALLOW_ASM_HAZARDS"):      # (override for timing experiments only)
-        raise RuntimeError("inline-asm MFMA hazards in the attention kernel:\n  " + "\n  ".join(hazards[:20]))
+        raise RuntimeError("inline-asm MFMA hazards:\n  " + "\n  ".join(hazards[:20]))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + [u[0] for u in units])
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
