@@ -108,3 +108,32 @@ def test_select_config_host_logic():
     assert fact.fact_select_config(1, 64, 60, 64, 1, 0)[1] >= 0
     assert fact.fact_select_config(0, 1, 1, 1, 0, 0)[0] == -2
     assert fact.fact_select_config(1, 8, 9, 8, 1, 2)[0] == -5
+
+
+def test_new_entry_points_validate_on_the_host_before_any_gpu_call():
+    """Argument validation comes before anything touches the GPU, so it can be exercised here."""
+    st = (64 * 192, 192, 64)
+    p = 4096                                   # a non-NULL, 16-byte aligned number; never dereferenced
+    att = lambda **k: fact.fact_attention(k.get("B", 1), k.get("T", 64), k.get("hq", 2), k.get("hkv", 1), k.get("D", 64),
+                                          k.get("Q", p), k.get("qs", st), p, st, p, st, p, (64 * 128, 128, 64), k.get("causal", 1), 0.0, 0)
+    assert att(D=96) == -7 and att(hq=3, hkv=2) == -2 and att(Q=None) == -1 and att(Q=p + 2) == -3
+    assert att(qs=(64 * 192, 32, 64)) == -2 and att(causal=3) == -4 and att(T=0) == -2
+    assert fact.fact_norm(16, 60, p, 64, p, None, 1e-5, 1, p, 64, 0) == -7
+    assert fact.fact_norm(16, 64, p, 32, p, None, 1e-5, 1, p, 64, 0) == -2
+    assert fact.fact_norm(16, 64, p, 64, p, p, 1e-5, 1, p, 64, 0) == -5
+    assert fact.fact_norm(16, 16384, p, 16384, p, None, 1e-5, 0, p, 16384, 0) == -7
+    assert fact.fact_rope(1, 64, 3, 24, p, st, 10000.0, 0) == -7
+    assert fact.fact_rope(1, 64, 3, 64, p, st, 0.5, 0) == -2
+    assert fact.fact_rope(1, 64, 3, 64, None, st, 10000.0, 0) == -1
+    w = dict(norm1_g=p, norm2_g=p, Wqkv=p, Wo=p, W1=p, W2=p)
+    ok = fact.Block(2, 128, 256, 4, 2, 64, 512, 1, fact.ACT_NONE, **w)
+    n = fact.fact_block_scratch_bytes(ok)
+    T, nqkv = 256, (4 + 2 * 2) * 64
+    assert n >= 2 * (3 * T * 256 + T * nqkv + T * 256 + T * 512) and n % 256 == 0
+    offs = fact.fact_block_scratch_offsets(ok)
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and offs[0] == 0
+    assert fact.fact_block_scratch_bytes(fact.Block(2, 128, 256, 4, 3, 64, 512, 1, fact.ACT_NONE, **w)) == 0
+    assert fact.fact_block_forward(ok, p, p, p, n - 1, 0) == -6
+    assert fact.fact_block_forward(fact.Block(2, 128, 256, 4, 2, 64, 512, 1, fact.ACT_SILU_GATE, **w), p, p, p, n, 0) == -5
+    assert fact.fact_gemm_f32out_workspace_bytes(256, 256, 4096, 1) == 256 * 256 * 4
+    assert fact.fact_gemm_f32out_workspace_bytes(256, 256, 4096, 4) == 4 * 256 * 256 * 4
