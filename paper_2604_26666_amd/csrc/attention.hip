@@ -30,6 +30,20 @@ static hipError_t launch(AttnArgs a, hipStream_t stream)
     constexpr int BQ = NW * 64;
     a.q_blocks = (a.T + BQ - 1) / BQ;
     a.total = a.q_blocks * a.Hq * a.B;
+    // Pairs per group of the work-group order (see the kernel): a multiple of 4, so that each of an
+    // XCD's shader engines gets the same mix of heavy and light work-groups; as large as the K/V of
+    // the group's heads still fits an XCD's L2 (4 MB), which also starts the heavy work-groups early.
+    {
+        const int pairs = a.Hq * a.B, per = (pairs & 7) == 0 ? pairs >> 3 : pairs, G = a.Hq / a.Hkv;
+        int best = 0, smallest = 0;
+        for (int r = 4; r <= per; r += 4) {
+            if (per % r) continue;
+            if (!smallest) smallest = r;
+            const int64_t kv_heads = r >= G ? (r + G - 1) / G : 1;
+            if (kv_heads * a.T * D * 4 <= (int64_t)4 << 20) best = r;
+        }
+        a.group = best ? best : smallest ? smallest : per;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)a.total), dim3(NW * 64), lds, stream, a);
     return hipGetLastError();
 }
@@ -74,7 +88,7 @@ extern "C" int fact_attention(int64_t batch, int64_t T, int64_t n_q_heads, int64
     a.causal = causal;
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)head_dim);
     a.scale_log2 = sc * 1.4426950408889634f;
-    a.q_blocks = 0; a.total = 0;
+    a.q_blocks = 0; a.total = 0; a.group = 1;
 
     // 256 queries per work-group when that still gives every compute unit two work-groups;
     // otherwise 128 (two of those fit on a compute unit)

@@ -63,6 +63,7 @@ struct AttnArgs {
     float scale_log2;       // softmax scale * log2(e)
     int q_blocks;           // ceil(T / BQ)
     int total;              // q_blocks * Hq * B work-groups
+    int group;              // (batch, query head) pairs per group of the work-group order; divides the pairs of an XCD
 };
 
 constexpr uint32_t kBufFlags = 0x00020000u;      // raw buffer descriptor word 3 (32-bit data format)
@@ -142,18 +143,31 @@ attn_fwd_kernel(const AttnArgs p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r16 = lane & 15, q4 = lane >> 4;
 
-    // Work-group -> (batch, key/value head, query block, query head).  Consecutive work-group ids
-    // go to different XCDs (each with its own L2): id % 8 picks the XCD and every XCD gets one
-    // contiguous range of the order below, in which the query heads and query blocks that read
-    // the same K/V follow each other, heaviest (last) query block first.
-    int v = blockIdx.x;
-    if ((p.total & 7) == 0) v = (v & 7) * (p.total >> 3) + (v >> 3);
+    // Work-group -> (batch, key/value head, query head, query block).  Consecutive work-group ids go
+    // to different XCDs (each with its own L2): id % 8 picks the XCD, and every XCD gets its own
+    // eighth of the (batch, head) pairs, the query heads that read the same K/V next to each other.
+    // Within an XCD the pairs come in groups of p.group: a group's work-groups are ordered by query
+    // block, the heaviest (last) first, all pairs of the group before the next lighter block.  So
+    // runs of p.group consecutive work-groups carry the same amount of work, and the K/V of one
+    // group (sized by the host to fit the L2) is what the XCD reads at any one time.
+    // (The hardware hands consecutive work-groups of an XCD to its shader engines in turn and in
+    // order; with a heavy .. light pattern whose period matched that turn, one engine got all the
+    // heavy work-groups and the others idled between theirs - measured 30% of the time.)
     const int G = p.Hq / p.Hkv;
-    const int per_kv = p.q_blocks * G;
-    const int kv = v / per_kv, rest = v - kv * per_kv;
+    const int pairs = p.total / p.q_blocks;                    // batch * query heads
+    int qb, pair;
+    {
+        const int v = blockIdx.x;
+        const bool split = (pairs & 7) == 0;                   // else: one sequence over all pairs
+        const int pos = split ? v >> 3 : v, first = split ? (v & 7) * (pairs >> 3) : 0;
+        const int per_group = p.group * p.q_blocks;
+        const int gi = pos / per_group, within = pos - gi * per_group;
+        qb = p.q_blocks - 1 - within / p.group;
+        pair = first + gi * p.group + within % p.group;
+    }
+    const int kv = pair / G;
     const int b = kv / p.Hkv, hk = kv - b * p.Hkv;
-    const int qb = p.q_blocks - 1 - rest / G;
-    const int hq = hk * G + rest % G;
+    const int hq = hk * G + (pair - kv * G);
     const int q0 = qb * BQ, q0w = q0 + wave * QW;
     const int T = p.T;
 
