@@ -72,12 +72,17 @@ __device__ __forceinline__ float sigmoid_fast(float t)
     return __builtin_amdgcn_rcpf(1.0f + __expf(-t));
 }
 
-// tanh-form GELU: 0.5 z (1 + tanh(u)) = z * sigmoid(2u), u = sqrt(2/pi) (z + 0.044715 z^3)
+// tanh-form GELU: 0.5 z (1 + tanh(u)) = z * sigmoid(2u) = z / (1 + e^(-2u)), u = sqrt(2/pi) (z + 0.044715 z^3).
+// Written as -2u log2(e) = z (k0 + k1 z^2) so that an element costs five plain vector instructions
+// and the two transcendental ones (the epilogue of a 256 x 256 tile is 128 elements per lane, all
+// of them vector-ALU time that no MFMA overlaps).  For z -> -inf the exponential overflows to
+// +inf and the result is -0; for z -> +inf it underflows to 0 and the result is z.
 __device__ __forceinline__ float gelu_tanh(float z)
 {
-    const float c = 0.7978845608028654f;
-    float u = c * (z + 0.044715f * z * z * z);
-    return z * sigmoid_fast(2.0f * u);
+    constexpr float k0 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+    constexpr float k1 = k0 * 0.044715f;
+    const float t = __builtin_fmaf(z * z, k1, k0) * z;
+    return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
 __device__ __forceinline__ float silu(float z) { return z * sigmoid_fast(z); }
