@@ -90,13 +90,16 @@ extern "C" int fact_attention(int64_t batch, int64_t T, int64_t n_q_heads, int64
     a.scale_log2 = sc * 1.4426950408889634f;
     a.q_blocks = 0; a.total = 0; a.group = 1;
 
-    // 256 queries per work-group when that still gives every compute unit two work-groups;
-    // otherwise 128 (two of those fit on a compute unit)
+    // 128 queries per work-group (two waves; two work-groups share a compute unit, and fewer of a
+    // causal work-group's key blocks lie partly above the diagonal).  256 queries halve the K/V
+    // traffic into LDS per query, which pays only for long sequences of wide heads (measured: from
+    // T = 8192 at head_dim 128, 3-4%; below that the smaller work-groups are 5-20% faster), and
+    // only with enough work-groups to give every compute unit two.
     const int64_t wgs256 = ((T + 255) / 256) * n_q_heads * batch;
-    const bool four = wgs256 >= 512;
+    const bool four = head_dim == 128 && T >= 8192 && wgs256 >= 512;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     if (head_dim == 128) e = four ? launch<128, 4>(a, s) : launch<128, 2>(a, s);
-    else e = four ? launch<64, 4>(a, s) : launch<64, 2>(a, s);
+    else e = launch<64, 2>(a, s);
     return e == hipSuccess ? FACT_OK : fact::record_hip_failure(e, "attention launch");
 }

@@ -164,6 +164,14 @@ def test_attention_gpt_shape_8x1024():
     _attention_full(wl.attention4(), [(0, 0), (0, 11), (3, 5), (7, 0), (7, 11)])
 
 
+def test_attention_long_sequence_256_query_work_groups():
+    # head_dim 128 from 8192 tokens on is where the library switches to 256 queries (four waves) per
+    # work-group; T is not a multiple of the key block, so the last query block and key block are ragged
+    w = {"qkv": wl.attention_qkv(1, 8229, 16, 4, 128, 1.28, "attlong.qkv"), "batch": 1, "tokens": 8229,
+         "q_heads": 16, "kv_heads": 4, "head_dim": 128}
+    _attention_full(w, [(0, 0), (0, 7), (0, 15)])
+
+
 # ---- the paper's own problem shapes (Section 5.1), the second workload ----------------------------
 
 def test_paper_square_4096():
