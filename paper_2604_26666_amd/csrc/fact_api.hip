@@ -110,6 +110,7 @@ static Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_
     for (int i = 0; i < kNumConfigs; ++i) {
         const ConfigDesc &c = g_configs[i];
         if (gated && !c.gate_capable()) continue;
+        if (!c.serves(trans_b)) continue;
         int max_split = 1;
         if (allow_split && batch == 1) {
             max_split = (int)(K / 1024);
@@ -212,6 +213,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         if (cfg_id >= kNumConfigs) return FACT_ERR_UNSUPPORTED;
         if (!fast_dims_ok(q.M, q.N, q.K, q.trans_b)) return FACT_ERR_UNSUPPORTED;
         if (gated && !g_configs[cfg_id].gate_capable()) return FACT_ERR_UNSUPPORTED;
+        if (!g_configs[cfg_id].serves(q.trans_b)) return FACT_ERR_UNSUPPORTED;
         pl.cfg = cfg_id;
         if (split <= 0) pl.split = 1;
     }

@@ -150,6 +150,11 @@ __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int
 template <int N, class F>
 __device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
+// B given as [K][N] (trans_b = 0) is staged with loads that cover whole K-rows of the tile:
+// the tile's N must hold a power-of-two number of 16-byte chunks.  Other tile widths serve
+// trans_b = 1 only.
+constexpr bool plain_b_supported(int bn) { return 64 % (bn / 8) == 0; }
+
 // Epilogue staging geometry (shared with the host side, which sizes the dynamic LDS): each wave
 // transposes its accumulators through an fp32 region of epi_rows rows with this pitch.
 constexpr int epi_pitch(int wtn) { return wtn * 4 + 16; }
@@ -280,7 +285,8 @@ gemm_kernel(const GemmArgs p)
     // num_records that much larger) so that the offset never goes negative.
     auto clamp31 = [](int64_t v) -> uint32_t { return v > 0x7FFFFFFF ? 0x7FFFFFFFu : (uint32_t)v; };
     constexpr uint32_t kOffBias = 3072;
-    constexpr int A_RUN = A_LD < 4 ? A_LD : 4, B_RUN = B_LD < 4 ? B_LD : 4;
+    constexpr auto run_of = [](int ld) { return ld % 4 == 0 ? 4 : ld % 3 == 0 ? 3 : ld % 2 == 0 ? 2 : 1; };
+    constexpr int A_RUN = A_LD < 4 ? A_LD : run_of(A_LD), B_RUN = B_LD < 4 ? B_LD : run_of(B_LD);
     static_assert(A_LD % A_RUN == 0 && B_LD % B_RUN == 0, "loads split into whole runs");
 
     // K-contiguous rows: 8 rows x 8 chunks per load; lane -> row lane/8 of the block, chunk
@@ -718,11 +724,13 @@ gemm_kernel(const GemmArgs p)
     auto fast_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
         constexpr bool GATED = decltype(gated_tag)::value;
         constexpr int OUT_W = GATED ? WTN / 2 : WTN;
-        constexpr int LPR = OUT_W / 8;                              // lanes per row
-        constexpr int TOTAL = EPI_ROWS * LPR;
+        constexpr int LPR_USED = OUT_W / 8;                         // lanes a row needs
+        constexpr int LPR = LPR_USED <= 1 ? 1 : LPR_USED <= 2 ? 2 : LPR_USED <= 4 ? 4 : LPR_USED <= 8 ? 8 : LPR_USED <= 16 ? 16 : 32;
+        constexpr int TOTAL = EPI_ROWS * LPR;                       // (a power of two of lanes is set aside per row)
         constexpr int FU = NWAVES > 4 ? 2 : 4;                      // row-chunks per lane and batch
         static_assert(64 % LPR == 0 && TOTAL % 64 == 0, "a lane keeps its columns; batches are whole waves");
         const int c8 = lane % LPR;
+        if constexpr (LPR != LPR_USED) { if (c8 >= LPR_USED) return; }      // 96- or 48-wide wave tiles: the lanes past a row's end idle
         const int n = n_wave + c8 * 8;
         float bv[8];
 #pragma unroll

@@ -10,6 +10,10 @@ namespace fact {
 template <bool TRANS_B>
 static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t stream)
 {
+    if constexpr (!TRANS_B && !plain_b_supported(FACT_BN)) {
+        (void)args; (void)grid_z; (void)stream;
+        return hipErrorInvalidConfiguration;          // (the host side never selects such a tile for this layout)
+    } else {
     auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES>;
     constexpr int lds = lds_total(FACT_BM, FACT_BN, FACT_WM, FACT_WN, FACT_BK, FACT_STAGES);
     static bool attr_set[64] = {};
@@ -28,6 +32,7 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
     dim3 block(FACT_WM * FACT_WN * 64, 1, 1);
     hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
     return hipGetLastError();
+    }
 }
 
 hipError_t FACT_CAT(fact_launch_cfg, FACT_ID)(const GemmArgs &args, bool trans_b, int grid_z, hipStream_t stream)

@@ -19,6 +19,7 @@ struct ConfigDesc {
     int lds_bytes() const { return fact::lds_total(bm, bn, wm, wn, bk, stages); }
     int threads() const { return wm * wn * 64; }
     bool gate_capable() const { return true; }      // every wave tile has an even number of MFMA tiles along N
+    bool serves(int trans_b) const { return trans_b || plain_b_supported(bn); }      // 192-wide tiles: B as [N][K] only
 };
 
 // Split-K reduction + epilogue, and the guarded fallback GEMM (aux_kernels.hip).

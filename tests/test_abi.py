@@ -86,6 +86,8 @@ def test_validation_rejects_before_any_launch():
     ex = lambda cfg, N=64, tb=0: fact.fact_gemm_ex(1, 64, N, 64, p, 64, 0, p, 64, 0, tb, p, 64, 0, None, cfg, 0, 0, None, 0, 0)
     assert ex(n) == -7
     assert ex(0, N=60) == -7          # N % 8 != 0 with trans_b = 0 cannot use the MFMA kernel
+    wide192 = [c for c in range(n) if fact.fact_config_info(c)[1] == 192]
+    assert wide192 and all(ex(c, tb=0) == -7 for c in wide192)       # 192-wide tiles stage B as [N][K] only
 
 
 def test_select_config_host_logic():
