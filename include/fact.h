@@ -77,10 +77,11 @@ typedef struct fact_epilogue {
     int64_t ldr;
     int64_t stride_r;
     int32_t act;
-    int32_t out_f32;        /* 1: C is fp32 [M][ldc] (ldc in fp32 elements), written without rounding: the paper's
-                               choice for its large-K problem (Section 5.2.3: fp32 accumulator AND output).  Only
-                               through fact_gemm_splitk / fact_gemm_ex with a workspace of
-                               fact_gemm_f32out_workspace_bytes(); FACT_ERR_UNSUPPORTED elsewhere. */
+    int32_t out_f32;        /* 1: C is fp32 [M][ldc] (ldc and stride_c in fp32 elements, C 4-byte aligned), written
+                               without rounding: the paper's choice for its large-K problem (Section 5.2.3: fp32
+                               accumulator AND output).  Every entry point takes it; with K whole the GEMM's own
+                               epilogue writes the fp32 result, with K split (fact_gemm_splitk / fact_gemm_ex and
+                               a workspace of fact_gemm_f32out_workspace_bytes()) the reduction pass does. */
 } fact_epilogue;
 
 /* ---- entry points --------------------------------------------------------------------- */
@@ -131,8 +132,8 @@ int fact_gemm_splitk(int64_t M, int64_t N, int64_t K,
  * of -split_k ranges, largest need over the tile configurations).  Returns 0 when no
  * workspace is needed or the arguments are invalid. */
 size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k);
-/* Workspace of the same call with ep->out_f32 = 1: the fp32 result always passes through fp32
- * partial planes (one plane when K is not split) and the reduction pass writes it. */
+/* Workspace of the same call with ep->out_f32 = 1: the fp32 partial planes when K is split
+ * (split_k > 1, or 0 and the table splits this shape), else 0. */
 size_t fact_gemm_f32out_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k);
 
 /*

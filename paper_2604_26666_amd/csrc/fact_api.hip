@@ -236,13 +236,15 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         pl.cfg = -1;
     }
     if (pl.cfg < 0) pl.split = 1;     // the fallback never splits
-    const bool out_f32 = q.ep.out_f32 != 0;
+    // fp32 output: with K whole the main kernel's epilogue writes it, unrounded; with K split the
+    // reduction pass does (no batch then, as for any split).  No tail split, no fallback kernel.
+    bool out_f32 = q.ep.out_f32 != 0, c_f32 = false;
     if (out_f32) {
-        // fp32 output is written by the reduction pass, so the GEMM always goes through fp32 partials
-        // (one plane when K is not split); no tail split, no batch, no fallback kernel
-        if (q.batch != 1 || pl.cfg < 0 || !allow_table_split) return FACT_ERR_UNSUPPORTED;
+        if (pl.cfg < 0) return FACT_ERR_UNSUPPORTED;
         tail_g = 0;
         if (pl.split < 1) pl.split = 1;
+        if (pl.split == 1) { c_f32 = true; out_f32 = false; }
+        else if (q.batch != 1 || !allow_table_split) return FACT_ERR_UNSUPPORTED;
     }
 
     GemmArgs a;
@@ -261,7 +263,9 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     a.group_m = pl.group_m;
     // 16-byte vector access to C / residual / bias in the epilogue
     a.out_f32 = out_f32 ? 1 : 0;
-    a.vec_store = (nout % 8 == 0) && q.ldc % 8 == 0 && aligned16(q.C) && q.stride_c % 8 == 0 &&
+    a.c_f32 = c_f32 ? 1 : 0;
+    // (an fp32 row of 8 columns is two 16-byte pieces: ldc and the batch stride in multiples of 4)
+    a.vec_store = (nout % 8 == 0) && q.ldc % (c_f32 ? 4 : 8) == 0 && aligned16(q.C) && q.stride_c % (c_f32 ? 4 : 8) == 0 &&
                   (!q.ep.bias || aligned16(q.ep.bias)) &&
                   (!q.ep.residual || (aligned16(q.ep.residual) && q.ep.ldr % 8 == 0 && q.ep.stride_r % 8 == 0));
 
@@ -434,8 +438,13 @@ size_t fact_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int spl
 size_t fact_gemm_f32out_workspace_bytes(int64_t M, int64_t N, int64_t K, int split_k)
 {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    const size_t a = fact_gemm_splitk_workspace_bytes(M, N, K, split_k < 0 ? 0 : split_k), b = (size_t)M * (size_t)N * sizeof(float);
-    return a > b ? a : b;
+    int s = split_k < 0 ? 0 : split_k;
+    if (s == 0)                                       // the table's split-K factor, over both layouts (tail splits do not apply)
+        for (int tb = 0; tb < 2; ++tb) {
+            const Plan pl = make_plan(1, M, N, K, tb, FACT_ACT_NONE, true);
+            if (pl.cfg >= 0 && pl.split > s) s = pl.split;
+        }
+    return splitk_ws_bytes(M, N, s);                  // nothing when K stays whole: the main kernel writes the fp32 result
 }
 
 int fact_gemm_ex(int64_t batch, int64_t M, int64_t N, int64_t K,

@@ -56,6 +56,7 @@ struct GemmArgs {
     // Tail split (the last, partly filled round of tiles): work-groups [0, tail_first) own one tile
     // each; the remaining tiles are shared by tail_g work-groups each, one K range apiece.
     int out_f32;            // fp32 output (written by the reduce pass; the main kernel then always stores partials)
+    int c_f32;              // C holds fp32 and this kernel's epilogue writes it, unrounded (K not split)
     int tail_first;         // number of tiles computed whole (== tiles_m * tiles_n when tail_g <= 1)
     int tail_g;             // K ranges per tail tile (0 or 1: off)
     float *tail_ws;         // fp32 partial accumulators, (tail_g - 1) per tail tile
@@ -710,6 +711,7 @@ gemm_kernel(const GemmArgs p)
     const bool partial = p.splits > 1 || p.out_f32;
     float *P = partial ? p.P + (int64_t)z * p.M * p.N : nullptr;
     __bf16 *C = p.C + batch_c;
+    float *Cf = (float *)p.C + batch_c;                         // the same matrix when it holds fp32 (c_f32)
     const __bf16 *R = p.res ? p.res + batch_r : nullptr;
 
     // Fast path: the wave's whole tile lies inside C and everything allows 16-byte access.  Straight
@@ -780,6 +782,12 @@ gemm_kernel(const GemmArgs p)
                     if (R) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                    }
+                    if (p.c_f32) {
+                        float *cf = Cf + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n;
+                        *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
+                        *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
+                        continue;
                     }
                     u32x4_t o;
 #pragma unroll
@@ -940,6 +948,18 @@ gemm_kernel(const GemmArgs p)
                         for (int e = 0; e < 8; ++e)
                             if (n + e < nout) z[e] += (float)rp[e];
                     }
+                }
+                if (p.c_f32) {
+                    float *cf = Cf + (int64_t)m * p.ldc + n;
+                    if (vec[j]) {
+                        *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
+                        *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < nout) cf[e] = z[e];
+                    }
+                    continue;
                 }
                 __bf16 *cp = C + (int64_t)m * p.ldc + n;
                 if (vec[j]) {

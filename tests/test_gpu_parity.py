@@ -360,7 +360,7 @@ def test_tail_split_refusals():
         G().gemm(A, B, 1, cfg=3, split=-2)        # 2 K steps: too little K per range
 
 
-# ---- fp32 output (written by the reduction pass) -----------------------------------------------------
+# ---- fp32 output (by the main kernel's epilogue; by the reduction pass when K is split) ------------------
 
 def _f32_call(A, B, trans_b, split, bias=None, residual=None, act=fact.ACT_NONE, cfg=-1):
     M, K = A.shape
@@ -368,7 +368,7 @@ def _f32_call(A, B, trans_b, split, bias=None, residual=None, act=fact.ACT_NONE,
     nout = N // 2 if act == fact.ACT_SILU_GATE else N
     C = torch.full((M + 1, nout + 4), float("nan"), dtype=torch.float32, device="cuda")
     need = fact.fact_gemm_f32out_workspace_bytes(M, N, K, split)
-    ws = torch.empty(need, dtype=torch.uint8, device="cuda").fill_(0xA5)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda").fill_(0xA5)
     ep = fact.Epilogue(bias=G().to_dev(bias), residual=G().to_dev(residual), ldr=nout, act=act, out_f32=1)
     Ad, Bd = A.cuda(), B.cuda()
     if cfg >= 0:
@@ -412,9 +412,39 @@ def test_fp32_output_with_epilogue_and_exact_integers():
     assert np.abs(_f32_call(A, W, 1, 1, bias=bias, act=fact.ACT_GELU_TANH) - r.z).max() < 5e-4     # fast-math GELU, not a rounding to bf16
 
 
+def test_fp32_output_without_workspace_plain_and_batched():
+    # K whole: every entry point writes fp32 straight from its epilogue, ragged edges and every tile shape included
+    M, N, K = 300, 264, 520
+    A = wl.normal((M, K), 1.0, "f32d.A")
+    W = wl.normal((N, K), 0.05, "f32d.W")
+    bias = wl.normal((N,), 1.0, "f32d.b")
+    r = ref.gemm_epilogue(A, W, True, bias=bias)
+    ep = fact.Epilogue(bias=bias.cuda(), out_f32=1)
+    for ldc in (N, N + 3):                       # 16-byte rows, and rows that only allow element stores
+        C = torch.full((M + 1, ldc), float("nan"), dtype=torch.float32, device="cuda")
+        fact.binding.check(fact.fact_gemm(M, N, K, A.cuda(), K, W.cuda(), K, 1, C, ldc, ep))
+        out = C.cpu().numpy()
+        assert np.isnan(out[M]).all() and np.isnan(out[:, N:]).all(), "wrote outside C"
+        _assert_f32_close(out[:M, :N].astype(np.float64), r, f"fp32 out direct ldc {ldc}")
+    for cfg in cfgs(1):
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        fact.binding.check(fact.fact_gemm_ex(1, M, N, K, A.cuda(), K, 0, W.cuda(), K, 0, 1, C, N, 0, ep, cfg, 1, 0, None, 0))
+        _assert_f32_close(C.cpu().numpy().astype(np.float64), r, f"fp32 out direct cfg {cfg}")
+    # batched: two problems, fp32 strides in fp32 elements
+    A2 = wl.normal((2, 128, 256), 1.0, "f32d.A2")
+    B2 = wl.normal((2, 256, 136), 1.0, "f32d.B2")
+    C = torch.full((2, 128, 136), float("nan"), dtype=torch.float32, device="cuda")
+    fact.binding.check(fact.fact_gemm_batched(2, 128, 136, 256, A2.cuda(), 256, 128 * 256, B2.cuda(), 136, 256 * 136, 0,
+                                              C, 136, 128 * 136, fact.Epilogue(out_f32=1)))
+    for b in range(2):
+        _assert_f32_close(C[b].cpu().numpy().astype(np.float64), ref.gemm_epilogue(A2[b], B2[b], False), f"fp32 out batch {b}")
+
+
 def test_fp32_output_refusals():
-    A = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    A = torch.zeros(64, 4096, dtype=torch.bfloat16, device="cuda")
+    B = torch.zeros(4096, 64, dtype=torch.bfloat16, device="cuda")
     C = torch.zeros(64, 64, dtype=torch.float32, device="cuda")
     ep = fact.Epilogue(out_f32=1)
-    assert fact.fact_gemm(64, 64, 64, A, 64, A, 64, 0, C, 64, ep) == -7                      # only with a workspace
-    assert fact.fact_gemm_splitk(64, 64, 64, A, 64, A, 64, 0, C, 64, ep, 1, None, 0) == -6
+    assert fact.fact_gemm_splitk(64, 64, 4096, A, 4096, B, 64, 0, C, 64, ep, 4, None, 0) == -6       # K split: partial planes need a workspace
+    Codd = torch.zeros(64 * 64 + 1, dtype=torch.float32, device="cuda")
+    assert fact.fact_gemm(64, 64, 4096, A, 4096, B, 64, 0, Codd.view(torch.uint8)[2:].data_ptr(), 64, ep) == -3   # fp32 C not 4-byte aligned
