@@ -981,6 +981,15 @@ gemm_kernel(const GemmArgs p)
         __syncthreads();
         if (tid == 0)
             __hip_atomic_store(p.tail_flags + (int64_t)tail_tile * tail_parts + tail_seg, p.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    } else if (in_tail) {
+        // The collecting work-group takes the flags down again once every thread has its partial sums
+        // (each added them to its values before it got here).  A launch replayed from a captured graph
+        // carries the same epoch every time: without this, the second replay would find the flags
+        // of the first still raised and read partial tiles that are being rewritten.
+        __syncthreads();
+        if (tid == 0)
+            for (int sgm = 0; sgm < tail_parts; ++sgm)
+                __hip_atomic_store(p.tail_flags + (int64_t)tail_tile * tail_parts + sgm, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 #else
     (void)p;
