@@ -19,7 +19,10 @@
  *   - trans_b == 0: B is [K][N]  (C = A B).
  *     trans_b == 1: B is [N][K]  (C = A B^T, the weight layout of a linear layer).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work
- *     is enqueued on it; the calls do not synchronise.
+ *     is enqueued on it; the calls do not synchronise, allocate or clear memory, so
+ *     they may be captured in a HIP graph and replayed (call each entry point once
+ *     outside a capture first: a kernel's first launch on a device sets its LDS
+ *     limit).  Two launches that share a workspace must not overlap in time.
  *   - Return value: FACT_OK or a negative fact_status.  Arguments are validated
  *     on the host before anything is launched; on error nothing is launched.  No
  *     exception crosses the boundary and the library never aborts.
