@@ -1,6 +1,7 @@
 // fact_attention: argument validation and launch of the fused attention kernel.  Host code only;
 // the computation runs in attention_kernel.h.
 #include "../../include/fact.h"
+#include <atomic>
 #include "attention_kernel.h"
 
 #include <cmath>
@@ -17,15 +18,15 @@ static hipError_t launch(AttnArgs a, hipStream_t stream)
 {
     auto kern = attn_fwd_kernel<D, NW>;
     constexpr int lds = 2 * 2 * 64 * D * 2;                   // two stages of a K and a V block
-    static bool attr_set[64] = {};
+    static std::atomic<bool> attr_set[64];         // (two host threads may make a kernel's first launch at once: setting the limit twice is harmless)
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        attr_set[dev] = true;
+        attr_set[dev].store(true, std::memory_order_release);
     }
     constexpr int BQ = NW * 64;
     a.q_blocks = (a.T + BQ - 1) / BQ;

@@ -1,6 +1,7 @@
 // One tile configuration's kernels (both B layouts).  Built once per row of configs.def with
 // -DFACT_ID=.. -DFACT_BM=.. -DFACT_BN=.. -DFACT_WM=.. -DFACT_WN=.. -DFACT_BK=.. -DFACT_STAGES=..
 #include "launch.h"
+#include <atomic>
 
 namespace fact {
 
@@ -16,15 +17,15 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
     } else {
     auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES>;
     constexpr int lds = lds_total(FACT_BM, FACT_BN, FACT_WM, FACT_WN, FACT_BK, FACT_STAGES);
-    static bool attr_set[64] = {};
+    static std::atomic<bool> attr_set[64];         // (two host threads may make a kernel's first launch at once: setting the limit twice is harmless)
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!attr_set[dev]) {
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        attr_set[dev] = true;
+        attr_set[dev].store(true, std::memory_order_release);
     }
     const int tiles = args.tiles_m * args.tiles_n;
     const int grid_x = args.tail_g > 1 ? args.tail_first + (tiles - args.tail_first) * args.tail_g : tiles;
