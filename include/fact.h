@@ -84,7 +84,8 @@ typedef struct fact_epilogue {
                                without rounding: the paper's choice for its large-K problem (Section 5.2.3: fp32
                                accumulator AND output).  Every entry point takes it; with K whole the GEMM's own
                                epilogue writes the fp32 result, with K split (fact_gemm_splitk / fact_gemm_ex and
-                               a workspace of fact_gemm_f32out_workspace_bytes()) the reduction pass does. */
+                               a workspace of fact_gemm_f32out_workspace_bytes()) the reduction pass does.
+                               Shapes or pointers that only the guarded fallback kernel serves: FACT_ERR_UNSUPPORTED. */
 } fact_epilogue;
 
 /* ---- entry points --------------------------------------------------------------------- */
