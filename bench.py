@@ -122,7 +122,7 @@ def main():
         out["others"] = workbench.time_all(args.steps, args.warmup)
         out["attention"] = workbench.time_attention(args.steps, args.warmup)
         out["blocks"] = workbench.time_blocks()
-        out["paper_shapes"] = workbench.time_all(args.steps, args.warmup, names=["p1.", "p3.", "p6.", "pb."])
+        out["paper_shapes"] = workbench.time_all(args.steps, args.warmup, names=["p1.", "p3.", "p6.", "pb.", "pc."])
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

@@ -156,6 +156,20 @@ def cases(names=None):
         Case("pb.llama.gate_up_silu", 32768, 28672, 4096, 1, act=S, maker=lambda: {"A": bl()["X"], "B": _t.cat([bl()["W1"], bl()["Wu"]])}),
         Case("pb.llama.down+res", 32768, 4096, 14336, 1, residual=True,
              maker=lambda: {"A": wl.normal((32768, 14336), 0.3, "pb.llama.Hstandin"), "B": bl()["W2"], "R": bl()["R"]}),
+        # the attention output projections of the two blocks (not among the paper's fused patterns, but
+        # whole blocks run them): activations ~ N(0, 0.5) as a stand-in for attention outputs
+        Case("pb.gpt.out+bias+res", 65536, 768, 768, 1, bias=True, residual=True,
+             maker=lambda: {"A": wl.normal((65536, 768), 0.5, "pb.gpt.Astandin"), "B": wl.normal((768, 768), 0.02, "pb.gpt.Wo"),
+                            "bias": wl.normal((768,), 0.02, "pb.gpt.bo"), "R": bg()["R"]}),
+        Case("pb.llama.out+res", 32768, 4096, 4096, 1, residual=True,
+             maker=lambda: {"A": wl.normal((32768, 4096), 0.5, "pb.llama.Astandin"), "B": wl.normal((4096, 4096), 0.02, "pb.llama.Wo"),
+                            "R": bl()["R"]}),
+        Case("pc.gpt.out+bias+res", 8192, 768, 768, 1, bias=True, residual=True,
+             maker=lambda: {"A": wl.normal((8192, 768), 0.5, "pc.gpt.Astandin"), "B": wl.normal((768, 768), 0.02, "pb.gpt.Wo"),
+                            "bias": wl.normal((768,), 0.02, "pb.gpt.bo"), "R": g4()["R"]}),
+        Case("pc.llama.out+res", 2048, 4096, 4096, 1, residual=True,
+             maker=lambda: {"A": wl.normal((2048, 4096), 0.5, "pc.llama.Astandin"), "B": wl.normal((4096, 4096), 0.02, "pb.llama.Wo"),
+                            "R": g5()["R"]}),
     ]
     if names:
         return [c for c in allc + paper if any(c.name.startswith(n) for n in names)]
