@@ -324,8 +324,15 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         const int64_t grid = tiles_m * tiles_n * (a.splits > 1 ? a.splits : q.batch);
         const bool soff_ok = q.trans_b || (q.K * q.ldb * 2 < ((int64_t)1 << 31));
         auto pow2_floor = [](int v) { int r = 1; while (r * 2 <= v) r *= 2; return r; };
+        // Also with about one work-group per compute unit when K is long and not split: the panels then
+        // come from HBM at least once per launch, and inside a transformer block (weights of several
+        // layers between two uses) every time.  Measured with operands rotated out of the memory-side
+        // cache: Llama QKV 1052 -> 1260 TFLOP/s, down projection 1130 -> 1235, 4096^3 1243 -> 1330;
+        // no gain or a small loss for K = 768, for half-empty grids and for split-K ranges.
+        const int64_t wgs = a.tail_g > 1 ? a.tail_first + (tiles_m * tiles_n - a.tail_first) * a.tail_g : grid;
+        const bool one_round_long_k = pl.split <= 1 && wgs >= 3 * kNumCU / 4 && q.K >= 2048;
         if (!off && soff_ok) {
-            if (grid >= 2 * kNumCU) {
+            if (grid >= 2 * kNumCU || one_round_long_k) {
                 const int gsz = (int)(pl.group_m < tiles_m ? pl.group_m : tiles_m);
                 const int resident = 32 * wgs_per_cu(c);
                 int sb = pow2_floor(gsz), sa = pow2_floor(resident / gsz > 0 ? resident / gsz : 1);
