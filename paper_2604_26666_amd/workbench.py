@@ -205,8 +205,8 @@ def time_case(case, steps=30, warmup=30, cfg=-1, split=0, group_m=0, min_warm_ms
     return a.elapsed_time(b) / steps
 
 
-def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30):
-    """As time_case with the table's choice, but successive launches use different copies of A, B and
+def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30, cfg=-1, split=0, group_m=0):
+    """As time_case (the table's choice unless cfg / split / group_m say otherwise), but successive launches use different copies of A, B and
     C, enough copies that a launch never finds its operands in the 256 MB memory-side cache from
     the launch before: the figure for a GEMM whose operands come from HBM (the cases bound by
     memory traffic).  Returns (ms per launch, number of copies)."""
@@ -221,7 +221,7 @@ def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30):
 
     def launch(i):
         case.t = copies[i % sets]
-        return case.run()
+        return case.run(cfg, split, group_m)
 
     try:
         if launch(0) != 0:
