@@ -320,7 +320,6 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     // share one step ahead.  (With few work-groups, e.g. long split-K ranges streamed from HBM,
     // unshared prefetching several steps ahead was measured to be slower than none.)
     {
-        static const bool off = [] { const char *e = std::getenv("FACT_GEMM_PREFETCH"); return e && e[0] == '0'; }();
         const int64_t grid = tiles_m * tiles_n * (a.splits > 1 ? a.splits : q.batch);
         const bool soff_ok = q.trans_b || (q.K * q.ldb * 2 < ((int64_t)1 << 31));
         auto pow2_floor = [](int v) { int r = 1; while (r * 2 <= v) r *= 2; return r; };
@@ -331,7 +330,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         // no gain or a small loss for K = 768, for half-empty grids and for split-K ranges.
         const int64_t wgs = a.tail_g > 1 ? a.tail_first + (tiles_m * tiles_n - a.tail_first) * a.tail_g : grid;
         const bool one_round_long_k = pl.split <= 1 && wgs >= 3 * kNumCU / 4 && q.K >= 2048;
-        if (!off && soff_ok) {
+        if (soff_ok) {
             if (grid >= 2 * kNumCU || one_round_long_k) {
                 const int gsz = (int)(pl.group_m < tiles_m ? pl.group_m : tiles_m);
                 const int resident = 32 * wgs_per_cu(c);
