@@ -160,6 +160,11 @@ def test_attention_llama_shape_2048_tokens():
     _attention_full(wl.attention5(1), [(0, h) for h in (0, 1, 3, 4, 13, 30, 31)])
 
 
+def test_attention_llama_shape_16x2048_the_benchmark_launch():
+    # the batch the benchmark times: 512 (batch, head) pairs, several groups of the work-group order per XCD
+    _attention_full(wl.attention5(16), [(0, 0), (3, 9), (7, 31), (12, 16), (15, 5), (15, 31)])
+
+
 def test_attention_gpt_shape_8x1024():
     _attention_full(wl.attention4(), [(0, 0), (0, 11), (3, 5), (7, 0), (7, 11)])
 
