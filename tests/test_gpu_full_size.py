@@ -289,3 +289,38 @@ def test_whole_llama_block_2048_tokens_sampled_stage_by_stage():
     Wgu = np.concatenate([W["W1"], W["W1u"]], axis=0)
     check.assert_close(H, ref.gemm_epilogue(N2, Wgu, True, act=ref.ACT_SILU_GATE, rows=rows), rows="full", what="block H")
     check.assert_close(Yb, ref.gemm_epilogue(H, W["W2"], True, residual=X1, rows=rows), rows="full", what="block Y")
+
+
+def test_whole_gpt_block_8x1024_sampled_stage_by_stage():
+    """The GPT-shaped block at a shape the benchmark times (LayerNorm, biases, GELU, no rotary step),
+    stage by stage as above."""
+    from oracle import attention as att
+    from oracle import block as blk
+    desc, t, X = wl.block_weights("gpt", 8, 1024)
+    B, T, d, Hq, Hkv, D, dff = 8, 1024, desc["d_model"], desc["q_heads"], desc["kv_heads"], desc["head_dim"], desc["d_ff"]
+    b = fact.Block(B, T, d, Hq, Hkv, D, dff, 0, fact.ACT_GELU_TANH, 0, desc["eps"], 10000.0, **{k: v.cuda() for k, v in t.items()})
+    need = fact.fact_block_scratch_bytes(b)
+    scratch = torch.empty(need, dtype=torch.uint8, device="cuda")
+    n_tok = B * T
+    Y = torch.empty(n_tok, d, dtype=torch.bfloat16, device="cuda")
+    fact.binding.check(fact.fact_block_forward(b, X.cuda(), Y, scratch, need))
+    torch.cuda.synchronize()
+    offs = fact.fact_block_scratch_offsets(b)
+    raw = scratch.cpu().numpy()
+    n = (Hq + 2 * Hkv) * D
+    view = lambda i, r, c: raw[offs[i]: offs[i] + r * c * 2].view(np.uint16).reshape(r, c)
+    N1, QKV, A, X1, N2, H = view(0, n_tok, d), view(1, n_tok, n), view(2, n_tok, Hq * D), view(3, n_tok, d), view(4, n_tok, d), view(5, n_tok, dff)
+    Yb = bits_of(Y)
+    W = {k: wl.bits(v) for k, v in t.items()}
+    rows = rows_for(n_tok, 96, "full.gblk")
+    check.assert_close(N1, blk.layernorm(wl.bits(X), W["norm1_g"], W["norm1_b"]), what="gpt block N1")
+    check.assert_close(QKV, ref.gemm_epilogue(N1, W["Wqkv"], True, bias=W["bqkv"], rows=rows), rows="full", what="gpt block QKV")
+    q4 = QKV[:, : Hq * D].reshape(B, T, Hq, D); k4 = QKV[:, Hq * D: (Hq + Hkv) * D].reshape(B, T, Hkv, D)
+    v4 = QKV[:, (Hq + Hkv) * D:].reshape(B, T, Hkv, D)
+    for (bi, h) in ((0, 0), (3, 7), (7, 11)):
+        r = att.attention(q4[bi:bi + 1, :, h:h + 1], k4[bi:bi + 1, :, h:h + 1], v4[bi:bi + 1, :, h:h + 1])
+        check.assert_close(np.ascontiguousarray(A.reshape(B, T, Hq, D)[bi, :, h]), r, what=f"gpt block attention batch {bi} head {h}")
+    check.assert_close(X1, ref.gemm_epilogue(A, W["Wo"], True, bias=W["bo"], residual=wl.bits(X), rows=rows), rows="full", what="gpt block X1")
+    check.assert_close(N2, blk.layernorm(X1, W["norm2_g"], W["norm2_b"]), what="gpt block N2")
+    check.assert_close(H, ref.gemm_epilogue(N2, W["W1"], True, bias=W["b1"], act=ref.ACT_GELU_TANH, rows=rows), rows="full", what="gpt block H")
+    check.assert_close(Yb, ref.gemm_epilogue(H, W["W2"], True, bias=W["b2"], residual=X1, rows=rows), rows="full", what="gpt block Y")
