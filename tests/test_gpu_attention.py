@@ -12,7 +12,7 @@ import torch
 import paper_2604_26666_amd as fact
 import workloads as wl
 from oracle import attention as att
-from oracle import check
+from oracle import check, ref
 
 pytestmark = pytest.mark.gpu
 
@@ -73,6 +73,33 @@ def test_explicit_scale_and_peaked_scores():
     check.assert_close(got, r, what="attention scale 1.0")
     got, r = run_packed(1, 257, 2, 1, 64, 0, std=1.0, name="sc0", scale=0.01)
     check.assert_close(got, r, what="attention scale 0.01 (nearly uniform)")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("causal", [1, 0])
+def test_constructed_score_patterns(D, causal):
+    """Inputs built so that the running reference of the softmax is exercised: scores that grow
+    along the keys (every key block raises the reference and rescales the sums), scores that fall
+    (the first block's reference stays for good), and all-equal scores (uniform probabilities:
+    each output is the mean of the values it may see)."""
+    B, T, H = 1, 330, 2
+    V = wl.normal((B, T, H, D), 1.0, f"cs.V.{D}")
+    ramp = torch.arange(T, dtype=torch.float32).view(1, T, 1, 1) / 8.0           # + 8 per key block of 64 at scale 1 / D
+    for name, qv, kv in (("growing", 1.0, ramp), ("falling", 1.0, -ramp), ("equal", 0.0, ramp)):
+        Q = torch.full((B, T, H, D), qv).to(torch.bfloat16)
+        K = (kv * torch.ones(B, T, H, D)).to(torch.bfloat16)
+        r = att.attention(wl.bits(Q), wl.bits(K), wl.bits(V), causal=bool(causal), scale=1.0 / D)
+        O = torch.empty((B, T, H, D), dtype=torch.bfloat16, device="cuda")
+        st = (T * H * D, H * D, D)
+        fact.binding.check(fact.fact_attention(B, T, H, H, D, Q.cuda(), st, K.cuda(), st, V.cuda(), st, O, st, causal, 1.0 / D), name)
+        torch.cuda.synchronize()
+        got = wl.bits(O.cpu()).reshape(B * T * H, D)
+        check.assert_close(got, r, what=f"attention, {name} scores, D={D} causal={causal}")
+        if name == "equal":
+            v = V.float().numpy()
+            i = T - 1
+            mean = v[0, : i + 1].mean(axis=0) if causal else v[0].mean(axis=0)
+            assert np.abs(ref.widen(got.reshape(T, H, D)[i]) - mean).max() < 2e-2
 
 
 def test_dense_head_major_layout():
