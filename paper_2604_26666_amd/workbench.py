@@ -378,7 +378,7 @@ def time_all(steps=30, warmup=30, names=None):
         rc, cfg, split = fact.fact_select_config(c.batch, c.M, c.N, c.K, c.trans_b, c.act)
         r = report(c, ms) if ms else {"error": "refused"}
         r["config_id"], r["split_k"] = cfg, split          # split_k < 0: tail split of that many K ranges
-        if ms and c.name.startswith("c3"):                 # bound by memory traffic: also with operands that miss the memory-side cache
+        if ms and c.name.startswith("c"):                  # also with operands that miss the memory-side cache (what a GEMM meets inside a block)
             ms_rot, sets = time_case_rotating(c)
             if ms_rot:
                 rr = report(c, ms_rot)
