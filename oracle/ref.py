@@ -216,15 +216,6 @@ def gemm_epilogue(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE, r
     return Ref(z=z, bound=bound, bits=round_bf16(z), rows=rows_arr)
 
 
-def gemm_batched(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE):
-    """C[b] = epilogue(A[b] x B[b]) for 3-D A, B (and 3-D residual); returns a list of Ref."""
-    A = as_bits(A)
-    B = as_bits(B)
-    R = None if residual is None else as_bits(residual)
-    return [gemm_epilogue(A[b], B[b], trans_b, bias, None if R is None else R[b], act)
-            for b in range(A.shape[0])]
-
-
 def block_mlp(X, W1, W1u, b1, act, W2, b2, R, rows=None, H_bits=None):
     """Two-GEMM feed-forward block (Sections 5.2.4 and 5.2.5).
 

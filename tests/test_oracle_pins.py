@@ -374,3 +374,85 @@ def test_checker_accepts_rounded_reference_and_rejects_a_planted_error():
     assert not check.compare(np.ascontiguousarray(r.bits.T), r)["ok"]
     with pytest.raises(AssertionError):
         check.assert_bits_equal(bad, r)
+
+
+# ---- row subsets: residual selection, the block, and the checker's "full" mode -------------------
+
+def test_residual_rows_follow_the_row_subset():
+    # A = 0: the GEMM contributes nothing, so output row i is exactly residual row rows[i] (its own
+    # bits: a bf16 value rounds to itself).  Every residual row is different, the subset is
+    # unsorted and repeats a row, the residual is wider than the output.
+    M, K, N = 9, 3, 5
+    A = np.zeros((M, K), dtype=np.uint16)
+    B = wl.bits(wl.uniform((K, N), "rr.B"))
+    R = wl.bits(wl.normal((M, N + 3), 1.0, "rr.R"))
+    assert len({R[i, :N].tobytes() for i in range(M)}) == M
+    rows = [8, 2, 2, 0, 5]
+    r = ref.gemm_epilogue(A, B, residual=R, rows=rows)
+    assert np.array_equal(r.bits, R[rows, :N]) and np.array_equal(r.rows, rows)
+    assert np.array_equal(r.bound, np.abs(ref.widen(R[rows, :N])))
+    # and on a real product: the subset equals the same rows of the full result
+    A = wl.uniform((M, K), "rr.A")
+    full = ref.gemm_epilogue(A, B, bias=wl.uniform((N,), "rr.b"), residual=R, act=ref.ACT_GELU_TANH)
+    sub = ref.gemm_epilogue(A, B, bias=wl.uniform((N,), "rr.b"), residual=R, act=ref.ACT_GELU_TANH, rows=rows)
+    assert np.array_equal(sub.z, full.z[rows]) and np.array_equal(sub.bits, full.bits[rows]) and np.array_equal(sub.bound, full.bound[rows])
+    # a planted row mistake (residual taken from rows 0..n-1 instead of the subset) is not the same
+    wrong = ref.gemm_epilogue(A, B, bias=wl.uniform((N,), "rr.b"), residual=R[: len(rows)], act=ref.ACT_GELU_TANH,
+                              rows=list(range(len(rows))))
+    assert not np.array_equal(wrong.bits, sub.bits)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_block_mlp_rows_follow_the_row_subset(gated):
+    T, d, dff = 10, 8, 16
+    W1 = wl.normal((dff, d), 0.3, "br.W1")
+    Wu = wl.normal((dff, d), 0.3, "br.Wu") if gated else None
+    b1 = None if gated else wl.normal((dff,), 0.3, "br.b1")
+    act = ref.ACT_SILU_GATE if gated else ref.ACT_GELU_TANH
+    W2 = wl.normal((d, dff), 0.3, "br.W2")
+    b2 = wl.normal((d,), 0.3, "br.b2")
+    R = wl.normal((T, d), 1.0, "br.R")
+    rows = [9, 4, 4, 1]
+    # X = 0: H is the same in every row, so Y[i] - Y[j] = R[rows[i]] - R[rows[j]] exactly in fp64
+    X0 = np.zeros((T, d), dtype=np.uint16)
+    h, y = ref.block_mlp(X0, W1, Wu, b1, act, W2, b2, R, rows=rows)
+    assert (h.bits == h.bits[0]).all()
+    Rw = ref.widen(wl.bits(R))
+    const = y.z - Rw[rows]
+    assert np.abs(const - const[0]).max() < 1e-13 and np.array_equal(y.rows, rows)
+    # real X: the subset equals the same rows of the whole block, in both modes
+    X = wl.normal((T, d), 1.0, "br.X")
+    hf, yf = ref.block_mlp(X, W1, Wu, b1, act, W2, b2, R)
+    hs, ys = ref.block_mlp(X, W1, Wu, b1, act, W2, b2, R, rows=rows)
+    assert np.array_equal(hs.bits, hf.bits[rows]) and np.array_equal(ys.z, yf.z[rows]) and np.array_equal(ys.bound, yf.bound[rows])
+    # stage-wise mode: H handed in for ALL rows; the second stage must pick rows[] out of it
+    Hgiven = wl.bits(wl.normal((T, dff), 0.5, "br.H"))
+    _, yg = ref.block_mlp(X, W1, Wu, b1, act, W2, b2, R, rows=rows, H_bits=Hgiven)
+    direct = ref.gemm_epilogue(Hgiven[rows], W2, True, bias=b2, residual=wl.bits(R)[rows])
+    assert np.array_equal(yg.z, direct.z) and np.array_equal(yg.rows, rows)
+
+
+def test_checker_full_mode_takes_the_reference_rows():
+    c = wl.config1(64)
+    rows = [63, 5, 17, 0]
+    r = ref.gemm_epilogue(c["A"], c["B"], rows=rows)
+    full = np.full((64, 64), 0x7FC0, dtype=np.uint16)          # NaN everywhere ...
+    full[rows] = r.bits                                         # ... except the rows the reference names
+    s = check.compare(full, r, rows="full")
+    assert s["ok"] and s["bits_equal_frac"] == 1.0 and s["elements"] == len(rows) * 64
+    check.assert_bits_equal(full, r, rows="full")
+    # planted: the right values in the wrong rows (as if rows 0..3 of the output had been compared)
+    wrong = np.full((64, 64), 0x7FC0, dtype=np.uint16)
+    wrong[: len(rows)] = r.bits
+    assert not check.compare(wrong, r, rows="full")["ok"]
+    with pytest.raises(AssertionError):
+        check.assert_bits_equal(wrong, r, rows="full")
+    # planted: two of the named rows exchanged
+    swapped = full.copy()
+    swapped[[63, 5]] = swapped[[5, 63]]
+    assert not check.compare(swapped, r, rows="full")["ok"]
+    with pytest.raises(AssertionError):
+        check.assert_bits_equal(swapped, r, rows="full")
+    # without "full" the same array is taken row for row and has the wrong shape
+    with pytest.raises(ValueError):
+        check.compare(full, r)
