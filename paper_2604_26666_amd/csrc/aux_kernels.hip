@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(256) fallback_gemm_kernel(const GemmArgs p)
     float acc = 0.f, acc_up = 0.f;
     if (TRANS_B) {
         const uint16_t *w = B + (int64_t)n * p.ldb;
-        const uint16_t *wu = gated ? (const uint16_t *)p.B_up + (int64_t)n * p.ldb : nullptr;
+        const uint16_t *wu = gated ? (const uint16_t *)(p.B_up + z * p.stride_b) + (int64_t)n * p.ldb : nullptr;
         for (int k = 0; k < p.K; ++k) {
             const float a = bf16_bits_to_f32(A[k]);
             acc = __builtin_fmaf(a, bf16_bits_to_f32(w[k]), acc);

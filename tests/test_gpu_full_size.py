@@ -1,6 +1,8 @@
 """GPU parity at the full sizes of the five configurations, through the entry points and tile
-configurations the benchmark uses (the table's choice), on sampled output rows the oracle
-computes one by one (all columns, full K; tile-edge rows always included)."""
+configurations the benchmark uses (the table's choice): EVERY element of every output is compared
+with the oracle (all rows, all columns, full K; the oracle is walked in blocks of rows to bound
+its memory).  Only the larger shapes the paper measures (32768 tokens) and the attention cases
+further down are checked on sampled rows (tile-edge rows always included)."""
 import numpy as np
 import pytest
 import torch
@@ -29,16 +31,31 @@ def bits_of(t):
     return wl.bits(t.cpu().contiguous())
 
 
+def row_blocks(M, block=1024):
+    """All rows of an M-row output, as consecutive blocks the oracle handles one at a time."""
+    return [np.arange(i, min(i + block, M), dtype=np.int64) for i in range(0, M, block)]
+
+
+def merge(stats):
+    """Summary over the row blocks of one output: worst block for the ratios, element-weighted mean of the exact-bit share."""
+    n = sum(s["elements"] for s in stats)
+    return {"max_err_over_tol": max(s["max_err_over_tol"] for s in stats), "rel_frobenius": max(s["rel_frobenius"] for s in stats),
+            "bits_equal_frac": sum(s["bits_equal_frac"] * s["elements"] for s in stats) / n, "elements": n}
+
+
 def test_config2_square_8192_bias():
     c = wl.config2()
     n = 8192
     A, B, bias = c["A"].cuda(), c["B"].cuda(), c["bias"].cuda()
     C = torch.empty(n, n, dtype=torch.bfloat16, device="cuda")
     fact.binding.check(fact.fact_gemm(n, n, n, A, n, B, n, 0, C, n, fact.Epilogue(bias=bias)))
-    rows = rows_for(n, 80, "full.c2")
-    r = ref.gemm_epilogue(c["A"], c["B"], False, bias=c["bias"], rows=rows)
-    s = check.assert_close(bits_of(C), r, rows="full", what="config 2")
-    assert s["bits_equal_frac"] > 0.95, s
+    got = bits_of(C)
+    stats = []
+    for rows in row_blocks(n):
+        r = ref.gemm_epilogue(c["A"], c["B"], False, bias=c["bias"], rows=rows)
+        stats.append(check.assert_close(got, r, rows="full", what=f"config 2 rows {rows[0]}.."))
+    s = merge(stats)
+    assert s["elements"] == n * n and s["bits_equal_frac"] > 0.95, s
     # same call again: identical bits
     C2 = torch.empty_like(C)
     fact.binding.check(fact.fact_gemm(n, n, n, A, n, B, n, 0, C2, n, fact.Epilogue(bias=bias)))
@@ -52,7 +69,7 @@ def test_config3a_batched_128x512():
     C = torch.empty(batch, n, n, dtype=torch.bfloat16, device="cuda")
     fact.binding.check(fact.fact_gemm_batched(batch, n, n, n, A, n, n * n, B, n, n * n, 0, C, n, n * n, None))
     got = bits_of(C)
-    for b in (0, 1, 37, 64, 126, 127):
+    for b in range(batch):
         r = ref.gemm_epilogue(c["A"][b], c["B"][b])
         check.assert_close(got[b], r, what=f"config 3a batch {b}")
 
@@ -80,13 +97,14 @@ def test_config4_gpt_block():
     c = wl.config4()
     T, d, dff = 8192, 768, 3072
     X = c["X"].cuda()
-    rows = rows_for(T, 120, "full.c4")
     # QKV projection + bias
     Cq = torch.empty(T, 3 * d, dtype=torch.bfloat16, device="cuda")
     fact.binding.check(fact.fact_gemm(T, 3 * d, d, X, d, c["Wqkv"].cuda(), d, 1, Cq, 3 * d,
                                       fact.Epilogue(bias=c["bqkv"].cuda())))
-    r = ref.gemm_epilogue(c["X"], c["Wqkv"], True, bias=c["bqkv"], rows=rows)
-    check.assert_close(bits_of(Cq), r, rows="full", what="config 4 qkv")
+    Cqg = bits_of(Cq)
+    for rows in row_blocks(T, 2048):
+        r = ref.gemm_epilogue(c["X"], c["Wqkv"], True, bias=c["bqkv"], rows=rows)
+        check.assert_close(Cqg, r, rows="full", what=f"config 4 qkv rows {rows[0]}..")
     # MLP: up + bias + GELU, down + bias + residual
     H = torch.empty(T, dff, dtype=torch.bfloat16, device="cuda")
     Y = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")
@@ -95,24 +113,28 @@ def test_config4_gpt_block():
     fact.binding.check(fact.fact_block_mlp(T, d, dff, X, c["W1"].cuda(), None, c["b1"].cuda(), fact.ACT_GELU_TANH,
                                            c["W2"].cuda(), c["b2"].cuda(), c["R"].cuda(), H, Y, ws, need))
     Hg, Yg = bits_of(H), bits_of(Y)
-    h, y = ref.block_mlp(c["X"], c["W1"], None, c["b1"], ref.ACT_GELU_TANH, c["W2"], c["b2"], c["R"], rows=rows)
-    check.assert_close(Hg, h, rows="full", what="config 4 H")
-    check.assert_close(Yg, y, rows="full", what="config 4 Y end to end")
-    _, y2 = ref.block_mlp(c["X"], c["W1"], None, c["b1"], ref.ACT_GELU_TANH, c["W2"], c["b2"], c["R"], rows=rows, H_bits=Hg)
-    s = check.assert_close(Yg, y2, rows="full", what="config 4 Y stage-wise")
-    assert s["bits_equal_frac"] > 0.97, s
+    stats = []
+    for rows in row_blocks(T, 2048):
+        h, y = ref.block_mlp(c["X"], c["W1"], None, c["b1"], ref.ACT_GELU_TANH, c["W2"], c["b2"], c["R"], rows=rows)
+        check.assert_close(Hg, h, rows="full", what=f"config 4 H rows {rows[0]}..")
+        check.assert_close(Yg, y, rows="full", what=f"config 4 Y end to end rows {rows[0]}..")
+        _, y2 = ref.block_mlp(c["X"], c["W1"], None, c["b1"], ref.ACT_GELU_TANH, c["W2"], c["b2"], c["R"], rows=rows, H_bits=Hg)
+        stats.append(check.assert_close(Yg, y2, rows="full", what=f"config 4 Y stage-wise rows {rows[0]}.."))
+    s = merge(stats)
+    assert s["elements"] == T * d and s["bits_equal_frac"] > 0.97, s
 
 
 def test_config5_llama_block():
     c = wl.config5()
     T, d, dff = 2048, 4096, 14336
     X = c["X"].cuda()
-    rows = rows_for(T, 48, "full.c5")
     nqkv = c["Wqkv"].shape[0]
     Cq = torch.empty(T, nqkv, dtype=torch.bfloat16, device="cuda")
     fact.binding.check(fact.fact_gemm(T, nqkv, d, X, d, c["Wqkv"].cuda(), d, 1, Cq, nqkv, None))
-    r = ref.gemm_epilogue(c["X"], c["Wqkv"], True, rows=rows)
-    check.assert_close(bits_of(Cq), r, rows="full", what="config 5 qkv")
+    Cqg = bits_of(Cq)
+    for rows in row_blocks(T, 512):
+        r = ref.gemm_epilogue(c["X"], c["Wqkv"], True, rows=rows)
+        check.assert_close(Cqg, r, rows="full", what=f"config 5 qkv rows {rows[0]}..")
     # SwiGLU MLP: fused gate/up with SiLU(gate)*up, down + residual
     H = torch.empty(T, dff, dtype=torch.bfloat16, device="cuda")
     Y = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")
@@ -121,12 +143,15 @@ def test_config5_llama_block():
     fact.binding.check(fact.fact_block_mlp(T, d, dff, X, c["Wg"].cuda(), c["Wu"].cuda(), None, fact.ACT_SILU_GATE,
                                            c["Wd"].cuda(), None, c["R"].cuda(), H, Y, ws, need))
     Hg, Yg = bits_of(H), bits_of(Y)
-    h, y = ref.block_mlp(c["X"], c["Wg"], c["Wu"], None, ref.ACT_SILU_GATE, c["Wd"], None, c["R"], rows=rows)
-    check.assert_close(Hg, h, rows="full", what="config 5 H")
-    check.assert_close(Yg, y, rows="full", what="config 5 Y end to end")
-    _, y2 = ref.block_mlp(c["X"], c["Wg"], c["Wu"], None, ref.ACT_SILU_GATE, c["Wd"], None, c["R"], rows=rows, H_bits=Hg)
-    s = check.assert_close(Yg, y2, rows="full", what="config 5 Y stage-wise")
-    assert s["bits_equal_frac"] > 0.97, s
+    stats = []
+    for rows in row_blocks(T, 512):
+        h, y = ref.block_mlp(c["X"], c["Wg"], c["Wu"], None, ref.ACT_SILU_GATE, c["Wd"], None, c["R"], rows=rows)
+        check.assert_close(Hg, h, rows="full", what=f"config 5 H rows {rows[0]}..")
+        check.assert_close(Yg, y, rows="full", what=f"config 5 Y end to end rows {rows[0]}..")
+        _, y2 = ref.block_mlp(c["X"], c["Wg"], c["Wu"], None, ref.ACT_SILU_GATE, c["Wd"], None, c["R"], rows=rows, H_bits=Hg)
+        stats.append(check.assert_close(Yg, y2, rows="full", what=f"config 5 Y stage-wise rows {rows[0]}.."))
+    s = merge(stats)
+    assert s["elements"] == T * d and s["bits_equal_frac"] > 0.97, s
 
 
 # ---- attention at the two block configurations' shapes ------------------------------------------
@@ -184,9 +209,10 @@ def test_paper_square_4096():
     n = 4096
     C = torch.empty(n, n, dtype=torch.bfloat16, device="cuda")
     fact.binding.check(fact.fact_gemm(n, n, n, c["A"].cuda(), n, c["B"].cuda(), n, 0, C, n, None))
-    rows = rows_for(n, 60, "full.p1")
-    s = check.assert_close(bits_of(C), ref.gemm_epilogue(c["A"], c["B"], False, rows=rows), rows="full", what="paper problem 1")
-    assert s["bits_equal_frac"] > 0.95, s
+    got = bits_of(C)
+    s = merge([check.assert_close(got, ref.gemm_epilogue(c["A"], c["B"], False, rows=rows), rows="full", what="paper problem 1")
+               for rows in row_blocks(n)])
+    assert s["elements"] == n * n and s["bits_equal_frac"] > 0.95, s
 
 
 def test_paper_batched_128x512x2048x1024():
@@ -206,9 +232,8 @@ def test_paper_large_k_524288():
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     C = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
     fact.binding.check(fact.fact_gemm_splitk(m, n, k, c["A"].cuda(), k, c["B"].cuda(), n, 0, C, n, None, 0, ws, need))
-    rows = rows_for(m, 24, "full.p6", tile=128)
-    s = check.assert_close(bits_of(C), ref.gemm_epilogue(c["A"], c["B"], False, rows=rows), rows="full", what="paper problem 6")
-    assert s["rel_frobenius"] < 3e-3, s
+    s = check.assert_close(bits_of(C), ref.gemm_epilogue(c["A"], c["B"], False), what="paper problem 6")      # every row
+    assert s["elements"] == m * n and s["rel_frobenius"] < 3e-3, s
 
 
 def test_paper_large_k_524288_fp32_output():
@@ -221,9 +246,8 @@ def test_paper_large_k_524288_fp32_output():
     ep = fact.Epilogue(out_f32=1)
     fact.binding.check(fact.fact_gemm_splitk(m, n, k, c["A"].cuda(), k, c["B"].cuda(), n, 0, C, n, ep, 0, ws, need))
     torch.cuda.synchronize()
-    rows = rows_for(m, 24, "full.p6f", tile=128)
-    r = ref.gemm_epilogue(c["A"], c["B"], False, rows=rows)
-    got = C.cpu().numpy().astype(np.float64)[rows]
+    r = ref.gemm_epilogue(c["A"], c["B"], False)                                     # every row
+    got = C.cpu().numpy().astype(np.float64)
     err = np.abs(got - r.z)
     assert (err <= 1e-5 + 1e-3 * np.abs(r.z)).all(), float(err.max())             # the paper's criterion (Section 5.1)
     assert np.linalg.norm(got - r.z) <= 5e-6 * np.linalg.norm(r.z)

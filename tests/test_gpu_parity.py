@@ -107,6 +107,30 @@ def test_tiny_and_unaligned_shapes_use_the_guarded_kernel(trans_b):
         check.assert_bits_equal(got, r, what=f"{(M, N, K)}")
 
 
+def test_guarded_kernel_gated_epilogue_and_batches():
+    # K = 9 is served by the guarded kernel only.  Small integers keep the gate and up sums exact, so
+    # the only inexact step is SiLU in fp32: the output is held to the usual tolerance and to a much
+    # tighter one that an up-weight matrix taken from another batch entry cannot meet.
+    M, K, I = 13, 9, 11
+    rc, cfg, _ = fact.fact_select_config(1, M, 2 * I, K, 1, fact.ACT_SILU_GATE)
+    assert cfg < 0, "this shape is meant for the guarded kernel"
+    for batch in (1, 3):
+        X = wl.small_int((batch, M, K), -2, 2, f"gg.X{batch}")
+        W = wl.small_int((batch, 2 * I, K), -2, 2, f"gg.W{batch}")        # distinct gate and up rows in every batch entry
+        C = G().poisoned(batch * M, I).view(batch, M, I)
+        ep = fact.Epilogue(act=fact.ACT_SILU_GATE)
+        fact.binding.check(fact.fact_gemm_batched(batch, M, 2 * I, K, X.cuda(), K, M * K, W.cuda(), K, 2 * I * K, 1,
+                                                  C, I, M * I, ep))
+        out = G().bits_of(C)
+        for b in range(batch):
+            r = ref.gemm_epilogue(X[b], W[b], True, act=ref.ACT_SILU_GATE)
+            check.assert_close(out[b], r, what=f"gated fallback batch {b} of {batch}")
+            # tight: the only inexact step is SiLU in fp32 (relative 1e-6) before one bf16 rounding
+            got = ref.widen(out[b])
+            assert np.abs(got - r.z).max() <= 2.0 ** -8 * np.abs(r.z).max() + 1e-6, f"batch {b}: up weights of another batch entry?"
+            assert len({out[b].tobytes() for b in range(batch)}) == batch
+
+
 def test_all_ones_closed_form():
     for K in (64, 256, 1024, 4096):
         A = torch.ones(256, K, dtype=torch.bfloat16)
