@@ -559,6 +559,6 @@ const char *fact_status_string(int status)
 
 const char *fact_last_error(void) { return g_last_error; }
 
-int fact_version(void) { return 100; }
+int fact_version(void) { return 200; }
 
 }  // extern "C"

@@ -407,10 +407,18 @@ gemm_kernel(const GemmArgs p)
     const __amdgpu_buffer_rsrc_t rsrc_pf = __builtin_amdgcn_make_buffer_rsrc(
         (void *)wave_uniform(pf_is_a ? base_a : (pf_up ? base_b_up : base_b)), 0, wave_uniform(pf_is_a ? nrec_a : nrec_b), kBufferFlags);
     char *pf_sink = smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES) + wave * 256;
+    const int pf_step_u = (int)wave_uniform(pf_step);          // the same in every lane: a scalar offset, no per-lane loop
     auto prefetch_step = [&](int step) __attribute__((always_inline)) {
         const uint32_t off = step < ksteps - 1 ? 0u : kOobOffset;
         const int st = step < ksteps - 1 ? step : 0;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_pf, FACT_LDS_PTR(pf_sink), 4, pf_voff | off, st * (int)pf_step, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_pf, FACT_LDS_PTR(pf_sink), 4, pf_voff | off, st * pf_step_u, 0, 0);
+    };
+    // The same inside the steady part of the K loop, without a per-lane operation: a step past the
+    // range is clamped to the last one (a line touched twice costs an L2 hit; lines past a K range
+    // or a matrix edge are outside the descriptor and touch nothing).
+    auto prefetch_steady = [&](int step) __attribute__((always_inline)) {
+        const int st = step < ksteps - 1 ? step : ksteps - 1;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_pf, FACT_LDS_PTR(pf_sink), 4, pf_voff, st * pf_step_u, 0, 0);
     };
 
     // The loads of K step `step` go to ring slot step % STAGES.  Every step index is legal: the
@@ -465,6 +473,66 @@ gemm_kernel(const GemmArgs p)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rb, FACT_LDS_PTR(dst), 16,
                                                          b_lane[i % B_NV] + ((uint32_t)blk * b_blk_bytes - t * 1024) + c.beyond, 0, t * 1024, 0);
             }
+        }
+    };
+
+    // Steady part of the K loop (every step it loads is a whole step inside the K range): nothing
+    // is computed per load.  Each load has its lane offset in a register of its own, fixed before
+    // the loop; K advances through one scalar offset shared by the K-contiguous operands and, for a
+    // [K][N] operand, through the descriptor's base (a 64-bit scalar add per step).  No range check
+    // is needed there: every row of a steady step exists, and columns past the matrix edge were
+    // clamped into it above.  The masked forms above serve the prologue and the last steps.
+    uint32_t voff_a[A_LD], voff_b[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int blk = wave * A_LD + i, t = i % A_RUN;
+        voff_a[i] = a_lane + ((uint32_t)blk * a_blk_bytes - t * 1024);
+        asm volatile("" : "+v"(voff_a[i]));                    // kept in its register (not recomputed inside the loop)
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int blk = wave * B_LD + i, t = i % B_RUN;
+        if constexpr (TRANS_B) {
+            const int seg = blk / G, x = blk % G;
+            voff_b[i] = b_lane[0] + ((uint32_t)(gated ? (seg >> 1) * G + x : blk) * b_blk_bytes - t * 1024);
+        } else {
+            voff_b[i] = b_lane[i % B_NV] + ((uint32_t)blk * b_blk_bytes - t * 1024);
+        }
+        asm volatile("" : "+v"(voff_b[i]));
+    }
+    struct Steady {
+        int koff;                          // byte offset of the step being loaded inside a K-contiguous row
+        const char *bslab;                 // [K][N] operand: start of the step's slab (minus kOffBias)
+        __amdgpu_buffer_rsrc_t rb;
+    };
+    auto steady_at = [&](int step) __attribute__((always_inline)) {
+        Steady c;
+        c.koff = step * ROWB;
+        c.bslab = nullptr;
+        c.rb = rsrc_bw;
+        if constexpr (!TRANS_B) {
+            c.bslab = (const char *)b_step_base + step * b_step_bytes - kOffBias;
+            c.rb = __builtin_amdgcn_make_buffer_rsrc((void *)c.bslab, 0, 0x7FFFFFFF, kBufferFlags);
+        }
+        return c;
+    };
+    auto steady_next = [&](Steady &c) __attribute__((always_inline)) {
+        c.koff += ROWB;
+        if constexpr (!TRANS_B) {
+            c.bslab += b_step_bytes;
+            c.rb = __builtin_amdgcn_make_buffer_rsrc((void *)c.bslab, 0, 0x7FFFFFFF, kBufferFlags);
+        }
+    };
+    auto issue_steady = [&](const Steady &c, char *stage, auto idx_) __attribute__((always_inline)) {
+        constexpr int idx = decltype(idx_)::value;
+        if constexpr (idx < A_LD) {
+            constexpr int i = idx, run0 = (i / A_RUN) * A_RUN, t = i % A_RUN;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, FACT_LDS_PTR(stage + (wave * A_LD + run0) * 1024), 16, voff_a[i], c.koff, t * 1024, 0);
+        } else {
+            constexpr int i = idx - A_LD, run0 = (i / B_RUN) * B_RUN, t = i % B_RUN;
+            char *dst = stage + A_BYTES + (wave * B_LD + run0) * 1024;
+            if constexpr (TRANS_B) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_bw, FACT_LDS_PTR(dst), 16, voff_b[i], c.koff, t * 1024, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rb, FACT_LDS_PTR(dst), 16, voff_b[i], 0, t * 1024, 0);
         }
     };
 
@@ -603,9 +671,14 @@ gemm_kernel(const GemmArgs p)
     constexpr int LOAD_SPAN = STAGES > 2 ? (TG * 15) / 16 : (TG * 3) / 4;
     auto load_gap = [](int l) constexpr { const int g = 1 + (l * LOAD_SPAN) / LOADS; return g < TG ? g : TG - 1; };
     constexpr int SPAN = (NMFMA * 7) / 8 > 0 ? (NMFMA * 7) / 8 : 1;
-    auto body = [&](int kt, auto slot_tag) __attribute__((always_inline)) {
+    Steady sc = steady_at(STAGES - 1);
+    auto body = [&](int kt, auto slot_tag, auto steady_tag) __attribute__((always_inline)) {
         constexpr int SLOT = decltype(slot_tag)::value;            // kt % STAGES, known at compile time
-        const StepCtx c = step_ctx(kt + STAGES - 1, (SLOT + STAGES - 1) % STAGES);
+        constexpr bool STEADY = decltype(steady_tag)::value;       // the step loaded here is a whole one inside the K range
+        constexpr int LSLOT = (SLOT + STAGES - 1) % STAGES;
+        StepCtx c;
+        if constexpr (!STEADY) c = step_ctx(kt + STAGES - 1, LSLOT);
+        char *lstage = smem + LSLOT * STAGE;
         const char *s = smem + SLOT * STAGE;
         static_for<U>([&](auto j_) __attribute__((always_inline)) {
             constexpr int j = decltype(j_)::value;
@@ -620,9 +693,14 @@ gemm_kernel(const GemmArgs p)
                 });
                 static_for<LOADS>([&](auto l_) __attribute__((always_inline)) {
                     constexpr int l = decltype(l_)::value;
-                    if constexpr (load_gap(l) == j * NMFMA + i) issue_one(c, l_);
+                    if constexpr (load_gap(l) == j * NMFMA + i) {
+                        if constexpr (STEADY) issue_steady(sc, lstage, l_); else issue_one(c, l_);
+                    }
                 });
-                if constexpr (load_gap(LOADS - 1) == j * NMFMA + i) prefetch_step(kt + STAGES - 1 + p.pf_dist);
+                if constexpr (load_gap(LOADS - 1) == j * NMFMA + i) {
+                    if constexpr (STEADY) { prefetch_steady(kt + STAGES - 1 + p.pf_dist); steady_next(sc); }
+                    else prefetch_step(kt + STAGES - 1 + p.pf_dist);
+                }
                 mfma_one(cu, i);
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -641,13 +719,22 @@ gemm_kernel(const GemmArgs p)
         prefetch_step(s + p.pf_dist);
     });
     wait_loads_and_barrier<WAIT_N>();
-    // unrolled over the ring so that each body knows its slot; an incomplete last round runs
-    // phantom (all-zero) steps
-    for (int kt = 0; kt < ksteps; kt += STAGES) {
-        body(kt, std::integral_constant<int, 0>{});
-        body(kt + 1, std::integral_constant<int, 1 % STAGES>{});
-        if constexpr (STAGES > 2) body(kt + 2, std::integral_constant<int, 2 % STAGES>{});
-        if constexpr (STAGES > 3) body(kt + 3, std::integral_constant<int, 3 % STAGES>{});
+    // Unrolled over the ring so that each body knows its slot.  Rounds whose loads are all whole
+    // steps inside the K range (the last body of a round loads step kt + 2 STAGES - 2) run the
+    // steady form; the remaining rounds the masked one, where an incomplete last round runs phantom
+    // (all-zero) steps.
+    int kt = 0;
+    for (; kt + 2 * STAGES - 1 < ksteps; kt += STAGES) {
+        body(kt, std::integral_constant<int, 0>{}, std::true_type{});
+        body(kt + 1, std::integral_constant<int, 1 % STAGES>{}, std::true_type{});
+        if constexpr (STAGES > 2) body(kt + 2, std::integral_constant<int, 2 % STAGES>{}, std::true_type{});
+        if constexpr (STAGES > 3) body(kt + 3, std::integral_constant<int, 3 % STAGES>{}, std::true_type{});
+    }
+    for (; kt < ksteps; kt += STAGES) {
+        body(kt, std::integral_constant<int, 0>{}, std::false_type{});
+        body(kt + 1, std::integral_constant<int, 1 % STAGES>{}, std::false_type{});
+        if constexpr (STAGES > 2) body(kt + 2, std::integral_constant<int, 2 % STAGES>{}, std::false_type{});
+        if constexpr (STAGES > 3) body(kt + 3, std::integral_constant<int, 3 % STAGES>{}, std::false_type{});
     }
     // drain: the last unit of the last step
     wait_frags((KK - 1) & 1);
