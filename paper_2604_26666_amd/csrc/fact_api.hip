@@ -267,7 +267,8 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     // (an fp32 row of 8 columns is two 16-byte pieces: ldc and the batch stride in multiples of 4)
     a.vec_store = (nout % 8 == 0) && q.ldc % (c_f32 ? 4 : 8) == 0 && aligned16(q.C) && q.stride_c % (c_f32 ? 4 : 8) == 0 &&
                   (!q.ep.bias || aligned16(q.ep.bias)) &&
-                  (!q.ep.residual || (aligned16(q.ep.residual) && q.ep.ldr % 8 == 0 && q.ep.stride_r % 8 == 0));
+                  (!q.ep.residual || (aligned16(q.ep.residual) && q.ep.ldr % 8 == 0 && q.ep.stride_r % 8 == 0)) &&
+                  q.ldc < ((int64_t)1 << 21) && q.ep.ldr < ((int64_t)1 << 21);     // a tile's rows within 2^31 bytes: 32-bit row offsets in the epilogue
 
     hipError_t e;
     if (pl.cfg < 0) {

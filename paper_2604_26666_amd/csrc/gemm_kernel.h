@@ -895,98 +895,82 @@ gemm_kernel(const GemmArgs p)
         }
     };
 
-    // Register path (interior wave tiles with 16-byte access, no K hand-over): no LDS at all.  Two
-    // neighbouring 16 x 16 accumulator tiles exchange 16-lane rows (v_permlane16_swap: the odd rows
-    // of the first operand with the even rows of the second), after which lane (r16, q) holds 8
-    // consecutive columns of output row r16: tile q & 1 of the pair, columns 8 (q >> 1) .. + 7.
-    // Bias, activation, residual and the single rounding happen there, in fp32, and every lane
-    // stores 16 bytes: the four lanes of a row write 64 consecutive bytes, the next pair of tiles
-    // the other half of the 128-byte line.  (Gated: gate and up values of an element sit in the
-    // same lane, so SiLU(gate) * up is formed before the exchange.)
-    auto reg_epilogue = [&](auto gated_tag) __attribute__((always_inline)) {
+    // The same pass as a short loop (bf16 output, no partial sums of other K ranges to add): the
+    // read-back of a pass is not unrolled, so the whole epilogue is a few hundred instructions that
+    // stay in the instruction cache from tile to tile (straight-line code of several thousand
+    // instructions was measured to run at the speed of its instruction fetch: 9-15 us per
+    // 256 x 256 tile on a compute unit's first tile).  C and the residual are addressed through
+    // buffer descriptors of the wave's tile with one lane-offset register each that advances by a
+    // constant per iteration (32-bit offsets: the host sets vec_store only if a tile's rows span
+    // less than 2^31 bytes).
+    auto compact_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
         constexpr bool GATED = decltype(gated_tag)::value;
-        constexpr int OT = GATED ? NT / 2 : NT;                     // output tiles along N of this wave
-        constexpr int NP = OT / 2;                                  // pairs of them
-        static_assert(OT % 2 == 0, "tiles are exchanged in pairs");
-        const int col = (q & 1) * 16 + (q >> 1) * 8;                // the lane's first column inside a pair
-        const int n_lane = n_wave + col;
-        // pairs are handled PB at a time (their residual loads issued together); 8-wave work-groups
-        // have half the registers per wave and also reload the bias instead of keeping it
-        constexpr int PB = NWAVES > 4 ? (NP < 2 ? NP : 2) : NP;
-        constexpr bool KEEP_BIAS = NWAVES <= 4;
-        u32x4_t bb[NP];
-        if constexpr (KEEP_BIAS) if (p.bias) {
+        constexpr int OUT_W = GATED ? WTN / 2 : WTN;
+        constexpr int LPR_USED = OUT_W / 8;
+        constexpr int LPR = LPR_USED <= 1 ? 1 : LPR_USED <= 2 ? 2 : LPR_USED <= 4 ? 4 : LPR_USED <= 8 ? 8 : LPR_USED <= 16 ? 16 : 32;
+        constexpr int RPB = 64 / LPR;                               // rows a wave-wide access covers
+        constexpr int NB = EPI_ROWS / RPB;                          // such accesses per pass
+        constexpr int FU0 = NWAVES > 4 ? 2 : 4, FU = NB < FU0 ? NB : FU0;       // of them per loop iteration
+        static_assert(64 % LPR == 0 && NB % FU == 0, "a lane keeps its columns; iterations are whole");
+        const int c8 = lane % LPR, lrow = lane / LPR;
+        if constexpr (LPR != LPR_USED) { if (c8 >= LPR_USED) return; }      // 96- or 48-wide wave tiles: the lanes past a row's end idle
+        float bv[8];
 #pragma unroll
-            for (int pr = 0; pr < NP; ++pr) bb[pr] = *(const u32x4_t *)(p.bias + n_lane + pr * 32);
+        for (int e = 0; e < 8; ++e) bv[e] = 0.0f;
+        if (p.bias) {
+            const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + c8 * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
         }
-        const int act = p.act;
+        const bool gelu = p.act == ACT_GELU_TANH, has_res = R != nullptr;
+        const int64_t row0 = m_wave + pass * EPI_ROWS;
+        const __amdgpu_buffer_rsrc_t rsrc_c = __builtin_amdgcn_make_buffer_rsrc((void *)wave_uniform((const char *)(C + row0 * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+        const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)wave_uniform((const char *)(has_res ? R + row0 * p.ldr + n_wave : C + row0 * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+        uint32_t vo = (uint32_t)((lrow * (int)p.ldc + c8 * 8) * 2), vr = (uint32_t)((lrow * (int)p.ldr + c8 * 8) * 2);
+        const uint32_t step_c = (uint32_t)(RPB * (int)p.ldc * 2), step_r = (uint32_t)(RPB * (int)p.ldr * 2);
+        const char *src = region + lrow * EPI_PITCH + c8 * 32;
+#pragma nounroll
+        for (int it = 0; it < NB / FU; ++it) {
+            u32x4_t rb[FU];
+            f32x4_t x[FU][2], y[FU][2];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int64_t m = m_wave + mt * 16 + r16;
-            // the tile row stays in the accumulation registers up to here (the compiler would otherwise
-            // copy every accumulator out ahead of the first store, and spill)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) asm volatile("" : "+a"(acc[mt][nt]));
-#pragma unroll
-            for (int p0 = 0; p0 < NP; p0 += PB) {
-                u32x4_t rb[PB];
-                if (R) {
-#pragma unroll
-                    for (int x = 0; x < PB; ++x) rb[x] = *(const u32x4_t *)(R + m * p.ldr + n_lane + (p0 + x) * 32);
-                }
-                if constexpr (!KEEP_BIAS) if (p.bias) {
-#pragma unroll
-                    for (int x = 0; x < PB; ++x) bb[p0 + x] = *(const u32x4_t *)(p.bias + n_lane + (p0 + x) * 32);
-                }
-#pragma unroll
-                for (int x = 0; x < PB; ++x) {
-                    const int pr = p0 + x;
-                    float z[8];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float x0 = acc[mt][2 * pr][e], x1 = acc[mt][2 * pr + 1][e];
-                        if constexpr (GATED) { x0 = silu(x0) * acc[mt][OT + 2 * pr][e]; x1 = silu(x1) * acc[mt][OT + 2 * pr + 1][e]; }
-                        const auto sw = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(uint32_t, x0), __builtin_bit_cast(uint32_t, x1), false, false);
-                        z[e] = __builtin_bit_cast(float, (uint32_t)sw[0]);
-                        z[4 + e] = __builtin_bit_cast(float, (uint32_t)sw[1]);
-                    }
-                    if (p.bias) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bb[pr][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bb[pr][e] >> 16); }
-                    }
-                    if (act == ACT_GELU_TANH) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
-                    }
-                    if (R) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[x][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[x][e] >> 16); }
-                    }
-                    if (p.c_f32) {
-                        float *cf = Cf + m * p.ldc + n_lane + pr * 32;
-                        *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
-                        *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
-                    } else {
-                        u32x4_t o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
-                            o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
-                        }
-                        *(u32x4_t *)(C + m * p.ldc + n_lane + pr * 32) = o;
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);  // one group at a time: the accumulators are not all copied out first
+            for (int j = 0; j < FU; ++j) {
+                if (has_res) rb[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, vr + j * step_r, 0, 0);
+                const char *sj = src + j * RPB * EPI_PITCH;
+                x[j][0] = *(const f32x4_t *)sj; x[j][1] = *(const f32x4_t *)(sj + 16);
+                if constexpr (GATED) { y[j][0] = *(const f32x4_t *)(sj + OUT_W * 4); y[j][1] = *(const f32x4_t *)(sj + OUT_W * 4 + 16); }
             }
+#pragma unroll
+            for (int j = 0; j < FU; ++j) {
+                float z[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    z[e] = x[j][e >> 2][e & 3];
+                    if constexpr (GATED) z[e] = silu(z[e]) * y[j][e >> 2][e & 3];
+                    z[e] += bv[e];
+                }
+                if (gelu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                }
+                if (has_res) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                }
+                u32x4_t o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
+                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                }
+                // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
+                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + j * step_c, 0, 0);
+            }
+            vo += FU * step_c; vr += FU * step_r; src += FU * RPB * EPI_PITCH;
         }
     };
-    bool in_registers = false;
-    if (fast && !in_tail) {
-        if (!gated) { reg_epilogue(std::false_type{}); in_registers = true; }
-        else if constexpr (NT % 4 == 0) { reg_epilogue(std::true_type{}); in_registers = true; }
-    }
 
-    if (!in_registers)
     static_for<WTM / EPI_ROWS>([&](auto pass_) __attribute__((always_inline)) {
         constexpr int pass = decltype(pass_)::value;
         if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
@@ -1030,7 +1014,8 @@ gemm_kernel(const GemmArgs p)
             return;
         }
         if (fast) {
-            if (gated) fast_pass(pass, std::true_type{}); else fast_pass(pass, std::false_type{});
+            if (tail_parts == 0 && !p.c_f32) { if (gated) compact_pass(pass, std::true_type{}); else compact_pass(pass, std::false_type{}); }
+            else if (gated) fast_pass(pass, std::true_type{}); else fast_pass(pass, std::false_type{});
             return;
         }
         // General path (tile edges, unaligned C / bias / residual, split-K partials), every access
