@@ -257,9 +257,38 @@ int fact_config_info(int id, int *tile_m, int *tile_n, int *waves_m, int *waves_
 int fact_select_config(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b, int act,
                        int *config_id, int *split_k);
 
+/* ---- the persisted registry (Section 3: entries keyed by rule, data type and architecture;
+ *      Section 4.2 Action 6: tuning results written back; Section 4.3: later lookups reuse them) -- */
+
+/*
+ * Loads tuning results from a registry file and consults them before the compiled-in table
+ * (which is generated from the file shipped with the library).  Text, one entry per line:
+ *
+ *     # fact-registry 1
+ *     gemm bf16 gfx950 <batch> <M> <N> <K> <kn|nk> <plain|gated> <config> <split_k> <group_m> [<ms> <TFLOP/s> <build> <name>]
+ *
+ * kn / nk: B as [K][N] (trans_b = 0) / as [N][K] (trans_b = 1); N counts the contraction's columns
+ * (2 x d_ff when gated); split_k as in fact_gemm_ex (1, > 1, or -g); the trailing fields are
+ * provenance and are not interpreted.  '#' lines other than the format line are comments.
+ * Entries of another rule, data type or architecture, and entries naming a configuration this
+ * build does not have (or one that cannot serve the layout), are skipped.  Of several entries for
+ * one shape the first applies; a call that brings no workspace takes the first one with
+ * split_k == 1.  Host only, callable from any thread; affects calls made after it returns.
+ * path: host pointer to a NUL-terminated file name, read during the call, not kept.
+ * Returns the number of entries taken (>= 0), FACT_ERR_NULL for a NULL path,
+ * FACT_ERR_UNSUPPORTED if the file cannot be read or is not a version-1 registry.
+ */
+int fact_registry_load(const char *path);
+void fact_registry_clear(void);               /* forgets every loaded entry; the compiled-in table stays */
+int fact_registry_size(void);                 /* entries currently loaded */
+
+#define FACT_CONFIG_TABLE   (-1)   /* config_id: the table's choice */
+#define FACT_CONFIG_GUARDED (-2)   /* config_id: the guarded one-thread-per-element kernel, whatever the shape (no K split,
+                                      no fp32 output): the product-side reference result of the on-device sweep */
+
 /*
  * fact_gemm_batched with the tile configuration, split factor and tile-row group size
- * forced: the entry point the on-device sweep uses.  config_id < 0, split_k == 0 and
+ * forced: the entry point the on-device sweep uses.  config_id == FACT_CONFIG_TABLE, split_k == 0 and
  * group_m <= 0 mean "table's choice".  split_k > 1 needs ws (see fact_gemm_splitk) and
  * batch == 1.
  * split_k = -g (g >= 2) asks for a tail split, this library's form of the paper's Stream-K

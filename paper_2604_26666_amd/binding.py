@@ -15,6 +15,8 @@ _LIB_PATH = os.environ.get("FACT_GEMM_LIB") or os.path.join(_HERE, "libfact_gemm
 ACT_NONE = 0
 ACT_GELU_TANH = 1
 ACT_SILU_GATE = 2
+CONFIG_TABLE = -1        # config_id of fact_gemm_ex: the table's choice
+CONFIG_GUARDED = -2      # config_id of fact_gemm_ex: the guarded one-thread-per-element kernel
 
 _i64 = ctypes.c_int64
 _int = ctypes.c_int
@@ -124,6 +126,12 @@ def lib():
         L.fact_last_error.argtypes = []
         L.fact_last_error.restype = ctypes.c_char_p
         L.fact_version.argtypes = []
+        L.fact_registry_load.argtypes = [ctypes.c_char_p]
+        L.fact_registry_load.restype = _int
+        L.fact_registry_clear.argtypes = []
+        L.fact_registry_clear.restype = None
+        L.fact_registry_size.argtypes = []
+        L.fact_registry_size.restype = _int
         for name in ("fact_gemm", "fact_gemm_batched", "fact_gemm_splitk", "fact_block_mlp", "fact_gemm_ex",
                      "fact_num_configs", "fact_config_info", "fact_select_config", "fact_version"):
             getattr(L, name).restype = _int
@@ -246,6 +254,19 @@ def fact_select_config(batch, M, N, K, trans_b, act):
     c, s = _int(-2), _int(0)
     rc = lib().fact_select_config(batch, M, N, K, int(trans_b), int(act), ctypes.byref(c), ctypes.byref(s))
     return rc, c.value, s.value
+
+
+def fact_registry_load(path):
+    """Entries taken from the registry file (>= 0) or a negative status."""
+    return int(lib().fact_registry_load(None if path is None else os.fsencode(path)))
+
+
+def fact_registry_clear():
+    lib().fact_registry_clear()
+
+
+def fact_registry_size():
+    return int(lib().fact_registry_size())
 
 
 def fact_status_string(rc):

@@ -9,6 +9,9 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
 
 namespace fact {
 
@@ -43,6 +46,12 @@ static const TableRow g_table[] = {
 #include "tile_table.inc"
     {0, 0, 0, 0, 0, 0, -1, 0, 0}   // sentinel
 };
+
+// Rows loaded at run time from a registry file (fact_registry_load): consulted before the
+// compiled-in table, newest load first.  Readers and the loader share one mutex: a lookup is a
+// short scan on the host and launches are asynchronous, so it is never held across GPU work.
+static std::mutex g_registry_mutex;
+static std::vector<TableRow> g_registry;
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -96,15 +105,22 @@ static Plan make_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_
     Plan pl;
     const bool gated = act == FACT_ACT_SILU_GATE;
     if (!fast_dims_ok(M, N, K, trans_b)) return pl;
-    for (const TableRow *r = g_table; r->cfg >= 0; ++r) {
-        if (r->batch == batch && r->M == M && r->N == N && r->K == K && r->trans_b == trans_b &&
-            r->gated == (int)gated && (allow_split || (r->split >= 0 && r->split <= 1))) {
-            pl.cfg = r->cfg;
-            pl.split = r->split == 0 ? 1 : r->split;       // negative: a tail split, which needs a workspace as well
-            pl.group_m = r->group_m > 0 ? r->group_m : 4;
-            return pl;
-        }
+    auto matches = [&](const TableRow &r) {
+        return r.batch == batch && r.M == M && r.N == N && r.K == K && r.trans_b == trans_b &&
+               r.gated == (int)gated && (allow_split || (r.split >= 0 && r.split <= 1));
+    };
+    auto take = [&](const TableRow &r) {
+        pl.cfg = r.cfg;
+        pl.split = r.split == 0 ? 1 : r.split;             // negative: a tail split, which needs a workspace as well
+        pl.group_m = r.group_m > 0 ? r.group_m : 4;
+    };
+    {
+        std::lock_guard<std::mutex> lock(g_registry_mutex);
+        for (const TableRow &r : g_registry)
+            if (matches(r)) { take(r); return pl; }
     }
+    for (const TableRow *r = g_table; r->cfg >= 0; ++r)
+        if (matches(*r)) { take(*r); return pl; }
     const int64_t nout = gated ? N / 2 : N;
     double best = 0;
     for (int i = 0; i < kNumConfigs; ++i) {
@@ -209,6 +225,10 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     const int64_t nout = gated ? q.N / 2 : q.N;
 
     Plan pl = make_plan(q.batch, q.M, q.N, q.K, q.trans_b, q.ep.act, allow_table_split);
+    if (cfg_id == FACT_CONFIG_GUARDED) {              // the guarded kernel on request: the sweep's reference result
+        if (split > 1 || split < 0 || q.ep.out_f32) return FACT_ERR_UNSUPPORTED;
+        pl.cfg = -1; pl.split = 1;
+    }
     if (cfg_id >= 0) {
         if (cfg_id >= kNumConfigs) return FACT_ERR_UNSUPPORTED;
         if (!fast_dims_ok(q.M, q.N, q.K, q.trans_b)) return FACT_ERR_UNSUPPORTED;
@@ -556,6 +576,60 @@ const char *fact_status_string(int status)
     case FACT_ERR_HIP: return "HIP error";
     default: return "unknown status";
     }
+}
+
+// Registry file: text, one entry per line (see include/fact.h).  Entries of another rule, data type
+// or architecture are skipped, as are entries naming a configuration this build does not have or
+// one that does not serve the entry's layout.
+int fact_registry_load(const char *path)
+{
+    if (!path) return FACT_ERR_NULL;
+    std::FILE *f = std::fopen(path, "r");
+    if (!f) return FACT_ERR_UNSUPPORTED;
+    char line[1024];
+    bool header = false;
+    std::vector<TableRow> rows;
+    while (std::fgets(line, sizeof line, f)) {
+        if (line[0] == '#') {
+            int ver = 0;
+            if (std::sscanf(line, "# fact-registry %d", &ver) == 1) {
+                if (ver != 1) { std::fclose(f); return FACT_ERR_UNSUPPORTED; }
+                header = true;
+            }
+            continue;
+        }
+        if (!header) { std::fclose(f); return FACT_ERR_UNSUPPORTED; }      // entries before the format line
+        char rule[32], dtype[32], arch[32], layout[8], epi[16];
+        long long batch, M, N, K;
+        int cfg, split, group_m;
+        if (std::sscanf(line, "%31s %31s %31s %lld %lld %lld %lld %7s %15s %d %d %d", rule, dtype, arch, &batch, &M, &N, &K,
+                        layout, epi, &cfg, &split, &group_m) != 12)
+            continue;
+        if (std::strcmp(rule, "gemm") || std::strcmp(dtype, "bf16") || std::strcmp(arch, "gfx950")) continue;
+        const int trans_b = !std::strcmp(layout, "nk") ? 1 : !std::strcmp(layout, "kn") ? 0 : -1;
+        const int gated = !std::strcmp(epi, "gated") ? 1 : !std::strcmp(epi, "plain") ? 0 : -1;
+        if (trans_b < 0 || gated < 0 || batch < 1 || M < 1 || N < 1 || K < 1) continue;
+        if (cfg < 0 || cfg >= kNumConfigs || !g_configs[cfg].serves(trans_b) || (gated && !g_configs[cfg].gate_capable())) continue;
+        if (split == 0 || split == -1 || split > kMaxGridZ || group_m < 0) continue;
+        rows.push_back(TableRow{batch, M, N, K, trans_b, gated, cfg, split, group_m});
+    }
+    std::fclose(f);
+    if (!header) return FACT_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_registry_mutex);
+    g_registry.insert(g_registry.begin(), rows.begin(), rows.end());       // the newest load is consulted first
+    return (int)rows.size();
+}
+
+void fact_registry_clear(void)
+{
+    std::lock_guard<std::mutex> lock(g_registry_mutex);
+    g_registry.clear();
+}
+
+int fact_registry_size(void)
+{
+    std::lock_guard<std::mutex> lock(g_registry_mutex);
+    return (int)g_registry.size();
 }
 
 const char *fact_last_error(void) { return g_last_error; }
