@@ -310,6 +310,29 @@ int fact_gemm_ex(int64_t batch, int64_t M, int64_t N, int64_t K,
                  int config_id, int split_k, int group_m,
                  void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Tail split hand-over, failure reporting.  The work-group that finishes a shared tile waits for
+ * its partners' partial sums (Section 5.2.3: the fix-up step of a K-partitioned tile).  Partners
+ * are dispatched first and never wait, so the wait ends unless the GPU is shared with work that
+ * keeps them from running; it is bounded all the same (about a third of a second).  A wait that
+ * gives up is an error, never a quietly wrong tile: every element of that tile is written as NaN,
+ * and the launch's identity is stored in the first word of the workspace (the workspace layout
+ * is: a 256-byte status block, the partial tiles, the hand-over flags).
+ * fact_tail_timeouts synchronizes `stream`, reads that word (a blocking device-to-host copy) and
+ * sets *gave_up to 1 if any tail-split launch of this process that used `ws` gave up since the
+ * word was last overwritten by other data, else to 0.  After a reported failure the hand-over
+ * flags are in an undefined state: clear the workspace (or take a fresh one) before it serves a
+ * captured graph again.  ws: the device pointer handed to fact_gemm_splitk / fact_gemm_ex /
+ * fact_block_mlp (16-byte aligned); gave_up: host pointer.  Returns FACT_OK, FACT_ERR_NULL,
+ * FACT_ERR_ALIGN or FACT_ERR_HIP.  Not capturable (it synchronizes).
+ */
+int fact_tail_timeouts(const void *ws, void *stream, int *gave_up);
+
+/* Test hook: the number of polls a finishing work-group spends waiting (default 2^20); a negative
+ * value makes it give up at once, which exercises the failure path above deterministically while
+ * every kernel still runs to its end.  Process-wide, applies to launches made after the call. */
+void fact_test_tail_poll_budget(int polls);
+
 /* ---- misc ------------------------------------------------------------------------------- */
 
 const char *fact_status_string(int status);   /* static string, never NULL */

@@ -126,6 +126,10 @@ def lib():
         L.fact_last_error.argtypes = []
         L.fact_last_error.restype = ctypes.c_char_p
         L.fact_version.argtypes = []
+        L.fact_tail_timeouts.argtypes = [_ptr, _ptr, ctypes.POINTER(_int)]
+        L.fact_tail_timeouts.restype = _int
+        L.fact_test_tail_poll_budget.argtypes = [_int]
+        L.fact_test_tail_poll_budget.restype = None
         L.fact_registry_load.argtypes = [ctypes.c_char_p]
         L.fact_registry_load.restype = _int
         L.fact_registry_clear.argtypes = []
@@ -254,6 +258,17 @@ def fact_select_config(batch, M, N, K, trans_b, act):
     c, s = _int(-2), _int(0)
     rc = lib().fact_select_config(batch, M, N, K, int(trans_b), int(act), ctypes.byref(c), ctypes.byref(s))
     return rc, c.value, s.value
+
+
+def fact_tail_timeouts(ws, stream=None):
+    """(status, gave_up) for a tail-split workspace; synchronizes the stream."""
+    g = _int(-1)
+    rc = lib().fact_tail_timeouts(_addr(ws), _stream(stream), ctypes.byref(g))
+    return rc, g.value
+
+
+def fact_test_tail_poll_budget(polls):
+    lib().fact_test_tail_poll_budget(int(polls))
 
 
 def fact_registry_load(path):

@@ -124,6 +124,39 @@ def check_asm_mfma_hazards(asm_text, kernel_filter="attn_fwd_kernel"):
     return findings
 
 
+def check_wide_store_hazards(asm_text):
+    """A buffer store of more than 64 bits whose data registers are overwritten by the vector ALU in the
+    very next instruction needs one wait state (the ISA manual's table of manually inserted wait
+    states: "VMEM store of more than 64 bits, then a VALU write of the store's data registers").  The
+    compiler's hazard pass applies the rule only to stores whose scalar-offset operand is a constant;
+    on gfx950 a store with a register there was seen to pick up the overwriting value in some lanes.
+    The sources therefore keep that operand constant; this scan refuses a build in which a wide
+    buffer store with a register offset is followed directly by a write to its data."""
+    findings = []
+    insts = []
+    for line in asm_text.splitlines():
+        t = line.strip()
+        if not t or t.startswith((";", ".", "//")) or t.endswith(":"):
+            continue
+        insts.append(t)
+    for i, t in enumerate(insts[:-1]):
+        op, _, rest = t.partition(" ")
+        if not (op.startswith("buffer_store_dwordx4") or op.startswith("buffer_store_dwordx3")):
+            continue
+        ops = [o.strip() for o in rest.split(",")]
+        if len(ops) < 4:
+            continue
+        soffset = ops[3].split()[0]
+        if not re.match(r"^(s\d+|m0|vcc_lo|vcc_hi|ttmp\d+)$", soffset):
+            continue                                  # constant (or off): the compiler keeps the wait state itself
+        data = _regs(ops[0])
+        nxt = insts[i + 1]
+        nop, _, nrest = nxt.partition(" ")
+        if nop.startswith("v_") and data & _regs(nrest.split(",")[0]):
+            findings.append(f"'{nxt}' overwrites the data of '{t}' in the next cycle")
+    return findings
+
+
 def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     """extra_flags / lib / obj_dir exist for experiments (a variant library beside the product one)."""
     OBJ = obj_dir
@@ -173,9 +206,11 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     # inline-asm MFMAs (GEMM and attention kernels): check the generated code for the wait-state cases
     hazards = []
     for path, kernel, _ in asm_units:
-        hazards += check_asm_mfma_hazards(open(path).read(), kernel_filter=kernel)
+        text = open(path).read()
+        hazards += check_asm_mfma_hazards(text, kernel_filter=kernel)
+        hazards += [f"{os.path.basename(path)}: {h}" for h in check_wide_store_hazards(text)]
     if hazards and not os.environ.get("FACT_ALLOW_ASM_HAZARDS"):      # (override for timing experiments only)
-        raise RuntimeError("inline-asm MFMA hazards:\n  " + "\n  ".join(hazards[:20]))
+        raise RuntimeError("wait-state hazards in the generated code:\n  " + "\n  ".join(hazards[:20]))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + [u[0] for u in units])
     return lib
 

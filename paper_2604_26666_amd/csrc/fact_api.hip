@@ -55,6 +55,14 @@ static std::vector<TableRow> g_registry;
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
+// Tail split hand-over: flags and the status word carry a launch-unique 64-bit value (a process-wide
+// counter that starts at a clock-derived value), so a workspace never needs clearing and a stale
+// word from another process or another use of the memory is not mistaken for one of ours.
+static const unsigned long long g_tail_epoch_first =
+    (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull;
+static std::atomic<unsigned long long> g_tail_epoch{g_tail_epoch_first};
+static std::atomic<int> g_tail_budget{1 << 20};           // polls (about 0.3 us each) a collecting work-group waits: a third of a second
+
 // Can the MFMA kernel take these operands at all?  (Dimensions only; pointer alignment is
 // checked separately at launch.)
 static bool fast_dims_ok(int64_t M, int64_t N, int64_t K, int trans_b)
@@ -194,8 +202,11 @@ struct TailPlan {
     int64_t first = 0;      // tiles computed whole
     int64_t rem = 0;        // tiles in the tail
     int g = 0;              // K ranges per tail tile (0: no tail split)
-    size_t bytes() const { return g > 1 ? (size_t)rem * (g - 1) * sizeof(float) * tile_floats + ((size_t)rem * (g - 1) + 1) * 8 : 0; }
-    size_t flags_offset() const { return (size_t)rem * (g - 1) * sizeof(float) * tile_floats; }
+    // workspace: a status block (its first word: see fact_tail_timeouts), the fp32 partial tiles, one flag per partial
+    static constexpr size_t kStatusBytes = 256;
+    size_t bytes() const { return g > 1 ? kStatusBytes + (size_t)rem * (g - 1) * sizeof(float) * tile_floats + (size_t)rem * (g - 1) * 8 : 0; }
+    size_t partials_offset() const { return kStatusBytes; }
+    size_t flags_offset() const { return kStatusBytes + (size_t)rem * (g - 1) * sizeof(float) * tile_floats; }
     size_t tile_floats = 0;
 };
 
@@ -308,13 +319,13 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         const TailPlan t = tail_plan(c, tiles_m * tiles_n, q.K, tail_g);
         if (t.g > 1 && ws && aligned16(ws) && ws_bytes >= t.bytes()) {
             // flags carry a launch-unique 64-bit value, so the workspace needs no clearing
-            static std::atomic<unsigned long long> epoch{
-                (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
             a.tail_first = (int)t.first;
             a.tail_g = t.g;
-            a.tail_ws = (float *)ws;
+            a.tail_ws = (float *)((char *)ws + t.partials_offset());
             a.tail_flags = (unsigned long long *)((char *)ws + t.flags_offset());
-            a.tail_epoch = ++epoch;
+            a.tail_status = (unsigned long long *)ws;
+            a.tail_epoch = ++g_tail_epoch;
+            a.tail_budget = g_tail_budget.load(std::memory_order_relaxed);
         } else if (split < 0) {
             return t.g > 1 ? FACT_ERR_WORKSPACE : FACT_ERR_UNSUPPORTED;
         }
@@ -577,6 +588,23 @@ const char *fact_status_string(int status)
     default: return "unknown status";
     }
 }
+
+int fact_tail_timeouts(const void *ws, void *stream, int *gave_up)
+{
+    if (!ws || !gave_up) return FACT_ERR_NULL;
+    if ((uintptr_t)ws & 15u) return FACT_ERR_ALIGN;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "fact_tail_timeouts: stream synchronize");
+    unsigned long long word = 0;
+    e = hipMemcpy(&word, ws, sizeof word, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e, "fact_tail_timeouts: read of the status word");
+    const unsigned long long last = g_tail_epoch.load();
+    // epochs handed out by this process: (first, last], compared modulo 2^64
+    *gave_up = (word - g_tail_epoch_first - 1) < (last - g_tail_epoch_first) ? 1 : 0;
+    return FACT_OK;
+}
+
+void fact_test_tail_poll_budget(int polls) { g_tail_budget.store(polls, std::memory_order_relaxed); }
 
 // Registry file: text, one entry per line (see include/fact.h).  Entries of another rule, data type
 // or architecture are skipped, as are entries naming a configuration this build does not have or

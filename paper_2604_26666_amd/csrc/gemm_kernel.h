@@ -60,8 +60,10 @@ struct GemmArgs {
     int tail_first;         // number of tiles computed whole (== tiles_m * tiles_n when tail_g <= 1)
     int tail_g;             // K ranges per tail tile (0 or 1: off)
     float *tail_ws;         // fp32 partial accumulators, (tail_g - 1) per tail tile
-    unsigned long long *tail_flags;   // one per partial, then one time-out counter
+    unsigned long long *tail_flags;   // one per partial
+    unsigned long long *tail_status;  // workspace word that takes the launch's epoch when a hand-over wait gave up
     unsigned long long tail_epoch;    // value a flag takes when its partial of THIS launch is complete
+    int tail_budget;                  // polls the collecting work-group of a tile spends on its partners' flags (< 0: gives up at once)
 };
 
 constexpr uint32_t kBufferFlags = 0x00020000u;   // raw buffer descriptor word 3 (32-bit data format)
@@ -763,21 +765,28 @@ gemm_kernel(const GemmArgs p)
     const __amdgpu_buffer_rsrc_t rsrc_part = __builtin_amdgcn_make_buffer_rsrc(      // this tile's partials
         (void *)wave_uniform((const char *)(in_tail ? p.tail_ws + (int64_t)tail_tile * tail_parts * TILE_FLOATS : nullptr)), 0,
         (uint32_t)(tail_parts * TILE_FLOATS * 4), kBufferFlags);
+    // A wait that gives up is an error, never a quietly wrong tile: the work-group then writes NaN to
+    // every element of its tile and stores the launch's epoch into the workspace's status word,
+    // which fact_tail_timeouts reads.  (Every thread learns of it through a word of the first
+    // wave's prefetch sink: the operand stages may still be read by slower waves.)
+    bool tail_gave_up = false;
     if (in_tail && !tail_producer) {
         unsigned long long *flags = p.tail_flags + (int64_t)tail_tile * tail_parts;
+        volatile int *verdict = (volatile int *)(smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES));
         if (tid == 0) {
-            int budget = 1 << 20;
-            for (int sgm = 0; sgm < tail_parts; ++sgm)
-                while (__hip_atomic_load(flags + sgm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != p.tail_epoch && budget > 0) {
+            int budget = p.tail_budget;
+            bool gave_up = budget < 0;
+            for (int sgm = 0; sgm < tail_parts && !gave_up; ++sgm)
+                while (__hip_atomic_load(flags + sgm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != p.tail_epoch) {
+                    if (budget <= 0) { gave_up = true; break; }
                     __builtin_amdgcn_s_sleep(8);
                     --budget;
                 }
-            if (budget == 0) {
-                const int t_rem = p.tiles_m * p.tiles_n - p.tail_first;
-                __hip_atomic_fetch_add(p.tail_flags + (int64_t)t_rem * tail_parts, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            }
+            if (gave_up) __hip_atomic_store(p.tail_status, p.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            *verdict = gave_up ? 1 : 0;
         }
         __syncthreads();
+        tail_gave_up = *verdict != 0;
     }
 
     // ---- epilogue ---------------------------------------------------------------------------
@@ -876,6 +885,10 @@ gemm_kernel(const GemmArgs p)
                     if (R) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                    }
+                    if (tail_gave_up) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) z[e] = __builtin_nanf("");
                     }
                     if (p.c_f32) {
                         float *cf = Cf + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n;
@@ -1119,6 +1132,10 @@ gemm_kernel(const GemmArgs p)
                         for (int e = 0; e < 8; ++e)
                             if (n + e < nout) z[e] += (float)rp[e];
                     }
+                }
+                if (tail_gave_up) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = __builtin_nanf("");
                 }
                 if (p.c_f32) {
                     float *cf = Cf + (int64_t)m * p.ldc + n;

@@ -34,3 +34,21 @@ def test_vector_read_of_a_fresh_mfma_result_is_found():
 
 def test_a_missing_kernel_is_reported():
     assert build.check_asm_mfma_hazards("_ZN4fact11gemm_kernelE: ; @y\n\ts_endpgm\n") != []
+
+
+def test_wide_store_data_hazard_scan():
+    bad = ("\tbuffer_store_dwordx4 v[18:21], v52, s[20:23], s5 offen\n"
+           "\tv_add_u32_e32 v19, v1, v2\n")
+    assert len(build.check_wide_store_hazards(bad)) == 1
+    # a constant scalar offset: the compiler's own hazard pass covers it
+    assert build.check_wide_store_hazards(bad.replace(", s5 offen", ", 0 offen")) == []
+    # a wait state, a write to other registers, or a narrow store in between: nothing to report
+    assert build.check_wide_store_hazards(bad.replace("\tv_add", "\ts_nop 0\n\tv_add")) == []
+    assert build.check_wide_store_hazards(bad.replace("v19, v1", "v22, v1")) == []
+    assert build.check_wide_store_hazards(bad.replace("dwordx4 v[18:21]", "dwordx2 v[18:19]")) == []
+    # the product's generated code, as built, is clean
+    import glob, os
+    files = glob.glob(os.path.join(os.path.dirname(build.__file__), "_build", "inst*.s"))
+    if files:
+        for f in files:
+            assert build.check_wide_store_hazards(open(f).read()) == [], f

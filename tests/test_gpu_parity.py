@@ -309,17 +309,12 @@ def test_errors_launch_nothing():
 
 # ---- tail split: the last, partly filled round of tiles shared along K ---------------------------
 
-def _tail_timeouts(ws, cfg, M, nout_tiles_cols, K, g, gated=False):
-    """How often a work-group gave up waiting for a partial tile: the counter behind the flags of a
-    tail-split workspace is only ever incremented, and the helper pre-fills the workspace with 0xA5."""
-    bm, bn, _, _, _ = fact.fact_config_info(cfg)
-    bn_out = bn // 2 if gated else bn
-    tiles = -(-M // bm) * -(-nout_tiles_cols // bn_out)
-    slots = 256 * (2 if bm * bn <= 128 * 128 else 1)
-    rem = tiles - tiles // slots * slots or tiles
-    off = rem * (g - 1) * bm * bn * 4 + rem * (g - 1) * 8
-    torch.cuda.synchronize()
-    return int(ws[off:off + 8].cpu().view(torch.int64)[0]) - int(np.array([0xA5] * 8, dtype=np.uint8).view(np.int64)[0])
+def _tail_timeouts(ws, *unused, **unused_kw):
+    """1 if a work-group of a tail-split launch on this workspace gave up waiting for a partial tile
+    (the helper pre-fills workspaces with 0xA5, which is no launch's identity)."""
+    rc, gave_up = fact.fact_tail_timeouts(ws)
+    assert rc == 0
+    return gave_up
 
 
 @pytest.mark.parametrize("trans_b", [0, 1])
@@ -375,6 +370,42 @@ def test_tail_split_after_full_rounds():
     plain = G().gemm(A, B, 1, cfg=6)
     whole = 512 * 64 * 64            # outputs of tiles computed whole are identical to the plain launch's
     assert (got != plain).sum() <= got.size - whole
+
+
+def test_tail_split_wait_that_gives_up_is_reported_not_hidden():
+    # The give-up branch, forced from the host (a negative poll budget makes the finishing work-groups
+    # give up at once; every kernel still runs to its end): the shared tiles come out as NaN, whole
+    # tiles are untouched, the workspace's status word reports it, and the next launch with the
+    # normal budget is correct again on the same workspace.
+    n, K = 1536, 512                 # 576 tiles of 64 x 64 on 512 slots -> 512 whole tiles + 64 shared by two work-groups
+    A = wl.uniform((n, K), "tt.A")
+    B = wl.uniform((n, K), "tt.B")
+    plain = G().gemm(A, B, 1, cfg=6)
+    keep = []
+    try:
+        fact.fact_test_tail_poll_budget(-1)
+        got = G().gemm(A, B, 1, cfg=6, split=-2, return_ws=keep)
+    finally:
+        fact.fact_test_tail_poll_budget(1 << 20)
+    ws = keep[0]
+    nan = (got & 0x7FFF) > 0x7F80
+    assert nan.sum() == 64 * 64 * 64, "exactly the 64 shared tiles are NaN"
+    tiles = nan.reshape(n // 64, 64, n // 64, 64).transpose(0, 2, 1, 3).reshape(-1, 64 * 64)
+    assert set(tiles.sum(1).tolist()) == {0, 64 * 64}, "a shared tile is NaN in every element, a whole tile in none"
+    assert np.array_equal(got[~nan], plain[~nan])
+    assert _tail_timeouts(ws) == 1
+    # same workspace, normal budget: correct, and bit-identical to a run on a fresh workspace
+    Ad, Bd = A.cuda(), B.cuda()
+    C = G().poisoned(n, n)
+    need = fact.fact_gemm_splitk_workspace_bytes(n, n, K, -2)
+    fact.binding.check(fact.fact_gemm_ex(1, n, n, K, Ad, K, 0, Bd, K, 0, 1, C, n, 0, None, 6, -2, 0, ws, need))
+    again = G().bits_of(C)
+    fresh = G().gemm(A, B, 1, cfg=6, split=-2)
+    assert np.array_equal(again, fresh) and not ((again & 0x7FFF) > 0x7F80).any()
+    assert _tail_timeouts(ws) == 1            # the word is sticky until the caller clears the workspace
+    ws.fill_(0)
+    assert _tail_timeouts(ws) == 0
+    assert fact.fact_tail_timeouts(None)[0] == -1 and fact.fact_tail_timeouts(ws.data_ptr() + 8)[0] == -3
 
 
 def test_tail_split_refusals():
