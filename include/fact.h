@@ -131,6 +131,29 @@ int fact_gemm_splitk(int64_t M, int64_t N, int64_t K,
                      const fact_epilogue *ep,
                      int split_k, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * fact_gemm_splitk for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same arguments, same results (bit for
+ * bit) and same error codes as fact_gemm_splitk, without ws / ws_bytes: the fp32 partial sums (or
+ * the hand-over tiles of a tail split) live in a static device array inside the library, of
+ * fact_gemm_splitk_static_capacity() bytes (32 MiB: 128 K ranges of a 256 x 256 problem).  Every
+ * GPU the library runs on holds its own copy of the array until the process ends.  The call
+ * allocates nothing and frees nothing; a call that would need more than the array holds returns
+ * FACT_ERR_WORKSPACE (fact_last_error says how much) and launches nothing.  All calls on one GPU
+ * share that GPU's array and it keeps the last call's contents (every byte a call reads it has
+ * written itself first, so nothing needs clearing): calls that overlap in time on one GPU, on
+ * any streams, race.  The array's device address is looked up on the first call on a device (or
+ * by fact_gemm_splitk_static_init with that device current, e.g. before a capture begins).
+ */
+int fact_gemm_splitk_static(int64_t M, int64_t N, int64_t K,
+                            const void *A, int64_t lda,
+                            const void *B, int64_t ldb, int trans_b,
+                            void *C, int64_t ldc,
+                            const fact_epilogue *ep,
+                            int split_k, void *stream);
+int fact_gemm_splitk_static_init(void);          /* FACT_OK, or FACT_ERR_HIP / FACT_ERR_UNSUPPORTED (device index >= 64) */
+size_t fact_gemm_splitk_static_capacity(void);   /* bytes of the static array */
+
 /* Bytes of workspace fact_gemm_splitk needs for this shape and split_k (0 = the table's
  * choice, which may also be a tail split, see fact_gemm_ex; negative = a forced tail split
  * of -split_k ranges, largest need over the tile configurations).  Returns 0 when no

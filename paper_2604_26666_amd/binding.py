@@ -126,6 +126,12 @@ def lib():
         L.fact_last_error.argtypes = []
         L.fact_last_error.restype = ctypes.c_char_p
         L.fact_version.argtypes = []
+        L.fact_gemm_splitk_static.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _int, _ptr, _i64, ep, _int, _ptr]
+        L.fact_gemm_splitk_static.restype = _int
+        L.fact_gemm_splitk_static_init.argtypes = []
+        L.fact_gemm_splitk_static_init.restype = _int
+        L.fact_gemm_splitk_static_capacity.argtypes = []
+        L.fact_gemm_splitk_static_capacity.restype = _size
         L.fact_tail_timeouts.argtypes = [_ptr, _ptr, ctypes.POINTER(_int)]
         L.fact_tail_timeouts.restype = _int
         L.fact_test_tail_poll_budget.argtypes = [_int]
@@ -183,6 +189,19 @@ def fact_gemm_batched(batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, trans_
 def fact_gemm_splitk(M, N, K, A, lda, B, ldb, trans_b, C, ldc, ep, split_k, ws, ws_bytes, stream=None):
     return lib().fact_gemm_splitk(M, N, K, _addr(A), lda, _addr(B), ldb, int(trans_b), _addr(C), ldc, _ep(ep),
                                   int(split_k), _addr(ws), int(ws_bytes), _stream(stream))
+
+
+def fact_gemm_splitk_static(M, N, K, A, lda, B, ldb, trans_b, C, ldc, ep, split_k, stream=None):
+    return lib().fact_gemm_splitk_static(M, N, K, _addr(A), lda, _addr(B), ldb, int(trans_b), _addr(C), ldc, _ep(ep),
+                                         int(split_k), _stream(stream))
+
+
+def fact_gemm_splitk_static_init():
+    return int(lib().fact_gemm_splitk_static_init())
+
+
+def fact_gemm_splitk_static_capacity():
+    return int(lib().fact_gemm_splitk_static_capacity())
 
 
 def fact_gemm_splitk_workspace_bytes(M, N, K, split_k):

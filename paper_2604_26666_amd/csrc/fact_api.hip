@@ -589,6 +589,65 @@ const char *fact_status_string(int status)
     }
 }
 
+// ---- split-K without a caller's workspace: partials in a library-owned static device array --------
+// For callers that cannot allocate (code under graph capture, serving loops, harnesses that forbid
+// it).  The array lives in this library's device image: every GPU the library runs on holds its own
+// copy, at its own address, until the process ends.  Host code never uses the array's name as an
+// address (on the host it is a stand-in for the symbol): the address is asked for once per device,
+// with that device current, and kept.
+static constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "static scratch: hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return FACT_ERR_UNSUPPORTED;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));       // this device's copy (the current device)
+        if (e != hipSuccess || !ptr) return hip_fail(e, "static scratch: hipGetSymbolAddress");
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release); // (two threads may both ask: they get the same address)
+    }
+    *out = ptr;
+    return FACT_OK;
+}
+
+size_t fact_gemm_splitk_static_capacity(void) { return kStaticScratchBytes; }
+
+int fact_gemm_splitk_static_init(void)
+{
+    void *ptr = nullptr;
+    return static_scratch(&ptr);
+}
+
+int fact_gemm_splitk_static(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                            int trans_b, void *C, int64_t ldc, const fact_epilogue *ep, int split_k, void *stream)
+{
+    if (split_k < 0) return FACT_ERR_UNSUPPORTED;
+    if (M <= 0 || N <= 0 || K <= 0) return FACT_ERR_DIM;
+    // what fact_gemm_splitk would ask the caller for, for this very call (layout and epilogue known here)
+    const fact_epilogue e0 = ep_or_none(ep);
+    Plan pl = make_plan(1, M, N, K, trans_b, e0.act, true);
+    if (split_k > 0) pl.split = split_k;
+    const bool gated = e0.act == FACT_ACT_SILU_GATE;
+    size_t need = pl.split > 1 && e0.out_f32 ? splitk_ws_bytes(M, N, pl.split) : plan_ws_bytes(pl, M, N, K, gated);
+    if (need > kStaticScratchBytes) {
+        std::snprintf(g_last_error, sizeof g_last_error,
+                      "fact_gemm_splitk_static: this call needs %zu bytes of partial sums, the static array holds %zu "
+                      "(use fact_gemm_splitk with a workspace, or a smaller split_k)", need, kStaticScratchBytes);
+        return FACT_ERR_WORKSPACE;
+    }
+    void *ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != FACT_OK) return rc;
+    Problem q{1, M, N, K, A, lda, 0, B, ldb, 0, trans_b, nullptr, C, ldc, 0, e0};
+    return run(q, -1, split_k, 0, true, ptr, kStaticScratchBytes, (hipStream_t)stream);
+}
+
 int fact_tail_timeouts(const void *ws, void *stream, int *gave_up)
 {
     if (!ws || !gave_up) return FACT_ERR_NULL;
