@@ -24,8 +24,11 @@
  *     outside a capture first: a kernel's first launch on a device sets its LDS
  *     limit).  Two launches that share a workspace must not overlap in time.
  *   - Return value: FACT_OK or a negative fact_status.  Arguments are validated
- *     on the host before anything is launched; on error nothing is launched.  No
- *     exception crosses the boundary and the library never aborts.
+ *     on the host before anything is launched; on error nothing is launched.  (The
+ *     entry points made of several launches, fact_block_mlp and fact_block_forward,
+ *     check every stage's arguments, limits and workspace before the first launch;
+ *     only a HIP launch failure of a later stage, FACT_ERR_HIP, can leave earlier
+ *     stages enqueued.)  No exception crosses the boundary and the library never aborts.
  *   - Aliasing: C may alias `residual` exactly (same pointer, same ld): each
  *     element is read before it is written by the same thread.  Any other overlap
  *     of an output with an input is undefined.

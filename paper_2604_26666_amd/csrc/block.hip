@@ -155,6 +155,14 @@ static int plan(const fact_block *b, Layout &L)
     if (b->act != FACT_ACT_SILU_GATE && b->W1u) return FACT_ERR_EPILOGUE;
     const int64_t T = b->batch * b->tokens, d = b->d_model, nq = b->n_q_heads * b->head_dim;
     const int64_t nqkv = (b->n_q_heads + 2 * b->n_kv_heads) * b->head_dim;
+    // what the later stages would refuse is refused here, before anything is launched: the attention
+    // kernel's 32-bit row offsets inside a batch entry of the packed projection and its grid limit,
+    // the norm kernels' 16-byte access to their parameters
+    if ((b->tokens + 512) * nqkv * 2 >= (int64_t)1 << 31 || b->tokens > 0x7FFFFFFF - 1024) return FACT_ERR_UNSUPPORTED;
+    if (b->batch * b->n_q_heads * ((b->tokens + 127) / 128) > 0x7FFFFFFF || T > 0x7FFFFFFF) return FACT_ERR_UNSUPPORTED;
+    if (!aligned16(b->norm1_g) || !aligned16(b->norm2_g) || (!b->norm_rms && ((b->norm1_b && !aligned16(b->norm1_b)) || (b->norm2_b && !aligned16(b->norm2_b)))))
+        return FACT_ERR_ALIGN;
+    if (b->norm_rms != 0 && b->norm_rms != 1) return FACT_ERR_LAYOUT;
     size_t off = 0;
     L.n1 = off; off += up256((size_t)T * d * 2);
     L.qkv = off; off += up256((size_t)T * nqkv * 2);

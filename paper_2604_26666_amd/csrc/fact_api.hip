@@ -69,7 +69,6 @@ static bool fast_dims_ok(int64_t M, int64_t N, int64_t K, int trans_b)
 {
     if (K % 8) return false;
     if (!trans_b && N % 8) return false;
-    (void)0;
     if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX - 64) return false;
     return true;
 }
@@ -210,7 +209,6 @@ struct TailPlan {
     size_t tile_floats = 0;
 };
 
-static int wgs_per_cu(const ConfigDesc &c);
 static TailPlan tail_plan(const ConfigDesc &c, int64_t tiles, int64_t K, int g)
 {
     TailPlan t;
@@ -528,13 +526,6 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
     e1.act = act;
     Problem q1{1, T, gated ? 2 * d_ff : d_ff, d_model, X, d_model, 0, W1, d_model, 0, 1,
                gated ? W1u : nullptr, H, d_ff, 0, e1};
-    const size_t need = fact_block_mlp_workspace_bytes(T, d_model, d_ff, act);
-    if (need > 0 && (!ws || ws_bytes < need)) return FACT_ERR_WORKSPACE;
-    // (the first GEMM never splits K into planes, but its last round of tiles may be split)
-    const Plan p1 = make_plan(1, T, gated ? 2 * d_ff : d_ff, d_model, 1, act, true);
-    int rc = run(q1, -1, p1.split < -1 ? 0 : 1, 0, p1.split < -1, ws, ws_bytes, (hipStream_t)stream);
-    if (rc != FACT_OK) return rc;
-
     // GEMM 2: Y = H W2^T + b2 + R  (may split K = d_ff when the table says so and ws allows)
     fact_epilogue e2;
     std::memset(&e2, 0, sizeof e2);
@@ -543,6 +534,17 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
     e2.ldr = d_model;
     e2.act = FACT_ACT_NONE;
     Problem q2{1, T, d_model, d_ff, H, d_ff, 0, W2, d_ff, 0, 1, nullptr, Y, d_model, 0, e2};
+    // everything either launch could refuse is checked before the first one: on error nothing runs
+    int rc = validate(q1);
+    if (rc == FACT_OK) rc = validate(q2);
+    if (rc != FACT_OK) return rc;
+    const size_t need = fact_block_mlp_workspace_bytes(T, d_model, d_ff, act);
+    if (need > 0 && (!ws || ws_bytes < need)) return FACT_ERR_WORKSPACE;
+    if (need > 0 && !aligned16(ws)) return FACT_ERR_ALIGN;
+    // (the first GEMM never splits K into planes, but its last round of tiles may be split)
+    const Plan p1 = make_plan(1, T, gated ? 2 * d_ff : d_ff, d_model, 1, act, true);
+    rc = run(q1, -1, p1.split < -1 ? 0 : 1, 0, p1.split < -1, ws, ws_bytes, (hipStream_t)stream);
+    if (rc != FACT_OK) return rc;
     return run(q2, -1, 0, 0, need > 0, ws, ws_bytes, (hipStream_t)stream);
 }
 

@@ -138,6 +138,24 @@ def test_block_refusals():
     assert fact.fact_block_forward(fact.Block(1, 64, 256, 4, 3, 64, 512, 0, fact.ACT_GELU_TANH, **w), Xd, Y, sc, need) == -2
     assert fact.fact_block_forward(fact.Block(1, 64, 256, 4, 4, 96, 512, 0, fact.ACT_GELU_TANH, **w), Xd, Y, sc, need) == -7
     assert fact.fact_block_forward(fact.Block(1, 64, 256, 4, 4, 64, 512, 0, fact.ACT_SILU_GATE, **w), Xd, Y, sc, need) == -5
+    # what only a later stage would refuse is refused before the first launch: the scratch stays untouched
+    sc.fill_(0x5A)
+    long_seq = fact.Block(1, 1 << 21, 256, 4, 4, 64, 512, 0, fact.ACT_GELU_TANH, **w)      # rows of the packed projection past the attention kernel's 32-bit offsets
+    assert fact.fact_block_scratch_bytes(long_seq) == 0 and fact.fact_block_forward(long_seq, Xd, Y, sc, need) == -7
+    w_odd = dict(w)
+    w_odd["norm2_g"] = torch.zeros(256 + 8, dtype=torch.bfloat16, device="cuda")[4:260]   # 8-byte aligned only: the second norm would refuse it
+    assert fact.fact_block_forward(fact.Block(1, 64, 256, 4, 4, 64, 512, 0, fact.ACT_GELU_TANH, **w_odd), Xd, Y, sc, need) == -3
     torch.cuda.synchronize()
-    assert (wl.bits(Y.cpu()) == POISON).all()
+    assert (wl.bits(Y.cpu()) == POISON).all() and (sc == 0x5A).all()
+    # the two-GEMM block: a workspace the second GEMM could not use is refused before the first GEMM runs
+    T, d, dff = 2048, 4096, 14336
+    needm = fact.fact_block_mlp_workspace_bytes(T, d, dff, fact.ACT_SILU_GATE)
+    if needm > 0:
+        z = lambda *shape: torch.zeros(*shape, dtype=torch.bfloat16, device="cuda")
+        H = torch.full((T, dff), POISON, dtype=torch.int16).view(torch.bfloat16).cuda()
+        wsm = torch.empty(needm + 16, dtype=torch.uint8, device="cuda")
+        assert fact.fact_block_mlp(T, d, dff, z(T, d), z(dff, d), z(dff, d), None, fact.ACT_SILU_GATE, z(d, dff), None, None,
+                                   H, z(T, d), wsm.data_ptr() + 8, needm) == -3
+        torch.cuda.synchronize()
+        assert (wl.bits(H.cpu()) == POISON).all()
     assert fact.fact_block_forward(ok, Xd, Y, sc, need) == 0
