@@ -91,6 +91,11 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--n", type=int, default=8192, help="size of the square workload (default: the headline 8192)")
+    ap.add_argument("--probe", default=None, metavar="CASE",
+                    help="for rocprofv3 runs on another workload: launch the named workbench case (a prefix such as c3b. or "
+                         "c3a.; the table's choice) 20 times, with operands rotated through copies larger than the "
+                         "memory-side cache when --cold is given, then 3 plain 1 GiB copies; no timing")
+    ap.add_argument("--cold", action="store_true", help="with --probe: rotate the operands through several copies")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: a few GEMM launches and a few plain "
                          "1 GiB device-to-device copies (the known-size kernel the counters are scaled by); no timing")
@@ -104,6 +109,29 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     fact.lib()
+
+    if args.probe:
+        from paper_2604_26666_amd import workbench
+        case = workbench.cases([args.probe])[0]
+        base = case.alloc()
+        sets = [base]
+        if args.cold:
+            for _ in range(max(1, int(-(-(768 << 20) // case.min_bytes)) - 1)):
+                t = dict(base)
+                t["A"], t["B"], t["C"], t["ws"] = base["A"].clone(), base["B"].clone(), torch.empty_like(base["C"]), None
+                sets.append(t)
+        for i in range(20 + len(sets)):
+            case.t = sets[i % len(sets)]
+            fact.binding.check(case.run(), case.name)
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        rc, cfg, split = fact.fact_select_config(case.batch, case.M, case.N, case.K, case.trans_b, case.act)
+        print(json.dumps({"probe": case.name, "launches": 20 + len(sets), "operand_sets": len(sets), "copies": 3, "copy_bytes": src.numel() * 4,
+                          "config_id": cfg, "split_k": split, "algorithmic_bytes": case.min_bytes, "flops": case.flops}))
+        return
 
     n = args.n
     c = wl.config2(n)

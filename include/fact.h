@@ -120,8 +120,9 @@ int fact_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
  * Large-K GEMM (Section 5.1, Problem 6; Section 5.2.3): K is cut into split_k
  * contiguous ranges, each range's product is written as an fp32 partial into the
  * workspace (fp32 because reduced precision is not enough there, Section 5.2.3), and a
- * second kernel adds the partials in ascending range order in fp32, applies the
- * epilogue and rounds once.  split_k == 0 lets the table choose; split_k == 1 (or a
+ * second kernel adds the partials in fp32 in a fixed order (the ranges in eight consecutive
+ * groups, ascending inside a group, then the eight group sums in ascending order), applies
+ * the epilogue and rounds once.  split_k == 0 lets the table choose; split_k == 1 (or a
  * choice of 1) runs the plain kernel and needs no workspace.  Bit-reproducible: the
  * order of additions is fixed.
  * ws: device pointer, 16-byte aligned, at least

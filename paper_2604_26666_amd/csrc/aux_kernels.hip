@@ -5,80 +5,111 @@
 namespace fact {
 
 // ---- split-K reduction -----------------------------------------------------------------
-// P holds `splits` fp32 partial products [M][N].  Each thread owns 4 consecutive output
-// columns of one row, adds the partials in ascending split order (fixed order, so the
-// result is bit-reproducible), applies the epilogue and rounds once.  The paper's
-// counterpart is the fix-up step of its Stream-K schedule (Section 5.2.3).
-__global__ void __launch_bounds__(64) splitk_reduce_kernel(const GemmArgs p)
+// P holds `splits` fp32 partial products [M][N].  A lane owns 4 consecutive output columns of
+// one row; the eight waves of a work-group own the same 64 such column groups and an eighth of
+// the K ranges each (consecutive ranges, added in ascending order); the eight sums are then
+// added in ascending order by the first wave, which applies the epilogue and rounds once.
+// The order of additions is fixed, so the result is bit-reproducible.  (One wave per column
+// group adding all ranges in turn was bound by its trips to memory: 8.5 us for the 17 MB of
+// 64 ranges of a 256 x 256 output, whatever the number of loads in flight per wave.)  The
+// paper's counterpart is the fix-up step of its Stream-K schedule (Section 5.2.3).
+constexpr int kReduceWaves = 8;
+__global__ void __launch_bounds__(64 * kReduceWaves) splitk_reduce_kernel(const GemmArgs p)
 {
+    __shared__ float part[kReduceWaves - 1][2][4][64];        // sums of waves 1..: [wave-1][gate|up][column][lane]
     const bool gated = p.act == ACT_SILU_GATE;
     const int nout = gated ? (p.N >> 1) : p.N;
     const int groups = (nout + 3) >> 2;
     const int64_t total = (int64_t)p.M * groups;
     const int64_t plane = (int64_t)p.M * p.N;
     const bool vec_p = (p.N & 3) == 0 && (!gated || (nout & 3) == 0);
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total;
-         t += (int64_t)gridDim.x * blockDim.x) {
-        const int m = (int)(t / groups);
-        const int n = (int)(t % groups) * 4;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int per = (p.splits + kReduceWaves - 1) / kReduceWaves;      // K ranges per wave
+    const int s_begin = wave * per < p.splits ? wave * per : p.splits;
+    const int s_end = s_begin + per < p.splits ? s_begin + per : p.splits;
+    for (int64_t t0 = (int64_t)blockIdx.x * 64; t0 < total; t0 += (int64_t)gridDim.x * 64) {
+        const int64_t t = t0 + lane;
+        const bool live = t < total;
+        int m = 0, n = 0;
+        if (live) {
+            if (total <= 0x7FFFFFFF) { m = (int)((uint32_t)t / (uint32_t)groups); n = (int)((uint32_t)t - (uint32_t)m * (uint32_t)groups) * 4; }
+            else { m = (int)(t / groups); n = (int)(t % groups) * 4; }
+        }
         float v[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
-        const float *src = p.P + (int64_t)m * p.N + n;
+        const float *src = p.P + (int64_t)m * p.N + n + (int64_t)s_begin * plane;
         const bool full = n + 3 < nout;
+        const int cnt = live ? s_end - s_begin : 0;
         if (full && vec_p) {
-            // batches of 8 partials: all loads of a batch are issued before the first add, the adds
-            // keep the ascending split order
-            for (int s0 = 0; s0 < p.splits; s0 += 8) {
-                f32x4_t a[8], b[8];
+            // whole batches with every load issued before the first add, then the rest one by one
+            constexpr int NB = 8;
+            int s0 = 0;
+            for (; s0 + NB <= cnt; s0 += NB) {
+                f32x4_t a[NB], b[NB];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if (s0 + j < p.splits) {
-                        a[j] = *(const f32x4_t *)(src + (s0 + j) * plane);
-                        if (gated) b[j] = *(const f32x4_t *)(src + (s0 + j) * plane + nout);
-                    }
+                for (int j = 0; j < NB; ++j) a[j] = *(const f32x4_t *)(src + (s0 + j) * plane);
+                if (gated) {
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) b[j] = *(const f32x4_t *)(src + (s0 + j) * plane + nout);
                 }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if (s0 + j < p.splits) {
-                        v[0] += a[j].x; v[1] += a[j].y; v[2] += a[j].z; v[3] += a[j].w;
-                        if (gated) { u[0] += b[j].x; u[1] += b[j].y; u[2] += b[j].z; u[3] += b[j].w; }
-                    }
+                for (int j = 0; j < NB; ++j) { v[0] += a[j].x; v[1] += a[j].y; v[2] += a[j].z; v[3] += a[j].w; }
+                if (gated) {
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) { u[0] += b[j].x; u[1] += b[j].y; u[2] += b[j].z; u[3] += b[j].w; }
                 }
             }
+            for (; s0 < cnt; ++s0) {
+                const f32x4_t a = *(const f32x4_t *)(src + s0 * plane);
+                v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+                if (gated) { const f32x4_t b = *(const f32x4_t *)(src + s0 * plane + nout); u[0] += b.x; u[1] += b.y; u[2] += b.z; u[3] += b.w; }
+            }
         } else {
-            for (int s = 0; s < p.splits; ++s)
+            for (int s0 = 0; s0 < cnt; ++s0)
                 for (int e = 0; e < 4; ++e)
                     if (n + e < nout) {
-                        v[e] += src[s * plane + e];
-                        if (gated) u[e] += src[s * plane + nout + e];
+                        v[e] += src[s0 * plane + e];
+                        if (gated) u[e] += src[s0 * plane + nout + e];
                     }
         }
-        for (int e = 0; e < 4; ++e) {
-            if (n + e >= nout) continue;
-            float zv = v[e];
-            if (gated) zv = silu(zv) * u[e];
-            if (p.bias) zv += (float)p.bias[n + e];
-            if (p.act == ACT_GELU_TANH) zv = gelu_tanh(zv);
-            if (p.res) zv += (float)p.res[(int64_t)m * p.ldr + n + e];
-            v[e] = zv;
+        if (wave > 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { part[wave - 1][0][e][lane] = v[e]; part[wave - 1][1][e][lane] = u[e]; }
         }
-        if (p.out_f32) {                                   // fp32 output: no rounding at all
-            float *cf = (float *)p.C + (int64_t)m * p.ldc + n;
-            if (full && p.vec_store) {
-                *(f32x4_t *)cf = f32x4_t{v[0], v[1], v[2], v[3]};
-            } else {
-                for (int e = 0; e < 4; ++e)
-                    if (n + e < nout) cf[e] = v[e];
+        __syncthreads();
+        if (wave == 0 && live) {
+#pragma unroll
+            for (int w = 0; w < kReduceWaves - 1; ++w)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[e] += part[w][0][e][lane]; u[e] += part[w][1][e][lane]; }
+            for (int e = 0; e < 4; ++e) {
+                if (n + e >= nout) continue;
+                float zv = v[e];
+                if (gated) zv = silu(zv) * u[e];
+                if (p.bias) zv += (float)p.bias[n + e];
+                if (p.act == ACT_GELU_TANH) zv = gelu_tanh(zv);
+                if (p.res) zv += (float)p.res[(int64_t)m * p.ldr + n + e];
+                v[e] = zv;
             }
-            continue;
+            if (p.out_f32) {                                   // fp32 output: no rounding at all
+                float *cf = (float *)p.C + (int64_t)m * p.ldc + n;
+                if (full && p.vec_store) {
+                    *(f32x4_t *)cf = f32x4_t{v[0], v[1], v[2], v[3]};
+                } else {
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < nout) cf[e] = v[e];
+                }
+            } else {
+                __bf16 *cp = p.C + (int64_t)m * p.ldc + n;
+                if (full && p.vec_store) {
+                    *(u32x2_t *)cp = pack4_bf16(v[0], v[1], v[2], v[3]);
+                } else {
+                    uint16_t *cs = (uint16_t *)cp;
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(v[e]);
+                }
+            }
         }
-        __bf16 *cp = p.C + (int64_t)m * p.ldc + n;
-        if (full && p.vec_store) {
-            *(u32x2_t *)cp = pack4_bf16(v[0], v[1], v[2], v[3]);
-        } else {
-            uint16_t *cs = (uint16_t *)cp;
-            for (int e = 0; e < 4; ++e)
-                if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(v[e]);
-        }
+        __syncthreads();                                       // the waves' sums are read before the next round overwrites them
     }
 }
 
@@ -86,10 +117,10 @@ hipError_t launch_splitk_reduce(const GemmArgs &args, hipStream_t stream)
 {
     const int nout = args.act == ACT_SILU_GATE ? args.N / 2 : args.N;
     const int64_t total = (int64_t)args.M * ((nout + 3) / 4);
-    // one-wave work-groups: even a 256 x 256 output spreads over all CUs
+    // 64 column groups per work-group: even a 256 x 256 output spreads over all CUs
     int64_t blocks = (total + 63) / 64;
     if (blocks > 256 * 256) blocks = 256 * 256;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, args);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(64 * kReduceWaves), 0, stream, args);
     return hipGetLastError();
 }
 

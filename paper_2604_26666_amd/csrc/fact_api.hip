@@ -377,6 +377,8 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         if (ws_bytes < need) return FACT_ERR_WORKSPACE;
         a.P = (float *)ws;
     }
+    // (the kernel numbers (K range or batch entry, tile) pairs with 32-bit integers)
+    if (tiles_m * tiles_n * (a.splits > 1 ? (int64_t)a.splits : q.batch) > INT32_MAX / 2) return FACT_ERR_DIM;
     e = c.launch(a, q.trans_b != 0, a.splits > 1 ? a.splits : (int)q.batch, stream);
     if (e != hipSuccess) return hip_fail(e, "gemm launch");
     if (a.splits > 1 || out_f32) {

@@ -241,7 +241,21 @@ gemm_kernel(const GemmArgs p)
     const bool tail_mode = p.tail_g > 1;
     const bool in_tail = tail_mode && (int)blockIdx.x >= p.tail_first;
     int tail_tile = 0, tail_seg = 0;                 // tile number within the tail, K range number
-    if (!in_tail) {
+    int z = blockIdx.z;
+    if (gridDim.z > 1) {
+        // Split-K and batched launches: (K range or batch entry, tile) pairs in range-major order,
+        // every XCD a contiguous run of them (the linear work-group id modulo 8 is the XCD).  The
+        // tiles of one K range or batch entry then run side by side on one XCD and share its
+        // operands through that XCD's L2.  With the plain grid.z mapping they sat on different
+        // XCDs: 256 x 256 x 131072 on 128 x 256 tiles fetched B twice (202 MB of L2 fills against
+        // 134 MB of operands), 128 x 512^3 on 256 x 256 tiles both operands twice (269 MB).
+        const int tiles = p.tiles_m * p.tiles_n, total = tiles * (int)gridDim.z;
+        const int lin = (int)blockIdx.x + tiles * (int)blockIdx.z;
+        const int qq = total >> 3, rem = total & 7, xcd = lin & 7, loc = lin >> 3;
+        const int item = xcd * qq + (xcd < rem ? xcd : rem) + loc;
+        z = item / tiles;
+        tile_index_to_coords(p, item - z * tiles, tm, tn);
+    } else if (!in_tail) {
         tile_coords(p, blockIdx.x, tail_mode ? p.tail_first : p.tiles_m * p.tiles_n, tm, tn);
     } else {
         const int t_rem = p.tiles_m * p.tiles_n - p.tail_first;
@@ -249,7 +263,6 @@ gemm_kernel(const GemmArgs p)
         tail_seg = j / t_rem; tail_tile = j - tail_seg * t_rem;
         tile_index_to_coords(p, p.tail_first + tail_tile, tm, tn);
     }
-    const int z = blockIdx.z;
     const bool gated = (p.act == ACT_SILU_GATE);
     const int nout = gated ? (p.N >> 1) : p.N;
     const int m0 = tm * BM;

@@ -95,13 +95,21 @@ def sweep_case(case, steps=20, warmup=20, groups=(1, 2, 4, 8, 16), splits=(2, 4,
     rows, ref = got
     ids = range(fact.fact_num_configs()) if configs is None else configs
     results, failures = [], []
+    # Large-K cases are bound by memory traffic: every operand byte is read once, so what matters is
+    # the time with operands that come from HBM.  They are timed with the operands rotated through
+    # copies larger than the memory-side cache (each copy's output is checked like any other).
+    copies = wb.operand_copies(case) if case.splitk else None
     whole_ref = None                         # first accepted output with K whole: the bit-level reference
     split_list = [1] + [t for t in tails if case.batch == 1] + [s for s in splits if case.splitk and case.K // s >= 256]
     for cfg in ids:
         for split in split_list:
             for g in groups:
                 case.t["C"].fill_(0)
-                ms = wb.time_case(case, steps, warmup, cfg, split, g, min_warm_ms=6.0, min_timed_ms=8.0)
+                if copies is None:
+                    ms = wb.time_case(case, steps, warmup, cfg, split, g, min_warm_ms=6.0, min_timed_ms=8.0)
+                else:
+                    ms, _ = wb.time_case_rotating(case, steps=steps, warmup=warmup, cfg=cfg, split=split, group_m=g, copies=copies,
+                                                  min_warm_ms=6.0, min_timed_ms=8.0)
                 if ms is None:
                     failures.append({"cfg": cfg, "split": split, "group_m": g, "reason": "refused"})
                     break

@@ -205,19 +205,29 @@ def time_case(case, steps=30, warmup=30, cfg=-1, split=0, group_m=0, min_warm_ms
     return a.elapsed_time(b) / steps
 
 
-def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30, cfg=-1, split=0, group_m=0):
-    """As time_case (the table's choice unless cfg / split / group_m say otherwise), but successive launches use different copies of A, B and
-    C, enough copies that a launch never finds its operands in the 256 MB memory-side cache from
-    the launch before: the figure for a GEMM whose operands come from HBM (the cases bound by
-    memory traffic).  Returns (ms per launch, number of copies)."""
+def operand_copies(case, min_bytes_total=768 << 20):
+    """The case's operand set and enough further copies of A, B and C (each with its own workspace
+    slot) that together they exceed the 256 MB memory-side cache several times."""
     base = case.alloc()
-    per_set = case.min_bytes
-    sets = max(2, int(-(-min_bytes_total // per_set)))
+    sets = max(2, int(-(-min_bytes_total // case.min_bytes)))
     copies = [base]
     for _ in range(sets - 1):
         c = dict(base)
         c["A"], c["B"], c["C"], c["ws"] = base["A"].clone(), base["B"].clone(), torch.empty_like(base["C"]), None
         copies.append(c)
+    return copies
+
+
+def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30, cfg=-1, split=0, group_m=0, copies=None,
+                       min_warm_ms=20.0, min_timed_ms=10.0):
+    """As time_case (the table's choice unless cfg / split / group_m say otherwise), but successive launches use different copies of A, B and
+    C, enough copies that a launch never finds its operands in the 256 MB memory-side cache from
+    the launch before: the figure for a GEMM whose operands come from HBM (the cases bound by
+    memory traffic).  Returns (ms per launch, number of copies)."""
+    base = case.alloc()
+    if copies is None:
+        copies = operand_copies(case, min_bytes_total)
+    sets = len(copies)
 
     def launch(i):
         case.t = copies[i % sets]
@@ -235,8 +245,8 @@ def time_case_rotating(case, min_bytes_total=768 << 20, steps=30, warmup=30, cfg
         b.record()
         torch.cuda.synchronize()
         est = max(a.elapsed_time(b) / 4, 1e-3)
-        warmup = min(max(warmup, int(20.0 / est) + 1), 2000)
-        steps = min(max(steps, int(10.0 / est) + 1), 1000)
+        warmup = min(max(warmup, int(min_warm_ms / est) + 1), 2000)
+        steps = min(max(steps, int(min_timed_ms / est) + 1), 1000)
         for i in range(warmup):
             launch(i)
         torch.cuda.synchronize()
