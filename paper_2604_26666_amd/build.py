@@ -124,6 +124,34 @@ def check_asm_mfma_hazards(asm_text, kernel_filter="attn_fwd_kernel"):
     return findings
 
 
+def check_accumulators_untouched(asm_text, kernel_filter="gemm_kernel"):
+    """The GEMM kernel keeps its accumulators in accumulation registers that only its inline assembly
+    names (declared as written by every statement that writes them).  Any instruction the compiler
+    emits by itself that names an accumulation register there - a copy, a spill into that register
+    file - could overwrite a tile: refuse such a build."""
+    findings = []
+    for m in re.finditer(r"^(_Z\w+):[^\n]*\n(.*?)^\s*s_endpgm", asm_text, re.S | re.M):
+        name, kern = m.group(1), m.group(2)
+        if kernel_filter not in name:
+            continue
+        in_asm = False
+        for line in kern.splitlines():
+            t = line.strip()
+            if t.startswith(";;#ASMSTART"):
+                in_asm = True
+                continue
+            if t.startswith(";;#ASMEND"):
+                in_asm = False
+                continue
+            if in_asm or not t or t.startswith((";", ".", "//")) or t.endswith(":"):
+                continue
+            if re.search(r"\ba(\d+|\[\d+:\d+\])", t.partition(" ")[2]) or t.startswith("v_accvgpr"):
+                findings.append(f"{name}: the compiler emitted '{t}', which names an accumulation register")
+                if len(findings) > 20:
+                    return findings
+    return findings
+
+
 def check_wide_store_hazards(asm_text):
     """A buffer store of more than 64 bits whose data registers are overwritten by the vector ALU in the
     very next instruction needs one wait state (the ISA manual's table of manually inserted wait
@@ -157,8 +185,21 @@ def check_wide_store_hazards(asm_text):
     return findings
 
 
+def write_acc_regs(path=os.path.join(CSRC, "acc_regs.inc")):
+    """csrc/acc_regs.inc: one line per accumulator tile, naming its four accumulation registers (the kernel
+    addresses them by name in its inline assembly; register names cannot be computed by templates)."""
+    text = ("// GENERATED by paper_2604_26666_amd/build.py (write_acc_regs): accumulator tile T lives in the accumulation\n"
+            "// registers a[4T .. 4T+3].  FACT_ACC_TILE(T, first, second, third, last register).\n" +
+            "".join(f"FACT_ACC_TILE({t}, {4 * t}, {4 * t + 1}, {4 * t + 2}, {4 * t + 3})\n" for t in range(64)))
+    if not os.path.exists(path) or open(path).read() != text:
+        with open(path, "w") as f:
+            f.write(text)
+    return path
+
+
 def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
     """extra_flags / lib / obj_dir exist for experiments (a variant library beside the product one)."""
+    write_acc_regs()
     OBJ = obj_dir
     LIB = lib
     FLAGS = list(globals()["FLAGS"]) + list(extra_flags)
@@ -209,6 +250,8 @@ def build(jobs=None, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
         text = open(path).read()
         hazards += check_asm_mfma_hazards(text, kernel_filter=kernel)
         hazards += [f"{os.path.basename(path)}: {h}" for h in check_wide_store_hazards(text)]
+        if kernel == "gemm_kernel":
+            hazards += check_accumulators_untouched(text)
     if hazards and not os.environ.get("FACT_ALLOW_ASM_HAZARDS"):      # (override for timing experiments only)
         raise RuntimeError("wait-state hazards in the generated code:\n  " + "\n  ".join(hazards[:20]))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + [u[0] for u in units])

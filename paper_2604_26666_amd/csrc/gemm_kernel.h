@@ -204,6 +204,45 @@ __device__ __forceinline__ int swz_n(int k)
     else return (k & 1) << 2;
 }
 
+// The accumulators are not C++ variables: tile T of a wave lives in the accumulation registers
+// a[4T .. 4T+3] by name, and only the inline assembly below touches them.  (As variables, the
+// compiler moved tiles between the two register files around the K loop whenever the code after
+// the loop used their elements in vector arithmetic, and spilled.)  Every statement declares the
+// registers it writes, so the compiler keeps nothing of its own there across the K loop and
+// counts them in the kernel's register budget; the build checks that the compiler itself emits no
+// write to an accumulation register in a GEMM kernel.
+template <int T> struct AccTile;
+#define FACT_ACC_TILE(T, R0, R1, R2, R3)                                                                                         \
+    template <> struct AccTile<T> {                                                                                              \
+        /* D = B-fragment x A-fragment + D */                                                                                    \
+        static __device__ __forceinline__ void mfma(const bf16x8_t &b, const bf16x8_t &a)                                        \
+        {                                                                                                                        \
+            asm volatile("v_mfma_f32_16x16x32_bf16 a[" #R0 ":" #R3 "], %0, %1, a[" #R0 ":" #R3 "]"                               \
+                         : : "v"(b), "v"(a) : "a" #R0, "a" #R1, "a" #R2, "a" #R3);                                               \
+        }                                                                                                                        \
+        static __device__ __forceinline__ void zero()                                                                            \
+        {                                                                                                                        \
+            asm volatile("v_accvgpr_write_b32 a" #R0 ", 0\n\tv_accvgpr_write_b32 a" #R1 ", 0\n\t"                                \
+                         "v_accvgpr_write_b32 a" #R2 ", 0\n\tv_accvgpr_write_b32 a" #R3 ", 0"                                    \
+                         : : : "a" #R0, "a" #R1, "a" #R2, "a" #R3);                                                              \
+        }                                                                                                                        \
+        /* the tile's 16 bytes per lane to LDS, straight from the accumulation registers */                                     \
+        template <int OFFSET> static __device__ __forceinline__ void to_lds(uint32_t lds_addr)                                   \
+        {                                                                                                                        \
+            asm volatile("ds_write_b128 %0, a[" #R0 ":" #R3 "] offset:%1" : : "v"(lds_addr), "n"(OFFSET) : "memory");            \
+        }                                                                                                                        \
+        static __device__ __forceinline__ f32x4_t get()                                                                          \
+        {                                                                                                                        \
+            float x0, x1, x2, x3;                                                                                                \
+            asm volatile("v_accvgpr_read_b32 %0, a" #R0 "\n\tv_accvgpr_read_b32 %1, a" #R1 "\n\t"                               \
+                         "v_accvgpr_read_b32 %2, a" #R2 "\n\tv_accvgpr_read_b32 %3, a" #R3                                      \
+                         : "=v"(x0), "=v"(x1), "=v"(x2), "=v"(x3));                                                              \
+            return f32x4_t{x0, x1, x2, x3};                                                                                      \
+        }                                                                                                                        \
+    };
+#include "acc_regs.inc"
+#undef FACT_ACC_TILE
+
 template <int BM, int BN, int WGM, int WGN, bool TRANS_B, int BK, int STAGES>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_kernel(const GemmArgs p)
@@ -581,11 +620,9 @@ gemm_kernel(const GemmArgs p)
         b_frag[t] = (uint32_t)(A_BYTES + k * (BN * 2) + ((((n >> 3) ^ swz_n<BN>(k))) << 4) + (c & 1) * 8);
     }
 
-    f32x4_t acc[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    // accumulator tile (mt, nt) is AccTile<mt * NT + nt>
+    static_assert(MT * NT <= 64, "accumulator tiles");
+    static_for<MT * NT>([&](auto t_) __attribute__((always_inline)) { AccTile<decltype(t_)::value>::zero(); });
 
     // A K step is consumed in U = KK * PH units: sub-step kk (32 K-values) x part h of the wave's
     // tile rows (MTH of them).  Register sets: two of MTH A fragments (alternating per unit), two
@@ -651,12 +688,11 @@ gemm_kernel(const GemmArgs p)
     // Operand order (B fragment first) makes the accumulator tile hold D[n_local][m_local]:
     // lane (r16, q) owns output row r16 and the 4 consecutive output columns 4q .. 4q+3.
     constexpr int NMFMA = MTH * NT;
-    auto mfma_one = [&](int u, int idx) __attribute__((always_inline)) {
-        const int kk = u / PH, h = u % PH;
-        const int x = idx / NT, nt = idx % NT;
-        // inline asm pins the accumulator tile in place in the accumulation registers; through the
-        // builtin the register allocator rotated tiles between loop iterations and paid for it in copies
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[h * MTH + x][nt]) : "v"(bf[kk & 1][nt]), "v"(af[u & 1][x]));
+    auto mfma_one = [&](auto u_, auto idx_) __attribute__((always_inline)) {
+        constexpr int u = decltype(u_)::value, idx = decltype(idx_)::value;     // compile-time: they name the accumulator's registers
+        constexpr int kk = u / PH, h = u % PH;
+        constexpr int x = idx / NT, nt = idx % NT;
+        AccTile<(h * MTH + x) * NT + nt>::mfma(bf[kk & 1][nt], af[u & 1][x]);
     };
 
     // ---- main loop -----------------------------------------------------------------------
@@ -716,7 +752,7 @@ gemm_kernel(const GemmArgs p)
                     if constexpr (STEADY) { prefetch_steady(kt + STAGES - 1 + p.pf_dist); steady_next(sc); }
                     else prefetch_step(kt + STAGES - 1 + p.pf_dist);
                 }
-                mfma_one(cu, i);
+                mfma_one(std::integral_constant<int, cu>{}, i_);
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
@@ -753,12 +789,18 @@ gemm_kernel(const GemmArgs p)
     }
     // drain: the last unit of the last step
     wait_frags((KK - 1) & 1);
-    static_for<NMFMA>([&](auto i_) __attribute__((always_inline)) { mfma_one(U - 1, decltype(i_)::value); });
+    static_for<NMFMA>([&](auto i_) __attribute__((always_inline)) { mfma_one(std::integral_constant<int, U - 1>{}, i_); });
     // The compiler does not see the MFMAs inside the asm statements, so it cannot pad the gap the
     // hardware needs between a matrix instruction and the first ordinary read of its result.
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // phantom loads still target LDS
 
+    // Everything from here on derives the lane's position anew, so that nothing of it stays live in a
+    // vector register across the K loop (the 8-wave kernels have no register to spare for that).
+    {
+    const int tid = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) + wave * 64;
+    const int lane = tid & 63;
+    const int r16 = lane & 15, q = lane >> 4;
     // ---- split tail: hand over or collect partial sums ------------------------------------------
     // A tile of the tail is accumulated by tail_g work-groups, one K range each.  All but the last
     // store their accumulators as an fp32 tile (row-major, through the epilogue's LDS transpose)
@@ -1000,11 +1042,13 @@ gemm_kernel(const GemmArgs p)
     static_for<WTM / EPI_ROWS>([&](auto pass_) __attribute__((always_inline)) {
         constexpr int pass = decltype(pass_)::value;
         if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
-#pragma unroll
-        for (int i = 0; i < EPI_TR; ++i)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                *(f32x4_t *)(region + (i * 16 + r16) * EPI_PITCH + (nt * 16 + q * 4) * 4) = acc[pass * EPI_TR + i][nt];
+        {
+            const uint32_t dst = (uint32_t)(size_t)FACT_LDS_PTR(region + r16 * EPI_PITCH + q * 16);
+            static_for<EPI_TR * NT>([&](auto w_) __attribute__((always_inline)) {
+                constexpr int i = decltype(w_)::value / NT, nt = decltype(w_)::value % NT;
+                AccTile<(pass * EPI_TR + i) * NT + nt>::template to_lds<i * 16 * EPI_PITCH + nt * 64>(dst);
+            });
+        }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
         const int total = EPI_ROWS * lanes_per_row;
         if (tail_producer) {
@@ -1191,6 +1235,7 @@ gemm_kernel(const GemmArgs p)
         if (tid == 0)
             for (int sgm = 0; sgm < tail_parts; ++sgm)
                 __hip_atomic_store(p.tail_flags + (int64_t)tail_tile * tail_parts + sgm, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
     }
 #else
     (void)p;

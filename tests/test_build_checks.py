@@ -52,3 +52,14 @@ def test_wide_store_data_hazard_scan():
     if files:
         for f in files:
             assert build.check_wide_store_hazards(open(f).read()) == [], f
+
+
+def test_accumulator_register_scan():
+    kern = ("_ZN4fact11gemm_kernelE: ; @x\n"
+            "\t;;#ASMSTART\n\tv_mfma_f32_16x16x32_bf16 a[0:3], v[2:5], v[6:9], a[0:3]\n\t;;#ASMEND\n"
+            "{extra}"
+            "\ts_endpgm\n")
+    assert build.check_accumulators_untouched(kern.format(extra="\tv_add_f32_e32 v1, v2, v3\n")) == []
+    assert len(build.check_accumulators_untouched(kern.format(extra="\tv_accvgpr_write_b32 a5, v1\n"))) == 1
+    assert len(build.check_accumulators_untouched(kern.format(extra="\tscratch_load_dwordx4 a[8:11], off, off\n"))) == 1
+    assert len(build.check_accumulators_untouched(kern.format(extra="\tv_accvgpr_read_b32 v7, a12\n"))) == 1
