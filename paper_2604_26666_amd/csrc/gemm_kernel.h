@@ -1039,6 +1039,137 @@ gemm_kernel(const GemmArgs p)
         }
     };
 
+    // Register path (interior wave tiles with 16-byte access, bf16 output, no K hand-over): no LDS at
+    // all (the transposing path above moves 1 MB through LDS per 256 x 256 tile, 4 us of LDS time).
+    // Two neighbouring 16 x 16 accumulator tiles exchange 16-lane rows (v_permlane16_swap: the odd
+    // rows of the first operand with the even rows of the second), after which lane (r16, q) holds 8
+    // consecutive columns of output row r16: tile q & 1 of the pair, columns 8 (q >> 1) .. + 7.
+    // Bias, activation, residual and the single rounding happen there, in fp32, and every lane
+    // stores 16 bytes: the four lanes of a row write 64 consecutive bytes, the next pair of tiles
+    // the other half of the 128-byte line.  (Gated: gate and up values of an element sit in the
+    // same lane, so SiLU(gate) * up is formed before the exchange.)  What the epilogue adds is
+    // fixed at compile time (one instance per combination, chosen once), so the code is straight;
+    // C and the residual are addressed through buffer descriptors of the wave's tile with one
+    // lane-offset register each (32-bit offsets: the host sets vec_store only if a tile's rows span
+    // less than 2^31 bytes), a tile row adds one vector add, a pair an immediate offset.
+    auto reg_epilogue = [&](auto gated_tag, auto bias_tag, auto gelu_tag, auto res_tag) __attribute__((always_inline)) {
+        constexpr bool GATED = decltype(gated_tag)::value, BIAS = decltype(bias_tag)::value;
+        constexpr bool GELU = decltype(gelu_tag)::value, RES = decltype(res_tag)::value;
+        constexpr int OT = GATED ? NT / 2 : NT;                     // output tiles along N of this wave
+        constexpr int NP = OT / 2;                                  // pairs of them
+        static_assert(OT % 2 == 0, "tiles are exchanged in pairs");
+        // 8-wave work-groups have half the registers per wave: the bias stays packed (unpacked at every
+        // use) and the residual is loaded row by row instead of one row ahead
+        constexpr bool LEAN = NWAVES > 4;
+        const int col = (q & 1) * 16 + (q >> 1) * 8;                // the lane's first column inside a pair
+        const __amdgpu_buffer_rsrc_t rsrc_c = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)wave_uniform((const char *)(C + (int64_t)m_wave * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+        const uint32_t voff_c = (uint32_t)((r16 * (int)p.ldc + col) * 2);
+        const uint32_t row_c = (uint32_t)(16 * (int)p.ldc * 2);     // bytes per tile row of C
+        __amdgpu_buffer_rsrc_t rsrc_r = rsrc_c;
+        uint32_t voff_r = 0, row_r = 0;
+        if constexpr (RES) {
+            rsrc_r = __builtin_amdgcn_make_buffer_rsrc((void *)wave_uniform((const char *)(R + (int64_t)m_wave * p.ldr + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+            voff_r = (uint32_t)((r16 * (int)p.ldr + col) * 2);
+            row_r = (uint32_t)(16 * (int)p.ldr * 2);
+        }
+        float bv[LEAN ? 1 : NP][8];
+        u32x4_t bp[LEAN ? NP : 1];
+        if constexpr (BIAS) {
+#pragma unroll
+            for (int pr = 0; pr < NP; ++pr) {
+                const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + col + pr * 32);
+                if constexpr (LEAN) bp[pr] = b4;
+                else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { bv[pr][2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[pr][2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+                }
+            }
+        }
+        u32x4_t rb[LEAN ? 1 : 2][NP];                               // residual of the row in work (and of the next one)
+        auto load_res = [&](int mt) __attribute__((always_inline)) {
+            if constexpr (RES) {
+#pragma unroll
+                for (int pr = 0; pr < NP; ++pr)
+                    rb[LEAN ? 0 : (mt & 1)][pr] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, voff_r + mt * row_r + pr * 64, 0, 0);
+            }
+        };
+        if constexpr (!LEAN) load_res(0);
+        static_for<MT>([&](auto mt_) __attribute__((always_inline)) {
+            constexpr int mt = decltype(mt_)::value;
+            if constexpr (LEAN) load_res(mt);
+            else if constexpr (mt + 1 < MT) load_res(mt + 1);
+            const uint32_t vo = voff_c + mt * row_c;
+            static_for<NP>([&](auto pr_) __attribute__((always_inline)) {
+                constexpr int pr = decltype(pr_)::value;
+                f32x4_t x0 = AccTile<mt * NT + 2 * pr>::get(), x1 = AccTile<mt * NT + 2 * pr + 1>::get();
+                if constexpr (GATED) {
+                    const f32x4_t u0 = AccTile<mt * NT + OT + 2 * pr>::get(), u1 = AccTile<mt * NT + OT + 2 * pr + 1>::get();
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { x0[e] = silu(x0[e]) * u0[e]; x1[e] = silu(x1[e]) * u1[e]; }
+                }
+                float z[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a0 = x0[e], a1 = x1[e];      // (a bit cast applied to a vector element directly reads element 0)
+                    const auto sw = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(uint32_t, a0), __builtin_bit_cast(uint32_t, a1), false, false);
+                    z[e] = __builtin_bit_cast(float, (uint32_t)sw[0]);
+                    z[4 + e] = __builtin_bit_cast(float, (uint32_t)sw[1]);
+                }
+                if constexpr (BIAS) {
+                    if constexpr (LEAN) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bp[pr][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bp[pr][e] >> 16); }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) z[e] += bv[pr][e];
+                    }
+                }
+                if constexpr (GELU) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                }
+                if constexpr (RES) {
+                    const u32x4_t r4 = rb[LEAN ? 0 : (mt & 1)][pr];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(r4[e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(r4[e] >> 16); }
+                }
+                u32x4_t o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
+                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                }
+                // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
+                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + pr * 64, 0, 0);
+            });
+        });
+    };
+    bool in_registers = false;
+    if (fast && !in_tail && !p.c_f32) {
+        const int what = (p.bias ? 1 : 0) | (p.act == ACT_GELU_TANH ? 2 : 0) | (R ? 4 : 0);
+        constexpr std::true_type T{};
+        constexpr std::false_type F{};
+        in_registers = true;
+        if (!gated) {
+            switch (what) {
+            case 0: reg_epilogue(F, F, F, F); break;
+            case 1: reg_epilogue(F, T, F, F); break;
+            case 2: reg_epilogue(F, F, T, F); break;
+            case 3: reg_epilogue(F, T, T, F); break;
+            case 4: reg_epilogue(F, F, F, T); break;
+            case 5: reg_epilogue(F, T, F, T); break;
+            case 6: reg_epilogue(F, F, T, T); break;
+            default: reg_epilogue(F, T, T, T); break;
+            }
+        } else if constexpr (NT % 4 == 0) {
+            if (R) reg_epilogue(T, F, F, T); else reg_epilogue(T, F, F, F);
+        } else {
+            in_registers = false;
+        }
+    }
+
+    if (!in_registers)
     static_for<WTM / EPI_ROWS>([&](auto pass_) __attribute__((always_inline)) {
         constexpr int pass = decltype(pass_)::value;
         if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
