@@ -894,7 +894,7 @@ gemm_kernel(const GemmArgs p)
         const int n = n_wave + c8 * 8;
         float bv[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) bv[e] = 0.0f;
+        for (int e = 0; e < 8; ++e) bv[e] = -0.0f;               // without a bias: the addend that leaves every value, a signed zero too, as it is
         if (p.bias) {
             const u32x4_t b4 = *(const u32x4_t *)(p.bias + n);
 #pragma unroll
@@ -984,7 +984,7 @@ gemm_kernel(const GemmArgs p)
         if constexpr (LPR != LPR_USED) { if (c8 >= LPR_USED) return; }      // 96- or 48-wide wave tiles: the lanes past a row's end idle
         float bv[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) bv[e] = 0.0f;
+        for (int e = 0; e < 8; ++e) bv[e] = -0.0f;               // without a bias: the addend that leaves every value, a signed zero too, as it is
         if (p.bias) {
             const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + c8 * 8);
 #pragma unroll

@@ -204,6 +204,25 @@ def test_gate_wiring_exact():
     assert np.allclose(ref.widen(got), want, rtol=2 ** -7, atol=1e-6)
 
 
+def test_gated_epilogue_keeps_the_sign_of_zero_in_every_config():
+    # g = 0 exactly and u = -1: SiLU(0) * (-1) = -0, and without a bias nothing may turn it
+    # into +0 (two such elements turn up in the 32768 x 14336 Llama gate/up output); with
+    # u = +1 the result is +0.  Every tile configuration must give the oracle's bits.
+    M, K, I = 512, 64, 384
+    X = torch.zeros(M, K)
+    X[:, 0] = 1.0
+    Wg = torch.zeros(I, K)                          # g_j = 0
+    Wu = torch.zeros(I, K)
+    Wu[:, 0] = torch.where(torch.arange(I) % 2 == 0, -1.0, 1.0)
+    X = X.to(torch.bfloat16)
+    W = torch.cat([Wg, Wu]).to(torch.bfloat16)
+    want = ref.gemm_epilogue(X, W, True, act=fact.ACT_SILU_GATE).bits
+    assert set(np.unique(want[:, 0::2]).tolist()) == {0x8000} and set(np.unique(want[:, 1::2]).tolist()) == {0}
+    for cfg in cfgs(1):
+        got = G().gemm(X, W, 1, act=fact.ACT_SILU_GATE, cfg=cfg)
+        assert np.array_equal(got, want), f"cfg {cfg}"
+
+
 # ---- random inputs, the five configurations at reduced size -------------------------------------
 
 def test_config1_full():
