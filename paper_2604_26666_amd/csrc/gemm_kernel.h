@@ -263,7 +263,7 @@ gemm_kernel(const GemmArgs p)
     static_assert(WTM % 16 == 0 && WTN % 32 == 0, "wave tile must be made of 16x16 MFMA tiles, an even number along N");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "tile must split into whole wave loads");
     static_assert(BK == 64, "BK");
-    static_assert((STAGES - 2) * (LOADS + 1) + 1 <= 63 && STAGES >= 2 && STAGES <= 4, "vmcnt range");
+    static_assert((STAGES - 2) * (LOADS + 1) + 1 <= 63 && STAGES >= 2, "vmcnt range");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -776,16 +776,10 @@ gemm_kernel(const GemmArgs p)
     // (all-zero) steps.
     int kt = 0;
     for (; kt + 2 * STAGES - 1 < ksteps; kt += STAGES) {
-        body(kt, std::integral_constant<int, 0>{}, std::true_type{});
-        body(kt + 1, std::integral_constant<int, 1 % STAGES>{}, std::true_type{});
-        if constexpr (STAGES > 2) body(kt + 2, std::integral_constant<int, 2 % STAGES>{}, std::true_type{});
-        if constexpr (STAGES > 3) body(kt + 3, std::integral_constant<int, 3 % STAGES>{}, std::true_type{});
+        static_for<STAGES>([&](auto s_) __attribute__((always_inline)) { body(kt + decltype(s_)::value, s_, std::true_type{}); });
     }
     for (; kt < ksteps; kt += STAGES) {
-        body(kt, std::integral_constant<int, 0>{}, std::false_type{});
-        body(kt + 1, std::integral_constant<int, 1 % STAGES>{}, std::false_type{});
-        if constexpr (STAGES > 2) body(kt + 2, std::integral_constant<int, 2 % STAGES>{}, std::false_type{});
-        if constexpr (STAGES > 3) body(kt + 3, std::integral_constant<int, 3 % STAGES>{}, std::false_type{});
+        static_for<STAGES>([&](auto s_) __attribute__((always_inline)) { body(kt + decltype(s_)::value, s_, std::false_type{}); });
     }
     // drain: the last unit of the last step
     wait_frags((KK - 1) & 1);
@@ -1210,7 +1204,10 @@ gemm_kernel(const GemmArgs p)
                 const f32x4_t x = *(const f32x4_t *)(region + row * EPI_PITCH + c4 * 16);
                 int nc = n0 + wn * WTN + c4 * 4;                       // plain: contraction column = output column
                 if (gated) nc = n0 + wn * (WTN / 2) + (c4 * 4) % (WTN / 2) + ((c4 * 4) / (WTN / 2)) * nout;
-                *(f32x4_t *)(P + (int64_t)(m_wave + pass * EPI_ROWS + row) * p.N + nc) = x;
+                // streaming store: a partial is read once, by the reduction pass, and a line left dirty in
+                // this XCD's L2 would have to be written back before the launch can end (large-K case with
+                // operands from HBM: 43.6 -> 38.7 us for GEMM plus reduction, 30.2 -> 29.4 us from the cache)
+                __builtin_nontemporal_store(x, (f32x4_t *)(P + (int64_t)(m_wave + pass * EPI_ROWS + row) * p.N + nc));
             }
             return;
         }
@@ -1282,7 +1279,7 @@ gemm_kernel(const GemmArgs p)
                             float *dst = P + (int64_t)m * p.N + nc;
                             if (nc + 7 < nlim && (p.N & 3) == 0) {
                                 const f32x4_t y0 = {w[0], w[1], w[2], w[3]}, y1 = {w[4], w[5], w[6], w[7]};
-                                *(f32x4_t *)dst = y0; *(f32x4_t *)(dst + 4) = y1;
+                                __builtin_nontemporal_store(y0, (f32x4_t *)dst); __builtin_nontemporal_store(y1, (f32x4_t *)(dst + 4));
                             } else {
 #pragma unroll
                                 for (int e = 0; e < 8; ++e)
