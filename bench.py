@@ -65,7 +65,7 @@ def time_calls(fn, steps, warmup, prewarm_ms=0.0):
     return start.elapsed_time(stop) / steps
 
 
-def cpu_baseline(rows=1024, n=8192):
+def cpu_baseline(rows=8192, n=8192):
     """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
     import numpy as np
     import workloads as wl

@@ -1,6 +1,7 @@
 """Reads rocprofv3 counter-collection and kernel-trace CSV files and prints per-kernel means.
 
     python -m paper_2604_26666_amd.counters summarise FILE.csv [FILE.csv ...]
+    python -m paper_2604_26666_amd.counters runs KERNEL_TRACE.csv [MIN_LAUNCHES]
     python -m paper_2604_26666_amd.counters traffic-json FETCH.csv WRITE.csv PROBE_STDOUT OUT.json
 
 `summarise` groups the dispatches of each file by (kernel, grid, work-group size) and prints the
@@ -8,6 +9,10 @@ mean of every counter, or of the duration for a kernel trace.  FETCH_SIZE and WR
 dispatch) are also given in bytes, scaled by what the same counter read for the plain 1 GiB
 device-to-device copies that `bench.py --probe` and `bench.py --traffic-probe` append to their
 launches (the last three dispatches of the copy kernel): scale = 2^30 / (1024 x the copy's reading).
+
+`runs` lists, in time order, every run of at least MIN_LAUNCHES (default 20) consecutive launches of
+one (kernel, grid): the timing loops of `bench.py --all`, one per shape, with the average duration
+of the run's second half (its timed part).
 
 `traffic-json` turns the two counter files of `bench.py --traffic-probe` and the line that
 the probe printed into the small file that bench.py quotes as `roofline.traffic`.
@@ -100,6 +105,23 @@ def summarise(paths, out=sys.stdout):
             print(f"   {name}  grid {grid} wg {wg}  dispatches {g['n']}:  " + "; ".join(parts), file=out)
 
 
+def runs(path, min_launches=20, out=sys.stdout):
+    rows = sorted(read(path), key=lambda r: int(r["Start_Timestamp"]))
+    found = []
+    for r in rows:
+        grid = "x".join(r.get(k, "1") for k in ("Grid_Size_X", "Grid_Size_Y", "Grid_Size_Z"))
+        key = (short_name(r["Kernel_Name"]), grid, r.get("Workgroup_Size_X", ""))
+        d = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+        if found and found[-1][0] == key:
+            found[-1][1].append(d)
+        else:
+            found.append((key, [d]))
+    for (name, grid, wg), d in found:
+        if len(d) >= min_launches:
+            half = d[len(d) // 2:]
+            print(f"{name}  grid {grid} wg {wg}  launches {len(d)}  second_half_avg_us {mean(half):.2f}  min_us {min(d):.2f}", file=out)
+
+
 def traffic_json(fetch_csv, write_csv, probe_stdout, out_path):
     probe = None
     with open(probe_stdout) as f:
@@ -131,6 +153,8 @@ def traffic_json(fetch_csv, write_csv, probe_stdout, out_path):
 def main(argv):
     if len(argv) >= 2 and argv[0] == "summarise":
         summarise(argv[1:])
+    elif len(argv) in (2, 3) and argv[0] == "runs":
+        runs(argv[1], int(argv[2]) if len(argv) == 3 else 20)
     elif len(argv) == 5 and argv[0] == "traffic-json":
         traffic_json(*argv[1:])
     else:
