@@ -360,6 +360,22 @@ int fact_tail_timeouts(const void *ws, void *stream, int *gave_up);
  * every kernel still runs to its end.  Process-wide, applies to launches made after the call. */
 void fact_test_tail_poll_budget(int polls);
 
+/*
+ * Persistent launches (the grid-level schedule of Section 4.2 Action 2 next to "Data Parallel" and
+ * "Split-K"; Section 5.2.3 describes the persistent Stream-K form).  With mode 1, a launch with K
+ * whole and a 4-wave tile configuration that has more tiles (times batch entries) than the GPU holds
+ * work-groups at once launches as many work-groups as fit, and each walks several tiles in the
+ * XCD-aware order; the first operand stages of a work-group's next tile are requested before the
+ * epilogue of the tile in hand runs.  Results are bit-identical either way.  Default: mode 0, one
+ * work-group per tile everywhere - on this chip the persistent form measured 0.5-3 % slower on the
+ * benchmark shapes (what the overlap saves per tile, the state carried from tile to tile costs).
+ * Process-wide, applies to launches made after the call; returns the previous mode.
+ */
+int fact_tune_persistent(int mode);
+/* Work-groups a launch of this problem with K whole uses when it is persistent, else 0 (config_id < 0:
+ * the table's or the model's configuration; 0 as well when that choice splits K). */
+int fact_persistent_grid(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b, int act, int config_id);
+
 /* ---- misc ------------------------------------------------------------------------------- */
 
 const char *fact_status_string(int status);   /* static string, never NULL */

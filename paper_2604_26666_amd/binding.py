@@ -136,6 +136,10 @@ def lib():
         L.fact_tail_timeouts.restype = _int
         L.fact_test_tail_poll_budget.argtypes = [_int]
         L.fact_test_tail_poll_budget.restype = None
+        L.fact_tune_persistent.argtypes = [_int]
+        L.fact_tune_persistent.restype = _int
+        L.fact_persistent_grid.argtypes = [_i64, _i64, _i64, _i64, _int, _int, _int]
+        L.fact_persistent_grid.restype = _int
         L.fact_registry_load.argtypes = [ctypes.c_char_p]
         L.fact_registry_load.restype = _int
         L.fact_registry_clear.argtypes = []
@@ -288,6 +292,14 @@ def fact_tail_timeouts(ws, stream=None):
 
 def fact_test_tail_poll_budget(polls):
     lib().fact_test_tail_poll_budget(int(polls))
+
+
+def fact_tune_persistent(mode):
+    return lib().fact_tune_persistent(int(mode))
+
+
+def fact_persistent_grid(batch, M, N, K, trans_b, act=ACT_NONE, cfg=-1):
+    return lib().fact_persistent_grid(batch, M, N, K, int(trans_b), int(act), int(cfg))
 
 
 def fact_registry_load(path):

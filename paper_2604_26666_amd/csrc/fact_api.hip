@@ -61,6 +61,7 @@ static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 static const unsigned long long g_tail_epoch_first =
     (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull;
 static std::atomic<unsigned long long> g_tail_epoch{g_tail_epoch_first};
+static std::atomic<int> g_persistent{0};                  // fact_tune_persistent (off unless asked for: measured 0.5-3 % slower than ordinary launches)
 static std::atomic<int> g_tail_budget{1 << 20};           // polls (about 0.3 us each) a collecting work-group waits: a third of a second
 
 // Can the MFMA kernel take these operands at all?  (Dimensions only; pointer alignment is
@@ -88,6 +89,16 @@ static double tile_efficiency(const ConfigDesc &c)
 {
     const double per_k = (double)(c.bm + c.bn) / ((double)c.bm * c.bn);   // operand bytes per MAC
     return 1.0 / (1.0 + 48.0 * per_k);
+}
+
+// Work-groups of a persistent launch of `items` tiles (times batch entries) with K whole, or 0 when the
+// launch is an ordinary one: every item fits at once, an 8-wave configuration (see the kernel), or
+// switched off.  A multiple of 8, so a work-group stays on its XCD's part of the tile order.
+static int persistent_grid(const ConfigDesc &c, int64_t items)
+{
+    if (c.wm * c.wn > 4 || !g_persistent.load(std::memory_order_relaxed)) return 0;
+    const int64_t slots = (int64_t)kNumCU * wgs_per_cu(c);
+    return items > slots && items <= INT32_MAX / 2 ? (int)slots : 0;
 }
 
 struct Plan {
@@ -377,6 +388,12 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         if (ws_bytes < need) return FACT_ERR_WORKSPACE;
         a.P = (float *)ws;
     }
+    // Persistent launch: more work items than resident work-groups, K whole, no tail split.
+    a.persist_items = 0; a.persist_z = 1; a.persist_grid = 0;
+    if (a.tail_g <= 1 && a.splits <= 1) {
+        const int grid = persistent_grid(c, tiles_m * tiles_n * q.batch);
+        if (grid > 0) { a.persist_items = (int)(tiles_m * tiles_n * q.batch); a.persist_z = (int)q.batch; a.persist_grid = grid; }
+    }
     // (the kernel numbers (K range or batch entry, tile) pairs with 32-bit integers)
     if (tiles_m * tiles_n * (a.splits > 1 ? (int64_t)a.splits : q.batch) > INT32_MAX / 2) return FACT_ERR_DIM;
     e = c.launch(a, q.trans_b != 0, a.splits > 1 ? a.splits : (int)q.batch, stream);
@@ -577,6 +594,21 @@ int fact_select_config(int64_t batch, int64_t M, int64_t N, int64_t K, int trans
     return FACT_OK;
 }
 
+int fact_persistent_grid(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b, int act, int config_id)
+{
+    if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return 0;
+    if (config_id < 0) {
+        Plan pl = make_plan(batch, M, N, K, trans_b, act, false);
+        if (pl.split != 1) return 0;
+        config_id = pl.cfg;
+    }
+    if (config_id < 0 || config_id >= kNumConfigs) return 0;
+    const ConfigDesc &c = g_configs[config_id];
+    const int64_t nout = act == FACT_ACT_SILU_GATE ? N / 2 : N;
+    const int bn_out = act == FACT_ACT_SILU_GATE ? c.bn / 2 : c.bn;
+    return persistent_grid(c, ((M + c.bm - 1) / c.bm) * ((nout + bn_out - 1) / bn_out) * batch);
+}
+
 const char *fact_status_string(int status)
 {
     switch (status) {
@@ -668,6 +700,7 @@ int fact_tail_timeouts(const void *ws, void *stream, int *gave_up)
 }
 
 void fact_test_tail_poll_budget(int polls) { g_tail_budget.store(polls, std::memory_order_relaxed); }
+int fact_tune_persistent(int mode) { return fact::g_persistent.exchange(mode != 0 ? 1 : 0, std::memory_order_relaxed); }
 
 // Registry file: text, one entry per line (see include/fact.h).  Entries of another rule, data type
 // or architecture are skipped, as are entries naming a configuration this build does not have or

@@ -64,6 +64,11 @@ struct GemmArgs {
     unsigned long long *tail_status;  // workspace word that takes the launch's epoch when a hand-over wait gave up
     unsigned long long tail_epoch;    // value a flag takes when its partial of THIS launch is complete
     int tail_budget;                  // polls the collecting work-group of a tile spends on its partners' flags (< 0: gives up at once)
+    // Persistent launch: grid.x work-groups walk persist_items work items (tiles x batch entries), work-group w
+    // taking items w, w + grid.x, ...; 0: one item per work-group (grid.z = batch entry or K range).
+    int persist_items;
+    int persist_z;                    // batch entries of a persistent launch
+    int persist_grid;                 // work-groups of a persistent launch (host side only)
 };
 
 constexpr uint32_t kBufferFlags = 0x00020000u;   // raw buffer descriptor word 3 (32-bit data format)
@@ -243,7 +248,28 @@ template <int T> struct AccTile;
 #include "acc_regs.inc"
 #undef FACT_ACC_TILE
 
-template <int BM, int BN, int WGM, int WGN, bool TRANS_B, int BK, int STAGES>
+// The launch's parameters, read afresh from the kernel-argument segment.  A persistent work-group
+// walks several tiles; with the by-value argument the compiler loads every field once at the
+// kernel's start and carries all of them across the K loop for the next tile (some 60 scalar
+// registers: it ran out and parked ~300 of them in vector-register lanes, +2.4 us per tile).  Behind
+// this opaque pointer each tile's set-up and each epilogue load what they use where they use it.
+__device__ __forceinline__ GemmArgs fresh_args()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef const __attribute__((address_space(4))) GemmArgs *kernarg_ptr_t;
+    kernarg_ptr_t k = (kernarg_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();       // GemmArgs is the kernel's only argument
+    asm volatile("" : "+s"(k));
+    GemmArgs a;
+    __builtin_memcpy(&a, k, sizeof a);
+    return a;
+#else
+    return GemmArgs{};
+#endif
+}
+
+// PERSIST: the work-group walks several work items (persistent launch; 4-wave configurations only).  The
+// ordinary kernel is a separate instantiation in which the loop below is gone at compile time.
+template <int BM, int BN, int WGM, int WGN, bool TRANS_B, int BK, int STAGES, bool PERSIST>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_kernel(const GemmArgs p)
 {
@@ -267,10 +293,587 @@ gemm_kernel(const GemmArgs p)
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
+
+    // ---- what the epilogue needs of its tile ------------------------------------------------
+    // A work-group may walk several tiles (persistent launch).  The epilogue of a tile runs when the
+    // next tile's first operand stages have been requested, so it must not look at anything the
+    // loop below derives for the tile in hand: these variables are set when a tile's K loop ends.
+    int e_tm = 0, e_tn = 0, e_z = 0;                  // tile coordinates, batch entry or K range
+    bool e_in_regs = false;                           // it takes the register path
+    bool e_in_tail = false, tail_gave_up = false;     // tail split: a shared tile; its collecting wait gave up
+    int e_tail_seg = 0, e_tail_tile = 0;              // tail split: K range number, tile number within the tail
+    constexpr int TILE_FLOATS = BM * BN;
+    constexpr int kSysScope = 17;                    // cache-policy bits sc0 | sc1 of buffer loads / stores
+
+    // ---- epilogue ---------------------------------------------------------------------------
+    // Accumulator tile (mt, nt), lane (r16, q): output row mt*16 + r16, output columns
+    // nt*16 + 4q .. + 3: a lane owns pieces of one row per tile, so a direct store would write
+    // 16-byte pieces of 16 different rows per instruction.  Instead each wave transposes its
+    // accumulators through its own LDS region (fp32, EPI_ROWS rows at a time) and reads them
+    // back row-wise: a lane then holds 8 consecutive columns of one row and all epilogue
+    // arithmetic happens there, in fp32, in registers:
+    //     z = acc + bias[n];  z = act(z);  z = z + residual[m][n];  store bf16(z)
+    // with 16-byte loads of bias / residual and 16-byte stores (whole 128-byte lines per row).
+    // Region row pitch = row bytes + 16, which spreads the 16 rows a write instruction touches
+    // over all banks.  Only the wave itself reads what it wrote: no work-group barrier inside.
+    constexpr int EPI_PITCH = epi_pitch(WTN);
+    constexpr int EPI_ROWS = epi_rows(WTM, WTN, NWAVES);
+    constexpr int EPI_TR = EPI_ROWS / 16;                       // tile-rows per pass
+    constexpr int EPI_REGION = EPI_ROWS * EPI_PITCH;
+    static_assert(lds_total(BM, BN, WGM, WGN, BK, STAGES) <= 160 * 1024 && NWAVES * EPI_REGION <= lds_bytes(BM, BN, WGM, WGN, BK, STAGES) && WTM % EPI_ROWS == 0, "LDS budget");
+    // IN_REGS: the register path (interior tile, bf16 output, no hand-over); it touches no LDS, so the
+    // operand ring may be filling for the next tile while it runs.  Otherwise the LDS-staged passes.
+    auto epilogue = [&](auto in_regs_tag) __attribute__((always_inline)) {
+    constexpr bool IN_REGS = decltype(in_regs_tag)::value;
+    const bool gated = (p.act == ACT_SILU_GATE);
+    const int nout = gated ? (p.N >> 1) : p.N;
+    const bool partial = p.splits > 1 || p.out_f32;
+    // The lane's position is derived anew here, so that nothing of it stays live in a vector register
+    // across the K loop (the 8-wave kernels have no register to spare for that).
+    const int tid = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) + wave * 64;
+    const int lane = tid & 63;
+    const int r16 = lane & 15, q = lane >> 4;
+    if constexpr (!IN_REGS) __syncthreads();                    // every wave is done with the operand stages
+    char *region = smem + wave * EPI_REGION;
+    const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns
+    const int lanes_per_row = out_w / 8;
+    const int e_n0 = e_tn * (gated ? BN / 2 : BN);              // first OUTPUT column of the tile
+    const int n_wave = e_n0 + wn * out_w;                       // first output column of this wave
+    const int m_wave = e_tm * BM + wm * WTM;
+    float *P = partial ? p.P + (int64_t)e_z * p.M * p.N : nullptr;       // split-K: this K range's plane of partials
+    const bool batched = !e_in_tail && p.splits <= 1;            // e_z is a batch entry (a K range otherwise)
+    __bf16 *C = p.C + (batched ? e_z * p.stride_c : 0);
+    float *Cf = (float *)p.C + (batched ? e_z * p.stride_c : 0);       // the same matrix when it holds fp32 (c_f32)
+    const __bf16 *R = p.res ? p.res + (batched ? e_z * p.stride_r : 0) : nullptr;
+    // Fast path: the wave's whole tile lies inside C and everything allows 16-byte access.  Straight
+    // code, no per-element guards: the general path spends most of its time in them.
+    const bool fast = !partial && p.vec_store && m_wave + WTM <= p.M && n_wave + out_w <= nout;
+    // (8-wave work-groups have half the registers per wave: they keep to the general path here)
+    const bool fast_partial = NWAVES <= 4 && partial && (p.N & 3) == 0 && (nout & 3) == 0 && m_wave + WTM <= p.M && n_wave + out_w <= nout;
+    const int tail_parts = e_in_tail ? p.tail_g - 1 : 0;
+    const bool tail_producer = e_in_tail && e_tail_seg < tail_parts;
+    const __amdgpu_buffer_rsrc_t rsrc_part = __builtin_amdgcn_make_buffer_rsrc(      // this tile's partials
+        (void *)wave_uniform((const char *)(e_in_tail ? p.tail_ws + (int64_t)e_tail_tile * tail_parts * TILE_FLOATS : nullptr)), 0,
+        (uint32_t)(tail_parts * TILE_FLOATS * 4), kBufferFlags);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    auto fast_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
+        constexpr bool GATED = decltype(gated_tag)::value;
+        constexpr int OUT_W = GATED ? WTN / 2 : WTN;
+        constexpr int LPR_USED = OUT_W / 8;                         // lanes a row needs
+        constexpr int LPR = LPR_USED <= 1 ? 1 : LPR_USED <= 2 ? 2 : LPR_USED <= 4 ? 4 : LPR_USED <= 8 ? 8 : LPR_USED <= 16 ? 16 : 32;
+        constexpr int TOTAL = EPI_ROWS * LPR;                       // (a power of two of lanes is set aside per row)
+        constexpr int FU = NWAVES > 4 ? 2 : 4;                      // row-chunks per lane and batch
+        static_assert(64 % LPR == 0 && TOTAL % 64 == 0, "a lane keeps its columns; batches are whole waves");
+        const int c8 = lane % LPR;
+        if constexpr (LPR != LPR_USED) { if (c8 >= LPR_USED) return; }      // 96- or 48-wide wave tiles: the lanes past a row's end idle
+        const int n = n_wave + c8 * 8;
+        float bv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bv[e] = -0.0f;               // without a bias: the addend that leaves every value, a signed zero too, as it is
+        if (p.bias) {
+            const u32x4_t b4 = *(const u32x4_t *)(p.bias + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+        }
+        const int act = p.act;
+#pragma unroll
+        for (int base = 0; base < TOTAL; base += 64 * FU) {
+            u32x4_t rb[FU];
+            f32x4_t x[FU][2], y[FU][2];
+            int row[FU];
+#pragma unroll
+            for (int j = 0; j < FU; ++j) {
+                if (base + 64 * j < TOTAL) {
+                    row[j] = (base + 64 * j + lane) / LPR;
+                    if (R) rb[j] = *(const u32x4_t *)(R + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldr + n);
+                    const char *src = region + row[j] * EPI_PITCH + c8 * 32;
+                    x[j][0] = *(const f32x4_t *)src; x[j][1] = *(const f32x4_t *)(src + 16);
+                    if constexpr (GATED) { y[j][0] = *(const f32x4_t *)(src + OUT_W * 4); y[j][1] = *(const f32x4_t *)(src + OUT_W * 4 + 16); }
+                    // last K range of a split tail tile: add the other ranges' partial sums, in range order
+                    for (int sgm = 0; sgm < tail_parts; ++sgm) {
+                        const int ps = ((wm * WTM + pass * EPI_ROWS + row[j]) * BN + wn * WTN + c8 * 8) * 4, so = sgm * TILE_FLOATS * 4;
+                        auto ld = [&](int off) { return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_part, ps + off, so, kSysScope)); };
+                        x[j][0] += ld(0); x[j][1] += ld(16);
+                        if constexpr (GATED) { y[j][0] += ld(OUT_W * 4); y[j][1] += ld(OUT_W * 4 + 16); }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < FU; ++j) {
+                if (base + 64 * j < TOTAL) {
+                    float z[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        z[e] = x[j][e >> 2][e & 3];
+                        if constexpr (GATED) z[e] = silu(z[e]) * y[j][e >> 2][e & 3];
+                        z[e] += bv[e];
+                    }
+                    if (act == ACT_GELU_TANH) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                    }
+                    if (R) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                    }
+                    if (tail_gave_up) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) z[e] = __builtin_nanf("");
+                    }
+                    if (p.c_f32) {
+                        float *cf = Cf + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n;
+                        *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
+                        *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
+                        continue;
+                    }
+                    u32x4_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
+                        o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                    }
+                    *(u32x4_t *)(C + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n) = o;
+                }
+            }
+        }
+    };
+
+    // The same pass as a short loop (bf16 output, no partial sums of other K ranges to add): the
+    // read-back of a pass is not unrolled, so the whole epilogue is a few hundred instructions that
+    // stay in the instruction cache from tile to tile (straight-line code of several thousand
+    // instructions was measured to run at the speed of its instruction fetch: 9-15 us per
+    // 256 x 256 tile on a compute unit's first tile).  C and the residual are addressed through
+    // buffer descriptors of the wave's tile with one lane-offset register each that advances by a
+    // constant per iteration (32-bit offsets: the host sets vec_store only if a tile's rows span
+    // less than 2^31 bytes).
+    auto compact_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
+        constexpr bool GATED = decltype(gated_tag)::value;
+        constexpr int OUT_W = GATED ? WTN / 2 : WTN;
+        constexpr int LPR_USED = OUT_W / 8;
+        constexpr int LPR = LPR_USED <= 1 ? 1 : LPR_USED <= 2 ? 2 : LPR_USED <= 4 ? 4 : LPR_USED <= 8 ? 8 : LPR_USED <= 16 ? 16 : 32;
+        constexpr int RPB = 64 / LPR;                               // rows a wave-wide access covers
+        constexpr int NB = EPI_ROWS / RPB;                          // such accesses per pass
+        constexpr int FU0 = NWAVES > 4 ? 2 : 4, FU = NB < FU0 ? NB : FU0;       // of them per loop iteration
+        static_assert(64 % LPR == 0 && NB % FU == 0, "a lane keeps its columns; iterations are whole");
+        const int c8 = lane % LPR, lrow = lane / LPR;
+        if constexpr (LPR != LPR_USED) { if (c8 >= LPR_USED) return; }      // 96- or 48-wide wave tiles: the lanes past a row's end idle
+        float bv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bv[e] = -0.0f;               // without a bias: the addend that leaves every value, a signed zero too, as it is
+        if (p.bias) {
+            const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + c8 * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+        }
+        const bool gelu = p.act == ACT_GELU_TANH, has_res = R != nullptr;
+        const int64_t row0 = m_wave + pass * EPI_ROWS;
+        const __amdgpu_buffer_rsrc_t rsrc_c = __builtin_amdgcn_make_buffer_rsrc((void *)wave_uniform((const char *)(C + row0 * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+        const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)wave_uniform((const char *)(has_res ? R + row0 * p.ldr + n_wave : C + row0 * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+        uint32_t vo = (uint32_t)((lrow * (int)p.ldc + c8 * 8) * 2), vr = (uint32_t)((lrow * (int)p.ldr + c8 * 8) * 2);
+        const uint32_t step_c = (uint32_t)(RPB * (int)p.ldc * 2), step_r = (uint32_t)(RPB * (int)p.ldr * 2);
+        const char *src = region + lrow * EPI_PITCH + c8 * 32;
+#pragma nounroll
+        for (int it = 0; it < NB / FU; ++it) {
+            u32x4_t rb[FU];
+            f32x4_t x[FU][2], y[FU][2];
+#pragma unroll
+            for (int j = 0; j < FU; ++j) {
+                if (has_res) rb[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, vr + j * step_r, 0, 0);
+                const char *sj = src + j * RPB * EPI_PITCH;
+                x[j][0] = *(const f32x4_t *)sj; x[j][1] = *(const f32x4_t *)(sj + 16);
+                if constexpr (GATED) { y[j][0] = *(const f32x4_t *)(sj + OUT_W * 4); y[j][1] = *(const f32x4_t *)(sj + OUT_W * 4 + 16); }
+            }
+#pragma unroll
+            for (int j = 0; j < FU; ++j) {
+                float z[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    z[e] = x[j][e >> 2][e & 3];
+                    if constexpr (GATED) z[e] = silu(z[e]) * y[j][e >> 2][e & 3];
+                    z[e] += bv[e];
+                }
+                if (gelu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                }
+                if (has_res) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                }
+                u32x4_t o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
+                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                }
+                // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
+                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + j * step_c, 0, 0);
+            }
+            vo += FU * step_c; vr += FU * step_r; src += FU * RPB * EPI_PITCH;
+        }
+    };
+
+    // Register path (interior wave tiles with 16-byte access, bf16 output, no K hand-over): no LDS at
+    // all (the transposing path above moves 1 MB through LDS per 256 x 256 tile, 4 us of LDS time).
+    // Two neighbouring 16 x 16 accumulator tiles exchange 16-lane rows (v_permlane16_swap: the odd
+    // rows of the first operand with the even rows of the second), after which lane (r16, q) holds 8
+    // consecutive columns of output row r16: tile q & 1 of the pair, columns 8 (q >> 1) .. + 7.
+    // Bias, activation, residual and the single rounding happen there, in fp32, and every lane
+    // stores 16 bytes: the four lanes of a row write 64 consecutive bytes, the next pair of tiles
+    // the other half of the 128-byte line.  (Gated: gate and up values of an element sit in the
+    // same lane, so SiLU(gate) * up is formed before the exchange.)  What the epilogue adds is
+    // fixed at compile time (one instance per combination, chosen once), so the code is straight;
+    // C and the residual are addressed through buffer descriptors of the wave's tile with one
+    // lane-offset register each (32-bit offsets: the host sets vec_store only if a tile's rows span
+    // less than 2^31 bytes), a tile row adds one vector add, a pair an immediate offset.
+    auto reg_epilogue = [&](auto gated_tag, auto bias_tag, auto gelu_tag, auto res_tag) __attribute__((always_inline)) {
+        constexpr bool GATED = decltype(gated_tag)::value, BIAS = decltype(bias_tag)::value;
+        constexpr bool GELU = decltype(gelu_tag)::value, RES = decltype(res_tag)::value;
+        constexpr int OT = GATED ? NT / 2 : NT;                     // output tiles along N of this wave
+        constexpr int NP = OT / 2;                                  // pairs of them
+        static_assert(OT % 2 == 0, "tiles are exchanged in pairs");
+        // 8-wave work-groups have half the registers per wave: the bias stays packed (unpacked at every
+        // use) and the residual is loaded row by row instead of one row ahead
+        constexpr bool LEAN = NWAVES > 4;
+        const int col = (q & 1) * 16 + (q >> 1) * 8;                // the lane's first column inside a pair
+        const __amdgpu_buffer_rsrc_t rsrc_c = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)wave_uniform((const char *)(C + (int64_t)m_wave * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+        const uint32_t voff_c = (uint32_t)((r16 * (int)p.ldc + col) * 2);
+        const uint32_t row_c = (uint32_t)(16 * (int)p.ldc * 2);     // bytes per tile row of C
+        __amdgpu_buffer_rsrc_t rsrc_r = rsrc_c;
+        uint32_t voff_r = 0, row_r = 0;
+        if constexpr (RES) {
+            rsrc_r = __builtin_amdgcn_make_buffer_rsrc((void *)wave_uniform((const char *)(R + (int64_t)m_wave * p.ldr + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
+            voff_r = (uint32_t)((r16 * (int)p.ldr + col) * 2);
+            row_r = (uint32_t)(16 * (int)p.ldr * 2);
+        }
+        float bv[LEAN ? 1 : NP][8];
+        u32x4_t bp[LEAN ? NP : 1];
+        if constexpr (BIAS) {
+#pragma unroll
+            for (int pr = 0; pr < NP; ++pr) {
+                const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + col + pr * 32);
+                if constexpr (LEAN) bp[pr] = b4;
+                else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { bv[pr][2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[pr][2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+                }
+            }
+        }
+        u32x4_t rb[LEAN ? 1 : 2][NP];                               // residual of the row in work (and of the next one)
+        auto load_res = [&](int mt) __attribute__((always_inline)) {
+            if constexpr (RES) {
+#pragma unroll
+                for (int pr = 0; pr < NP; ++pr)
+                    rb[LEAN ? 0 : (mt & 1)][pr] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, voff_r + mt * row_r + pr * 64, 0, 0);
+            }
+        };
+        if constexpr (!LEAN) load_res(0);
+        static_for<MT>([&](auto mt_) __attribute__((always_inline)) {
+            constexpr int mt = decltype(mt_)::value;
+            if constexpr (LEAN) load_res(mt);
+            else if constexpr (mt + 1 < MT) load_res(mt + 1);
+            const uint32_t vo = voff_c + mt * row_c;
+            static_for<NP>([&](auto pr_) __attribute__((always_inline)) {
+                constexpr int pr = decltype(pr_)::value;
+                f32x4_t x0 = AccTile<mt * NT + 2 * pr>::get(), x1 = AccTile<mt * NT + 2 * pr + 1>::get();
+                if constexpr (GATED) {
+                    const f32x4_t u0 = AccTile<mt * NT + OT + 2 * pr>::get(), u1 = AccTile<mt * NT + OT + 2 * pr + 1>::get();
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { x0[e] = silu(x0[e]) * u0[e]; x1[e] = silu(x1[e]) * u1[e]; }
+                }
+                float z[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a0 = x0[e], a1 = x1[e];      // (a bit cast applied to a vector element directly reads element 0)
+                    const auto sw = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(uint32_t, a0), __builtin_bit_cast(uint32_t, a1), false, false);
+                    z[e] = __builtin_bit_cast(float, (uint32_t)sw[0]);
+                    z[4 + e] = __builtin_bit_cast(float, (uint32_t)sw[1]);
+                }
+                if constexpr (BIAS) {
+                    if constexpr (LEAN) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bp[pr][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bp[pr][e] >> 16); }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) z[e] += bv[pr][e];
+                    }
+                }
+                if constexpr (GELU) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                }
+                if constexpr (RES) {
+                    const u32x4_t r4 = rb[LEAN ? 0 : (mt & 1)][pr];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(r4[e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(r4[e] >> 16); }
+                }
+                u32x4_t o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
+                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                }
+                // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
+                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + pr * 64, 0, 0);
+            });
+        });
+    };
+    if constexpr (IN_REGS) {
+        const int what = (p.bias ? 1 : 0) | (p.act == ACT_GELU_TANH ? 2 : 0) | (R ? 4 : 0);
+        constexpr std::true_type T{};
+        constexpr std::false_type F{};
+        if (!gated) {
+            switch (what) {
+            case 0: reg_epilogue(F, F, F, F); break;
+            case 1: reg_epilogue(F, T, F, F); break;
+            case 2: reg_epilogue(F, F, T, F); break;
+            case 3: reg_epilogue(F, T, T, F); break;
+            case 4: reg_epilogue(F, F, F, T); break;
+            case 5: reg_epilogue(F, T, F, T); break;
+            case 6: reg_epilogue(F, F, T, T); break;
+            default: reg_epilogue(F, T, T, T); break;
+            }
+        } else if constexpr (NT % 4 == 0) {
+            if (R) reg_epilogue(T, F, F, T); else reg_epilogue(T, F, F, F);
+        }
+    } else {
+    static_for<WTM / EPI_ROWS>([&](auto pass_) __attribute__((always_inline)) {
+        constexpr int pass = decltype(pass_)::value;
+        if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
+        {
+            const uint32_t dst = (uint32_t)(size_t)FACT_LDS_PTR(region + r16 * EPI_PITCH + q * 16);
+            static_for<EPI_TR * NT>([&](auto w_) __attribute__((always_inline)) {
+                constexpr int i = decltype(w_)::value / NT, nt = decltype(w_)::value % NT;
+                AccTile<(pass * EPI_TR + i) * NT + nt>::template to_lds<i * 16 * EPI_PITCH + nt * 64>(dst);
+            });
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
+        const int total = EPI_ROWS * lanes_per_row;
+        if (tail_producer) {
+            // partial tile, fp32 row-major [BM][BN] in accumulator column order (gated: gate columns,
+            // then up columns, per wave); the wave's EPI_ROWS x WTN block of this pass, 16 bytes per lane
+            constexpr int LPR4 = WTN / 4;
+            const int dst = (e_tail_seg * TILE_FLOATS + (wm * WTM + pass * EPI_ROWS) * BN + wn * WTN) * 4;     // bytes
+#pragma unroll
+            for (int base = 0; base < EPI_ROWS * LPR4; base += 64) {
+                const int idx = base + lane, row = idx / LPR4, c4 = idx % LPR4;
+                const u32x4_t x = *(const u32x4_t *)(region + row * EPI_PITCH + c4 * 16);
+                // The whole offset goes into the per-lane operand, the scalar one stays the constant 0:
+                // with a scalar-register offset the compiler assumes that the data registers of a
+                // 16-byte buffer store may be overwritten in the very next cycle, and on this chip
+                // the last lanes of each 16 then stored the overwriting value (seen as the next
+                // store's offset inside the partial tile).  With a constant it keeps the wait states.
+                __builtin_amdgcn_raw_buffer_store_b128(x, rsrc_part, dst + (row * BN + c4 * 4) * 4, 0, kSysScope);
+            }
+            return;
+        }
+        if constexpr (NWAVES <= 4) if (fast_partial) {
+            // split-K partials of an interior tile: raw fp32, 16-byte stores, both halves of a gated
+            // tile at their contraction columns
+            constexpr int LPR4 = WTN / 4;                             // lanes per row, 4 columns each
+#pragma unroll
+            for (int base = 0; base < EPI_ROWS * LPR4; base += 64) {
+                const int idx = base + lane, row = idx / LPR4, c4 = idx % LPR4;
+                const f32x4_t x = *(const f32x4_t *)(region + row * EPI_PITCH + c4 * 16);
+                int nc = e_n0 + wn * WTN + c4 * 4;                       // plain: contraction column = output column
+                if (gated) nc = e_n0 + wn * (WTN / 2) + (c4 * 4) % (WTN / 2) + ((c4 * 4) / (WTN / 2)) * nout;
+                // streaming store: a partial is read once, by the reduction pass, and a line left dirty in
+                // this XCD's L2 would have to be written back before the launch can end (large-K case with
+                // operands from HBM: 43.6 -> 38.7 us for GEMM plus reduction, 30.2 -> 29.4 us from the cache)
+                __builtin_nontemporal_store(x, (f32x4_t *)(P + (int64_t)(m_wave + pass * EPI_ROWS + row) * p.N + nc));
+            }
+            return;
+        }
+        if (fast) {
+            if (tail_parts == 0 && !p.c_f32) { if (gated) compact_pass(pass, std::true_type{}); else compact_pass(pass, std::false_type{}); }
+            else if (gated) fast_pass(pass, std::true_type{}); else fast_pass(pass, std::false_type{});
+            return;
+        }
+        // General path (tile edges, unaligned C / bias / residual, split-K partials), every access
+        // guarded.  Read-back in batches of EPI_U row-chunks per lane: first every LDS read and every
+        // bias / residual load of the batch is issued, then the arithmetic and the stores follow,
+        // so the global-load latency is paid once per batch, not once per chunk.  (The residual
+        // may alias C, which keeps the compiler from hoisting those loads over stores itself.)
+        constexpr int EPI_U = NWAVES > 4 ? 2 : 4;                  // 8-wave work-groups have half the registers per wave
+        for (int base = lane; base < total; base += 64 * EPI_U) {
+            float v[EPI_U][8], u[EPI_U][8];
+            u32x4_t rb[EPI_U], bb[EPI_U];
+            int mm[EPI_U], nn[EPI_U];
+            bool live[EPI_U], vec[EPI_U];
+#pragma unroll
+            for (int j = 0; j < EPI_U; ++j) {
+                const int idx = base + 64 * j;
+                const int row = idx / lanes_per_row, c8 = idx - row * lanes_per_row;
+                mm[j] = m_wave + pass * EPI_ROWS + row;
+                nn[j] = n_wave + c8 * 8;
+                live[j] = idx < total && mm[j] < p.M && nn[j] < nout;
+                vec[j] = live[j] && p.vec_store && (nn[j] + 7 < nout);
+                if (idx < total) {
+                    const char *src = region + row * EPI_PITCH + c8 * 32;
+                    const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
+                    v[j][0] = x0.x; v[j][1] = x0.y; v[j][2] = x0.z; v[j][3] = x0.w;
+                    v[j][4] = x1.x; v[j][5] = x1.y; v[j][6] = x1.z; v[j][7] = x1.w;
+                    if (gated) {
+                        const char *su = src + out_w * 4;
+                        const f32x4_t u0 = *(const f32x4_t *)su, u1 = *(const f32x4_t *)(su + 16);
+                        u[j][0] = u0.x; u[j][1] = u0.y; u[j][2] = u0.z; u[j][3] = u0.w;
+                        u[j][4] = u1.x; u[j][5] = u1.y; u[j][6] = u1.z; u[j][7] = u1.w;
+                    }
+                    for (int sgm = 0; sgm < tail_parts && !tail_producer; ++sgm) {       // see the fast path
+                        const int ps = ((wm * WTM + pass * EPI_ROWS + row) * BN + wn * WTN + c8 * 8) * 4, so = sgm * TILE_FLOATS * 4;
+                        auto ld = [&](int off) { return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_part, ps + off, so, kSysScope)); };
+                        const f32x4_t a0 = ld(0), a1 = ld(16);
+                        v[j][0] += a0.x; v[j][1] += a0.y; v[j][2] += a0.z; v[j][3] += a0.w;
+                        v[j][4] += a1.x; v[j][5] += a1.y; v[j][6] += a1.z; v[j][7] += a1.w;
+                        if (gated) {
+                            const f32x4_t b0 = ld(out_w * 4), b1 = ld(out_w * 4 + 16);
+                            u[j][0] += b0.x; u[j][1] += b0.y; u[j][2] += b0.z; u[j][3] += b0.w;
+                            u[j][4] += b1.x; u[j][5] += b1.y; u[j][6] += b1.z; u[j][7] += b1.w;
+                        }
+                    }
+                }
+                if (!partial && vec[j]) {
+                    if (p.bias) bb[j] = *(const u32x4_t *)(p.bias + nn[j]);
+                    if (R) rb[j] = *(const u32x4_t *)(R + (int64_t)mm[j] * p.ldr + nn[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < EPI_U; ++j) {
+                const int m = mm[j], n = nn[j];
+                if (partial) {
+                    // split-K: raw fp32 partials, both halves of a gated tile at their contraction columns
+                    if (base + 64 * j < total && m < p.M) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            if (h == 1 && !gated) break;
+                            const float *w = h ? u[j] : v[j];
+                            const int nc = n + h * nout;                   // contraction column
+                            const int nlim = gated ? (h + 1) * nout : p.N;
+                            float *dst = P + (int64_t)m * p.N + nc;
+                            if (nc + 7 < nlim && (p.N & 3) == 0) {
+                                const f32x4_t y0 = {w[0], w[1], w[2], w[3]}, y1 = {w[4], w[5], w[6], w[7]};
+                                __builtin_nontemporal_store(y0, (f32x4_t *)dst); __builtin_nontemporal_store(y1, (f32x4_t *)(dst + 4));
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (nc + e < nlim) dst[e] = w[e];
+                            }
+                        }
+                    }
+                    continue;
+                }
+                if (!live[j]) continue;
+                float z[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) z[e] = gated ? silu(v[j][e]) * u[j][e] : v[j][e];
+                if (p.bias) {
+                    if (vec[j]) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bb[j][e] >> 16); }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < nout) z[e] += (float)p.bias[n + e];
+                    }
+                }
+                if (p.act == ACT_GELU_TANH) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
+                }
+                if (R) {
+                    if (vec[j]) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                    } else {
+                        const __bf16 *rp = R + (int64_t)m * p.ldr + n;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < nout) z[e] += (float)rp[e];
+                    }
+                }
+                if (tail_gave_up) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) z[e] = __builtin_nanf("");
+                }
+                if (p.c_f32) {
+                    float *cf = Cf + (int64_t)m * p.ldc + n;
+                    if (vec[j]) {
+                        *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
+                        *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < nout) cf[e] = z[e];
+                    }
+                    continue;
+                }
+                __bf16 *cp = C + (int64_t)m * p.ldc + n;
+                if (vec[j]) {
+                    u32x4_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(z[2 * e]) | (f32_to_bf16_bits(z[2 * e + 1]) << 16);
+                    *(u32x4_t *)cp = o;
+                } else {
+                    uint16_t *cs = (uint16_t *)cp;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(z[e]);
+                }
+            }
+        }
+    });
+    if (tail_producer) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // this thread's write-through stores have reached memory
+        __syncthreads();
+        if (tid == 0)
+            __hip_atomic_store(p.tail_flags + (int64_t)e_tail_tile * tail_parts + e_tail_seg, p.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    } else if (e_in_tail) {
+        // The collecting work-group takes the flags down again once every thread has its partial sums
+        // (each added them to its values before it got here).  A launch replayed from a captured graph
+        // carries the same epoch every time: without this, the second replay would find the flags
+        // of the first still raised and read partial tiles that are being rewritten.
+        __syncthreads();
+        if (tid == 0)
+            for (int sgm = 0; sgm < tail_parts; ++sgm)
+                __hip_atomic_store(p.tail_flags + (int64_t)e_tail_tile * tail_parts + sgm, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    }
+    };
+
+    bool owed = false;                               // a finished K loop's epilogue has not run yet
+    // (8-wave work-groups never walk several items: they have no registers to carry anything across the K loop)
+    static_assert(!PERSIST || NWAVES <= 4, "persistent launches are for 4-wave configurations");
+    const int items = PERSIST ? p.persist_items : 0;            // > 0: a persistent launch
+    const GemmArgs &p_launch = p;
+    for (int round = 0;; ++round) {
+    // Work item of this round.  An ordinary launch has one per work-group; a persistent one walks
+    // items wg, wg + grid.x, ... in the same XCD-aware order (grid.x is a multiple of 8, so a
+    // work-group stays on its XCD's part of the order).
+    const bool persistent = items > 0;
+    const int wg = (int)blockIdx.x + round * (int)gridDim.x;
+    const bool has_tile = round == 0 || (PERSIST && wg < items);
+    // Epilogues that run before anything of the next tile is touched: the LDS-staged ones (the ring
+    // is their staging area) and the last tile's.
+    if (round > 0 && (!has_tile || !e_in_regs)) {
+        if (e_in_regs) epilogue(std::true_type{}); else epilogue(std::false_type{});
+        owed = false;
+        if (has_tile) __syncthreads();               // every wave has read its staging region back before the ring is refilled
+    }
+    if (!has_tile) break;
+    // The tile's set-up reads the launch's parameters afresh (see fresh_args); the epilogue reads the
+    // by-value copy, whose fields stay in registers across the K loop as far as it needs them.
+    auto tile_args = [&]() __attribute__((always_inline)) -> GemmArgs { if constexpr (PERSIST) return fresh_args(); else return p_launch; };
+    const GemmArgs p = tile_args();
+    const bool gated = (p.act == ACT_SILU_GATE);
+    const int nout = gated ? (p.N >> 1) : p.N;
+    const bool partial = p.splits > 1 || p.out_f32;
+    const int tid = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) + wave * 64;      // == threadIdx.x
+    const int lane = tid & 63;
     const int r16 = lane & 15, q = lane >> 4;
 
     // Work-group -> tile (and, for a tile of the split tail, K range).  Tail work-groups are
@@ -280,30 +883,29 @@ gemm_kernel(const GemmArgs p)
     const bool tail_mode = p.tail_g > 1;
     const bool in_tail = tail_mode && (int)blockIdx.x >= p.tail_first;
     int tail_tile = 0, tail_seg = 0;                 // tile number within the tail, K range number
-    int z = blockIdx.z;
-    if (gridDim.z > 1) {
+    const int nz = persistent ? p.persist_z : (int)gridDim.z;
+    int z = persistent ? 0 : (int)blockIdx.z;
+    if (nz > 1) {
         // Split-K and batched launches: (K range or batch entry, tile) pairs in range-major order,
         // every XCD a contiguous run of them (the linear work-group id modulo 8 is the XCD).  The
         // tiles of one K range or batch entry then run side by side on one XCD and share its
         // operands through that XCD's L2.  With the plain grid.z mapping they sat on different
         // XCDs: 256 x 256 x 131072 on 128 x 256 tiles fetched B twice (202 MB of L2 fills against
         // 134 MB of operands), 128 x 512^3 on 256 x 256 tiles both operands twice (269 MB).
-        const int tiles = p.tiles_m * p.tiles_n, total = tiles * (int)gridDim.z;
-        const int lin = (int)blockIdx.x + tiles * (int)blockIdx.z;
+        const int tiles = p.tiles_m * p.tiles_n, total = tiles * nz;
+        const int lin = persistent ? wg : (int)blockIdx.x + tiles * (int)blockIdx.z;
         const int qq = total >> 3, rem = total & 7, xcd = lin & 7, loc = lin >> 3;
         const int item = xcd * qq + (xcd < rem ? xcd : rem) + loc;
         z = item / tiles;
         tile_index_to_coords(p, item - z * tiles, tm, tn);
     } else if (!in_tail) {
-        tile_coords(p, blockIdx.x, tail_mode ? p.tail_first : p.tiles_m * p.tiles_n, tm, tn);
+        tile_coords(p, wg, tail_mode ? p.tail_first : p.tiles_m * p.tiles_n, tm, tn);
     } else {
         const int t_rem = p.tiles_m * p.tiles_n - p.tail_first;
         const int j = (int)blockIdx.x - p.tail_first;
         tail_seg = j / t_rem; tail_tile = j - tail_seg * t_rem;
         tile_index_to_coords(p, p.tail_first + tail_tile, tm, tn);
     }
-    const bool gated = (p.act == ACT_SILU_GATE);
-    const int nout = gated ? (p.N >> 1) : p.N;
     const int m0 = tm * BM;
     const int n0 = tn * (gated ? BN / 2 : BN);       // first OUTPUT column of this tile
 
@@ -622,7 +1224,6 @@ gemm_kernel(const GemmArgs p)
 
     // accumulator tile (mt, nt) is AccTile<mt * NT + nt>
     static_assert(MT * NT <= 64, "accumulator tiles");
-    static_for<MT * NT>([&](auto t_) __attribute__((always_inline)) { AccTile<decltype(t_)::value>::zero(); });
 
     // A K step is consumed in U = KK * PH units: sub-step kk (32 K-values) x part h of the wave's
     // tile rows (MTH of them).  Register sets: two of MTH A fragments (alternating per unit), two
@@ -633,14 +1234,6 @@ gemm_kernel(const GemmArgs p)
     constexpr int U = KK * PH;
     static_assert(U % 2 == 0 && KK % 2 == 0, "register sets alternate with period 2");
     bf16x8_t af[2][MTH], bf[2][NT];
-#pragma unroll
-    for (int x = 0; x < MTH; ++x)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) af[(U - 1) & 1][x][e] = (__bf16)0.0f;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) bf[(KK - 1) & 1][nt][e] = (__bf16)0.0f;
 
     // Fragment read number t of unit u of the stage at s: its MTH A fragments, then (first part
     // of a sub-step only) the NT B fragments of the sub-step.
@@ -769,6 +1362,39 @@ gemm_kernel(const GemmArgs p)
         static_for<LOADS>([&](auto i_) __attribute__((always_inline)) { issue_one(c, i_); });
         prefetch_step(s + p.pf_dist);
     });
+    // The previous tile's register epilogue, while this tile's first stages are on their way.  Its
+    // loads and stores are younger than those stages' loads, and the wait counts of the K loop
+    // assume that nothing else is outstanding: wait for all of it (the stores have left within
+    // ~0.3 us of the last one; the stages were requested before the epilogue began).
+    if (owed) {
+        epilogue(std::true_type{});
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        owed = false;
+    }
+    // ---- what this tile's epilogue will need (the previous tile's has run by now) -----------------
+    auto hand_over = [&]() __attribute__((always_inline)) {
+        e_tm = tm; e_tn = tn; e_z = z;
+        e_in_tail = in_tail; e_tail_seg = tail_seg; e_tail_tile = tail_tile;
+        // register epilogue: the whole tile inside C, bf16 output, no hand-over; gated tiles only where a
+        // wave's output tiles pair up
+        // (the same answer in every wave of the work-group: the two kinds of epilogue meet different
+        // barriers and run at different points of a persistent work-group's loop)
+        const bool inside = m0 + BM <= p_launch.M && n0 + (gated ? BN / 2 : BN) <= nout;
+        e_in_regs = !partial && p_launch.vec_store && inside && !in_tail && !p_launch.c_f32 && (!gated || NT % 4 == 0);
+    };
+    // (a persistent work-group sets these before the K loop, so that nothing of the tile's set-up is needed after
+    // it; an ordinary one after it, where its 8-wave form has the registers)
+    if constexpr (PERSIST) hand_over();
+    // accumulators and the "previous last unit" fragments start from zero
+    static_for<MT * NT>([&](auto t_) __attribute__((always_inline)) { AccTile<decltype(t_)::value>::zero(); });
+#pragma unroll
+    for (int x = 0; x < MTH; ++x)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) af[(U - 1) & 1][x][e] = (__bf16)0.0f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bf[(KK - 1) & 1][nt][e] = (__bf16)0.0f;
     wait_loads_and_barrier<WAIT_N>();
     // Unrolled over the ring so that each body knows its slot.  Rounds whose loads are all whole
     // steps inside the K range (the last body of a round loads step kt + 2 STAGES - 2) run the
@@ -789,12 +1415,8 @@ gemm_kernel(const GemmArgs p)
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // phantom loads still target LDS
 
-    // Everything from here on derives the lane's position anew, so that nothing of it stays live in a
-    // vector register across the K loop (the 8-wave kernels have no register to spare for that).
-    {
-    const int tid = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) + wave * 64;
-    const int lane = tid & 63;
-    const int r16 = lane & 15, q = lane >> 4;
+    // (From here to the end of the item the launch's parameters are read from the by-value copy, as in the
+    // epilogue: the set-up's own copy of them is then dead before the K loop.)
     // ---- split tail: hand over or collect partial sums ------------------------------------------
     // A tile of the tail is accumulated by tail_g work-groups, one K range each.  All but the last
     // store their accumulators as an fp32 tile (row-major, through the epilogue's LDS transpose)
@@ -807,564 +1429,41 @@ gemm_kernel(const GemmArgs p)
     // Partial tiles and flags therefore move with system-scope accesses (write-through stores,
     // cache-bypassing loads): a cache-wide write-back and invalidate around the hand-over, which is
     // what a device-scope fence amounts to here, was measured to cost more than the split saves.
-    const int tail_parts = in_tail ? p.tail_g - 1 : 0;
+    const int tail_parts = in_tail ? p_launch.tail_g - 1 : 0;
     const bool tail_producer = in_tail && tail_seg < tail_parts;
-    constexpr int TILE_FLOATS = BM * BN;
-    constexpr int kSysScope = 17;                    // cache-policy bits sc0 | sc1 of buffer loads / stores
-    const __amdgpu_buffer_rsrc_t rsrc_part = __builtin_amdgcn_make_buffer_rsrc(      // this tile's partials
-        (void *)wave_uniform((const char *)(in_tail ? p.tail_ws + (int64_t)tail_tile * tail_parts * TILE_FLOATS : nullptr)), 0,
-        (uint32_t)(tail_parts * TILE_FLOATS * 4), kBufferFlags);
     // A wait that gives up is an error, never a quietly wrong tile: the work-group then writes NaN to
     // every element of its tile and stores the launch's epoch into the workspace's status word,
     // which fact_tail_timeouts reads.  (Every thread learns of it through a word of the first
     // wave's prefetch sink: the operand stages may still be read by slower waves.)
-    bool tail_gave_up = false;
+    tail_gave_up = false;
     if (in_tail && !tail_producer) {
-        unsigned long long *flags = p.tail_flags + (int64_t)tail_tile * tail_parts;
+        unsigned long long *flags = p_launch.tail_flags + (int64_t)tail_tile * tail_parts;
         volatile int *verdict = (volatile int *)(smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES));
+        const int tid = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) + wave * 64;      // (derived anew: not kept across the K loop)
         if (tid == 0) {
-            int budget = p.tail_budget;
+            int budget = p_launch.tail_budget;
             bool gave_up = budget < 0;
             for (int sgm = 0; sgm < tail_parts && !gave_up; ++sgm)
-                while (__hip_atomic_load(flags + sgm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != p.tail_epoch) {
+                while (__hip_atomic_load(flags + sgm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != p_launch.tail_epoch) {
                     if (budget <= 0) { gave_up = true; break; }
                     __builtin_amdgcn_s_sleep(8);
                     --budget;
                 }
-            if (gave_up) __hip_atomic_store(p.tail_status, p.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            if (gave_up) __hip_atomic_store(p_launch.tail_status, p_launch.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             *verdict = gave_up ? 1 : 0;
         }
         __syncthreads();
         tail_gave_up = *verdict != 0;
     }
 
-    // ---- epilogue ---------------------------------------------------------------------------
-    // Accumulator tile (mt, nt), lane (r16, q): output row mt*16 + r16, output columns
-    // nt*16 + 4q .. + 3: a lane owns pieces of one row per tile, so a direct store would write
-    // 16-byte pieces of 16 different rows per instruction.  Instead each wave transposes its
-    // accumulators through its own LDS region (fp32, EPI_ROWS rows at a time) and reads them
-    // back row-wise: a lane then holds 8 consecutive columns of one row and all epilogue
-    // arithmetic happens there, in fp32, in registers:
-    //     z = acc + bias[n];  z = act(z);  z = z + residual[m][n];  store bf16(z)
-    // with 16-byte loads of bias / residual and 16-byte stores (whole 128-byte lines per row).
-    // Region row pitch = row bytes + 16, which spreads the 16 rows a write instruction touches
-    // over all banks.  Only the wave itself reads what it wrote: no work-group barrier inside.
-    constexpr int EPI_PITCH = epi_pitch(WTN);
-    constexpr int EPI_ROWS = epi_rows(WTM, WTN, NWAVES);
-    constexpr int EPI_TR = EPI_ROWS / 16;                       // tile-rows per pass
-    constexpr int EPI_REGION = EPI_ROWS * EPI_PITCH;
-    static_assert(lds_total(BM, BN, WGM, WGN, BK, STAGES) <= 160 * 1024 && NWAVES * EPI_REGION <= lds_bytes(BM, BN, WGM, WGN, BK, STAGES) && WTM % EPI_ROWS == 0, "LDS budget");
-    __syncthreads();                                            // every wave is done with the operand stages
-    char *region = smem + wave * EPI_REGION;
-    const int out_w = gated ? WTN / 2 : WTN;                    // output columns this wave owns
-    const int lanes_per_row = out_w / 8;
-    const int n_wave = n0 + wn * out_w;                         // first output column of this wave
-    const int m_wave = m0 + wm * WTM;
-    const bool partial = p.splits > 1 || p.out_f32;
-    float *P = partial ? p.P + (int64_t)z * p.M * p.N : nullptr;
-    __bf16 *C = p.C + batch_c;
-    float *Cf = (float *)p.C + batch_c;                         // the same matrix when it holds fp32 (c_f32)
-    const __bf16 *R = p.res ? p.res + batch_r : nullptr;
-
-    // Fast path: the wave's whole tile lies inside C and everything allows 16-byte access.  Straight
-    // code, no per-element guards: the general path below spends most of its time in them.
-    // A lane's 8 columns are the same in every row-chunk it handles (64 is a multiple of the
-    // lanes per row), so its bias values are loaded once.
-    const bool fast = !partial && p.vec_store && m_wave + WTM <= p.M && n_wave + out_w <= nout;
-    // (8-wave work-groups have half the registers per wave: they keep to the general path here)
-    const bool fast_partial = NWAVES <= 4 && partial && (p.N & 3) == 0 && (nout & 3) == 0 && m_wave + WTM <= p.M && n_wave + out_w <= nout;
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-    auto fast_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
-        constexpr bool GATED = decltype(gated_tag)::value;
-        constexpr int OUT_W = GATED ? WTN / 2 : WTN;
-        constexpr int LPR_USED = OUT_W / 8;                         // lanes a row needs
-        constexpr int LPR = LPR_USED <= 1 ? 1 : LPR_USED <= 2 ? 2 : LPR_USED <= 4 ? 4 : LPR_USED <= 8 ? 8 : LPR_USED <= 16 ? 16 : 32;
-        constexpr int TOTAL = EPI_ROWS * LPR;                       // (a power of two of lanes is set aside per row)
-        constexpr int FU = NWAVES > 4 ? 2 : 4;                      // row-chunks per lane and batch
-        static_assert(64 % LPR == 0 && TOTAL % 64 == 0, "a lane keeps its columns; batches are whole waves");
-        const int c8 = lane % LPR;
-        if constexpr (LPR != LPR_USED) { if (c8 >= LPR_USED) return; }      // 96- or 48-wide wave tiles: the lanes past a row's end idle
-        const int n = n_wave + c8 * 8;
-        float bv[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) bv[e] = -0.0f;               // without a bias: the addend that leaves every value, a signed zero too, as it is
-        if (p.bias) {
-            const u32x4_t b4 = *(const u32x4_t *)(p.bias + n);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
-        }
-        const int act = p.act;
-#pragma unroll
-        for (int base = 0; base < TOTAL; base += 64 * FU) {
-            u32x4_t rb[FU];
-            f32x4_t x[FU][2], y[FU][2];
-            int row[FU];
-#pragma unroll
-            for (int j = 0; j < FU; ++j) {
-                if (base + 64 * j < TOTAL) {
-                    row[j] = (base + 64 * j + lane) / LPR;
-                    if (R) rb[j] = *(const u32x4_t *)(R + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldr + n);
-                    const char *src = region + row[j] * EPI_PITCH + c8 * 32;
-                    x[j][0] = *(const f32x4_t *)src; x[j][1] = *(const f32x4_t *)(src + 16);
-                    if constexpr (GATED) { y[j][0] = *(const f32x4_t *)(src + OUT_W * 4); y[j][1] = *(const f32x4_t *)(src + OUT_W * 4 + 16); }
-                    // last K range of a split tail tile: add the other ranges' partial sums, in range order
-                    for (int sgm = 0; sgm < tail_parts; ++sgm) {
-                        const int ps = ((wm * WTM + pass * EPI_ROWS + row[j]) * BN + wn * WTN + c8 * 8) * 4, so = sgm * TILE_FLOATS * 4;
-                        auto ld = [&](int off) { return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_part, ps + off, so, kSysScope)); };
-                        x[j][0] += ld(0); x[j][1] += ld(16);
-                        if constexpr (GATED) { y[j][0] += ld(OUT_W * 4); y[j][1] += ld(OUT_W * 4 + 16); }
-                    }
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < FU; ++j) {
-                if (base + 64 * j < TOTAL) {
-                    float z[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        z[e] = x[j][e >> 2][e & 3];
-                        if constexpr (GATED) z[e] = silu(z[e]) * y[j][e >> 2][e & 3];
-                        z[e] += bv[e];
-                    }
-                    if (act == ACT_GELU_TANH) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
-                    }
-                    if (R) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
-                    }
-                    if (tail_gave_up) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) z[e] = __builtin_nanf("");
-                    }
-                    if (p.c_f32) {
-                        float *cf = Cf + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n;
-                        *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
-                        *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
-                        continue;
-                    }
-                    u32x4_t o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
-                        o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
-                    }
-                    *(u32x4_t *)(C + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n) = o;
-                }
-            }
-        }
-    };
-
-    // The same pass as a short loop (bf16 output, no partial sums of other K ranges to add): the
-    // read-back of a pass is not unrolled, so the whole epilogue is a few hundred instructions that
-    // stay in the instruction cache from tile to tile (straight-line code of several thousand
-    // instructions was measured to run at the speed of its instruction fetch: 9-15 us per
-    // 256 x 256 tile on a compute unit's first tile).  C and the residual are addressed through
-    // buffer descriptors of the wave's tile with one lane-offset register each that advances by a
-    // constant per iteration (32-bit offsets: the host sets vec_store only if a tile's rows span
-    // less than 2^31 bytes).
-    auto compact_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
-        constexpr bool GATED = decltype(gated_tag)::value;
-        constexpr int OUT_W = GATED ? WTN / 2 : WTN;
-        constexpr int LPR_USED = OUT_W / 8;
-        constexpr int LPR = LPR_USED <= 1 ? 1 : LPR_USED <= 2 ? 2 : LPR_USED <= 4 ? 4 : LPR_USED <= 8 ? 8 : LPR_USED <= 16 ? 16 : 32;
-        constexpr int RPB = 64 / LPR;                               // rows a wave-wide access covers
-        constexpr int NB = EPI_ROWS / RPB;                          // such accesses per pass
-        constexpr int FU0 = NWAVES > 4 ? 2 : 4, FU = NB < FU0 ? NB : FU0;       // of them per loop iteration
-        static_assert(64 % LPR == 0 && NB % FU == 0, "a lane keeps its columns; iterations are whole");
-        const int c8 = lane % LPR, lrow = lane / LPR;
-        if constexpr (LPR != LPR_USED) { if (c8 >= LPR_USED) return; }      // 96- or 48-wide wave tiles: the lanes past a row's end idle
-        float bv[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) bv[e] = -0.0f;               // without a bias: the addend that leaves every value, a signed zero too, as it is
-        if (p.bias) {
-            const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + c8 * 8);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
-        }
-        const bool gelu = p.act == ACT_GELU_TANH, has_res = R != nullptr;
-        const int64_t row0 = m_wave + pass * EPI_ROWS;
-        const __amdgpu_buffer_rsrc_t rsrc_c = __builtin_amdgcn_make_buffer_rsrc((void *)wave_uniform((const char *)(C + row0 * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
-        const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)wave_uniform((const char *)(has_res ? R + row0 * p.ldr + n_wave : C + row0 * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
-        uint32_t vo = (uint32_t)((lrow * (int)p.ldc + c8 * 8) * 2), vr = (uint32_t)((lrow * (int)p.ldr + c8 * 8) * 2);
-        const uint32_t step_c = (uint32_t)(RPB * (int)p.ldc * 2), step_r = (uint32_t)(RPB * (int)p.ldr * 2);
-        const char *src = region + lrow * EPI_PITCH + c8 * 32;
-#pragma nounroll
-        for (int it = 0; it < NB / FU; ++it) {
-            u32x4_t rb[FU];
-            f32x4_t x[FU][2], y[FU][2];
-#pragma unroll
-            for (int j = 0; j < FU; ++j) {
-                if (has_res) rb[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, vr + j * step_r, 0, 0);
-                const char *sj = src + j * RPB * EPI_PITCH;
-                x[j][0] = *(const f32x4_t *)sj; x[j][1] = *(const f32x4_t *)(sj + 16);
-                if constexpr (GATED) { y[j][0] = *(const f32x4_t *)(sj + OUT_W * 4); y[j][1] = *(const f32x4_t *)(sj + OUT_W * 4 + 16); }
-            }
-#pragma unroll
-            for (int j = 0; j < FU; ++j) {
-                float z[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    z[e] = x[j][e >> 2][e & 3];
-                    if constexpr (GATED) z[e] = silu(z[e]) * y[j][e >> 2][e & 3];
-                    z[e] += bv[e];
-                }
-                if (gelu) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
-                }
-                if (has_res) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
-                }
-                u32x4_t o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
-                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
-                }
-                // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
-                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + j * step_c, 0, 0);
-            }
-            vo += FU * step_c; vr += FU * step_r; src += FU * RPB * EPI_PITCH;
-        }
-    };
-
-    // Register path (interior wave tiles with 16-byte access, bf16 output, no K hand-over): no LDS at
-    // all (the transposing path above moves 1 MB through LDS per 256 x 256 tile, 4 us of LDS time).
-    // Two neighbouring 16 x 16 accumulator tiles exchange 16-lane rows (v_permlane16_swap: the odd
-    // rows of the first operand with the even rows of the second), after which lane (r16, q) holds 8
-    // consecutive columns of output row r16: tile q & 1 of the pair, columns 8 (q >> 1) .. + 7.
-    // Bias, activation, residual and the single rounding happen there, in fp32, and every lane
-    // stores 16 bytes: the four lanes of a row write 64 consecutive bytes, the next pair of tiles
-    // the other half of the 128-byte line.  (Gated: gate and up values of an element sit in the
-    // same lane, so SiLU(gate) * up is formed before the exchange.)  What the epilogue adds is
-    // fixed at compile time (one instance per combination, chosen once), so the code is straight;
-    // C and the residual are addressed through buffer descriptors of the wave's tile with one
-    // lane-offset register each (32-bit offsets: the host sets vec_store only if a tile's rows span
-    // less than 2^31 bytes), a tile row adds one vector add, a pair an immediate offset.
-    auto reg_epilogue = [&](auto gated_tag, auto bias_tag, auto gelu_tag, auto res_tag) __attribute__((always_inline)) {
-        constexpr bool GATED = decltype(gated_tag)::value, BIAS = decltype(bias_tag)::value;
-        constexpr bool GELU = decltype(gelu_tag)::value, RES = decltype(res_tag)::value;
-        constexpr int OT = GATED ? NT / 2 : NT;                     // output tiles along N of this wave
-        constexpr int NP = OT / 2;                                  // pairs of them
-        static_assert(OT % 2 == 0, "tiles are exchanged in pairs");
-        // 8-wave work-groups have half the registers per wave: the bias stays packed (unpacked at every
-        // use) and the residual is loaded row by row instead of one row ahead
-        constexpr bool LEAN = NWAVES > 4;
-        const int col = (q & 1) * 16 + (q >> 1) * 8;                // the lane's first column inside a pair
-        const __amdgpu_buffer_rsrc_t rsrc_c = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)wave_uniform((const char *)(C + (int64_t)m_wave * p.ldc + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
-        const uint32_t voff_c = (uint32_t)((r16 * (int)p.ldc + col) * 2);
-        const uint32_t row_c = (uint32_t)(16 * (int)p.ldc * 2);     // bytes per tile row of C
-        __amdgpu_buffer_rsrc_t rsrc_r = rsrc_c;
-        uint32_t voff_r = 0, row_r = 0;
-        if constexpr (RES) {
-            rsrc_r = __builtin_amdgcn_make_buffer_rsrc((void *)wave_uniform((const char *)(R + (int64_t)m_wave * p.ldr + n_wave)), 0, 0x7FFFFFFF, kBufferFlags);
-            voff_r = (uint32_t)((r16 * (int)p.ldr + col) * 2);
-            row_r = (uint32_t)(16 * (int)p.ldr * 2);
-        }
-        float bv[LEAN ? 1 : NP][8];
-        u32x4_t bp[LEAN ? NP : 1];
-        if constexpr (BIAS) {
-#pragma unroll
-            for (int pr = 0; pr < NP; ++pr) {
-                const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + col + pr * 32);
-                if constexpr (LEAN) bp[pr] = b4;
-                else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { bv[pr][2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[pr][2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
-                }
-            }
-        }
-        u32x4_t rb[LEAN ? 1 : 2][NP];                               // residual of the row in work (and of the next one)
-        auto load_res = [&](int mt) __attribute__((always_inline)) {
-            if constexpr (RES) {
-#pragma unroll
-                for (int pr = 0; pr < NP; ++pr)
-                    rb[LEAN ? 0 : (mt & 1)][pr] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, voff_r + mt * row_r + pr * 64, 0, 0);
-            }
-        };
-        if constexpr (!LEAN) load_res(0);
-        static_for<MT>([&](auto mt_) __attribute__((always_inline)) {
-            constexpr int mt = decltype(mt_)::value;
-            if constexpr (LEAN) load_res(mt);
-            else if constexpr (mt + 1 < MT) load_res(mt + 1);
-            const uint32_t vo = voff_c + mt * row_c;
-            static_for<NP>([&](auto pr_) __attribute__((always_inline)) {
-                constexpr int pr = decltype(pr_)::value;
-                f32x4_t x0 = AccTile<mt * NT + 2 * pr>::get(), x1 = AccTile<mt * NT + 2 * pr + 1>::get();
-                if constexpr (GATED) {
-                    const f32x4_t u0 = AccTile<mt * NT + OT + 2 * pr>::get(), u1 = AccTile<mt * NT + OT + 2 * pr + 1>::get();
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { x0[e] = silu(x0[e]) * u0[e]; x1[e] = silu(x1[e]) * u1[e]; }
-                }
-                float z[8];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float a0 = x0[e], a1 = x1[e];      // (a bit cast applied to a vector element directly reads element 0)
-                    const auto sw = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(uint32_t, a0), __builtin_bit_cast(uint32_t, a1), false, false);
-                    z[e] = __builtin_bit_cast(float, (uint32_t)sw[0]);
-                    z[4 + e] = __builtin_bit_cast(float, (uint32_t)sw[1]);
-                }
-                if constexpr (BIAS) {
-                    if constexpr (LEAN) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bp[pr][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bp[pr][e] >> 16); }
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) z[e] += bv[pr][e];
-                    }
-                }
-                if constexpr (GELU) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
-                }
-                if constexpr (RES) {
-                    const u32x4_t r4 = rb[LEAN ? 0 : (mt & 1)][pr];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(r4[e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(r4[e] >> 16); }
-                }
-                u32x4_t o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
-                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
-                }
-                // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
-                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + pr * 64, 0, 0);
-            });
-        });
-    };
-    bool in_registers = false;
-    if (fast && !in_tail && !p.c_f32) {
-        const int what = (p.bias ? 1 : 0) | (p.act == ACT_GELU_TANH ? 2 : 0) | (R ? 4 : 0);
-        constexpr std::true_type T{};
-        constexpr std::false_type F{};
-        in_registers = true;
-        if (!gated) {
-            switch (what) {
-            case 0: reg_epilogue(F, F, F, F); break;
-            case 1: reg_epilogue(F, T, F, F); break;
-            case 2: reg_epilogue(F, F, T, F); break;
-            case 3: reg_epilogue(F, T, T, F); break;
-            case 4: reg_epilogue(F, F, F, T); break;
-            case 5: reg_epilogue(F, T, F, T); break;
-            case 6: reg_epilogue(F, F, T, T); break;
-            default: reg_epilogue(F, T, T, T); break;
-            }
-        } else if constexpr (NT % 4 == 0) {
-            if (R) reg_epilogue(T, F, F, T); else reg_epilogue(T, F, F, F);
-        } else {
-            in_registers = false;
-        }
+    if constexpr (!PERSIST) hand_over();
+    owed = true;
+    if constexpr (!PERSIST) {                        // one item per work-group: straight to its epilogue (no loop for the compiler to carry state around)
+        if (e_in_regs) epilogue(std::true_type{}); else epilogue(std::false_type{});
+        break;
     }
+    }   // next work item
 
-    if (!in_registers)
-    static_for<WTM / EPI_ROWS>([&](auto pass_) __attribute__((always_inline)) {
-        constexpr int pass = decltype(pass_)::value;
-        if (pass > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // previous pass's reads are done
-        {
-            const uint32_t dst = (uint32_t)(size_t)FACT_LDS_PTR(region + r16 * EPI_PITCH + q * 16);
-            static_for<EPI_TR * NT>([&](auto w_) __attribute__((always_inline)) {
-                constexpr int i = decltype(w_)::value / NT, nt = decltype(w_)::value % NT;
-                AccTile<(pass * EPI_TR + i) * NT + nt>::template to_lds<i * 16 * EPI_PITCH + nt * 64>(dst);
-            });
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                    // the wave's own writes have landed
-        const int total = EPI_ROWS * lanes_per_row;
-        if (tail_producer) {
-            // partial tile, fp32 row-major [BM][BN] in accumulator column order (gated: gate columns,
-            // then up columns, per wave); the wave's EPI_ROWS x WTN block of this pass, 16 bytes per lane
-            constexpr int LPR4 = WTN / 4;
-            const int dst = (tail_seg * TILE_FLOATS + (wm * WTM + pass * EPI_ROWS) * BN + wn * WTN) * 4;     // bytes
-#pragma unroll
-            for (int base = 0; base < EPI_ROWS * LPR4; base += 64) {
-                const int idx = base + lane, row = idx / LPR4, c4 = idx % LPR4;
-                const u32x4_t x = *(const u32x4_t *)(region + row * EPI_PITCH + c4 * 16);
-                // The whole offset goes into the per-lane operand, the scalar one stays the constant 0:
-                // with a scalar-register offset the compiler assumes that the data registers of a
-                // 16-byte buffer store may be overwritten in the very next cycle, and on this chip
-                // the last lanes of each 16 then stored the overwriting value (seen as the next
-                // store's offset inside the partial tile).  With a constant it keeps the wait states.
-                __builtin_amdgcn_raw_buffer_store_b128(x, rsrc_part, dst + (row * BN + c4 * 4) * 4, 0, kSysScope);
-            }
-            return;
-        }
-        if constexpr (NWAVES <= 4) if (fast_partial) {
-            // split-K partials of an interior tile: raw fp32, 16-byte stores, both halves of a gated
-            // tile at their contraction columns
-            constexpr int LPR4 = WTN / 4;                             // lanes per row, 4 columns each
-#pragma unroll
-            for (int base = 0; base < EPI_ROWS * LPR4; base += 64) {
-                const int idx = base + lane, row = idx / LPR4, c4 = idx % LPR4;
-                const f32x4_t x = *(const f32x4_t *)(region + row * EPI_PITCH + c4 * 16);
-                int nc = n0 + wn * WTN + c4 * 4;                       // plain: contraction column = output column
-                if (gated) nc = n0 + wn * (WTN / 2) + (c4 * 4) % (WTN / 2) + ((c4 * 4) / (WTN / 2)) * nout;
-                // streaming store: a partial is read once, by the reduction pass, and a line left dirty in
-                // this XCD's L2 would have to be written back before the launch can end (large-K case with
-                // operands from HBM: 43.6 -> 38.7 us for GEMM plus reduction, 30.2 -> 29.4 us from the cache)
-                __builtin_nontemporal_store(x, (f32x4_t *)(P + (int64_t)(m_wave + pass * EPI_ROWS + row) * p.N + nc));
-            }
-            return;
-        }
-        if (fast) {
-            if (tail_parts == 0 && !p.c_f32) { if (gated) compact_pass(pass, std::true_type{}); else compact_pass(pass, std::false_type{}); }
-            else if (gated) fast_pass(pass, std::true_type{}); else fast_pass(pass, std::false_type{});
-            return;
-        }
-        // General path (tile edges, unaligned C / bias / residual, split-K partials), every access
-        // guarded.  Read-back in batches of EPI_U row-chunks per lane: first every LDS read and every
-        // bias / residual load of the batch is issued, then the arithmetic and the stores follow,
-        // so the global-load latency is paid once per batch, not once per chunk.  (The residual
-        // may alias C, which keeps the compiler from hoisting those loads over stores itself.)
-        constexpr int EPI_U = NWAVES > 4 ? 2 : 4;                  // 8-wave work-groups have half the registers per wave
-        for (int base = lane; base < total; base += 64 * EPI_U) {
-            float v[EPI_U][8], u[EPI_U][8];
-            u32x4_t rb[EPI_U], bb[EPI_U];
-            int mm[EPI_U], nn[EPI_U];
-            bool live[EPI_U], vec[EPI_U];
-#pragma unroll
-            for (int j = 0; j < EPI_U; ++j) {
-                const int idx = base + 64 * j;
-                const int row = idx / lanes_per_row, c8 = idx - row * lanes_per_row;
-                mm[j] = m_wave + pass * EPI_ROWS + row;
-                nn[j] = n_wave + c8 * 8;
-                live[j] = idx < total && mm[j] < p.M && nn[j] < nout;
-                vec[j] = live[j] && p.vec_store && (nn[j] + 7 < nout);
-                if (idx < total) {
-                    const char *src = region + row * EPI_PITCH + c8 * 32;
-                    const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
-                    v[j][0] = x0.x; v[j][1] = x0.y; v[j][2] = x0.z; v[j][3] = x0.w;
-                    v[j][4] = x1.x; v[j][5] = x1.y; v[j][6] = x1.z; v[j][7] = x1.w;
-                    if (gated) {
-                        const char *su = src + out_w * 4;
-                        const f32x4_t u0 = *(const f32x4_t *)su, u1 = *(const f32x4_t *)(su + 16);
-                        u[j][0] = u0.x; u[j][1] = u0.y; u[j][2] = u0.z; u[j][3] = u0.w;
-                        u[j][4] = u1.x; u[j][5] = u1.y; u[j][6] = u1.z; u[j][7] = u1.w;
-                    }
-                    for (int sgm = 0; sgm < tail_parts && !tail_producer; ++sgm) {       // see the fast path
-                        const int ps = ((wm * WTM + pass * EPI_ROWS + row) * BN + wn * WTN + c8 * 8) * 4, so = sgm * TILE_FLOATS * 4;
-                        auto ld = [&](int off) { return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_part, ps + off, so, kSysScope)); };
-                        const f32x4_t a0 = ld(0), a1 = ld(16);
-                        v[j][0] += a0.x; v[j][1] += a0.y; v[j][2] += a0.z; v[j][3] += a0.w;
-                        v[j][4] += a1.x; v[j][5] += a1.y; v[j][6] += a1.z; v[j][7] += a1.w;
-                        if (gated) {
-                            const f32x4_t b0 = ld(out_w * 4), b1 = ld(out_w * 4 + 16);
-                            u[j][0] += b0.x; u[j][1] += b0.y; u[j][2] += b0.z; u[j][3] += b0.w;
-                            u[j][4] += b1.x; u[j][5] += b1.y; u[j][6] += b1.z; u[j][7] += b1.w;
-                        }
-                    }
-                }
-                if (!partial && vec[j]) {
-                    if (p.bias) bb[j] = *(const u32x4_t *)(p.bias + nn[j]);
-                    if (R) rb[j] = *(const u32x4_t *)(R + (int64_t)mm[j] * p.ldr + nn[j]);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < EPI_U; ++j) {
-                const int m = mm[j], n = nn[j];
-                if (partial) {
-                    // split-K: raw fp32 partials, both halves of a gated tile at their contraction columns
-                    if (base + 64 * j < total && m < p.M) {
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            if (h == 1 && !gated) break;
-                            const float *w = h ? u[j] : v[j];
-                            const int nc = n + h * nout;                   // contraction column
-                            const int nlim = gated ? (h + 1) * nout : p.N;
-                            float *dst = P + (int64_t)m * p.N + nc;
-                            if (nc + 7 < nlim && (p.N & 3) == 0) {
-                                const f32x4_t y0 = {w[0], w[1], w[2], w[3]}, y1 = {w[4], w[5], w[6], w[7]};
-                                __builtin_nontemporal_store(y0, (f32x4_t *)dst); __builtin_nontemporal_store(y1, (f32x4_t *)(dst + 4));
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < 8; ++e)
-                                    if (nc + e < nlim) dst[e] = w[e];
-                            }
-                        }
-                    }
-                    continue;
-                }
-                if (!live[j]) continue;
-                float z[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) z[e] = gated ? silu(v[j][e]) * u[j][e] : v[j][e];
-                if (p.bias) {
-                    if (vec[j]) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bb[j][e] >> 16); }
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (n + e < nout) z[e] += (float)p.bias[n + e];
-                    }
-                }
-                if (p.act == ACT_GELU_TANH) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) z[e] = gelu_tanh(z[e]);
-                }
-                if (R) {
-                    if (vec[j]) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
-                    } else {
-                        const __bf16 *rp = R + (int64_t)m * p.ldr + n;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (n + e < nout) z[e] += (float)rp[e];
-                    }
-                }
-                if (tail_gave_up) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) z[e] = __builtin_nanf("");
-                }
-                if (p.c_f32) {
-                    float *cf = Cf + (int64_t)m * p.ldc + n;
-                    if (vec[j]) {
-                        *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
-                        *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (n + e < nout) cf[e] = z[e];
-                    }
-                    continue;
-                }
-                __bf16 *cp = C + (int64_t)m * p.ldc + n;
-                if (vec[j]) {
-                    u32x4_t o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(z[2 * e]) | (f32_to_bf16_bits(z[2 * e + 1]) << 16);
-                    *(u32x4_t *)cp = o;
-                } else {
-                    uint16_t *cs = (uint16_t *)cp;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(z[e]);
-                }
-            }
-        }
-    });
-    if (tail_producer) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // this thread's write-through stores have reached memory
-        __syncthreads();
-        if (tid == 0)
-            __hip_atomic_store(p.tail_flags + (int64_t)tail_tile * tail_parts + tail_seg, p.tail_epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    } else if (in_tail) {
-        // The collecting work-group takes the flags down again once every thread has its partial sums
-        // (each added them to its values before it got here).  A launch replayed from a captured graph
-        // carries the same epoch every time: without this, the second replay would find the flags
-        // of the first still raised and read partial tiles that are being rewritten.
-        __syncthreads();
-        if (tid == 0)
-            for (int sgm = 0; sgm < tail_parts; ++sgm)
-                __hip_atomic_store(p.tail_flags + (int64_t)tail_tile * tail_parts + sgm, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
-    }
 #else
     (void)p;
 #endif

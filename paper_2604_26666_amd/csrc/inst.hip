@@ -15,7 +15,11 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
         (void)args; (void)grid_z; (void)stream;
         return hipErrorInvalidConfiguration;          // (the host side never selects such a tile for this layout)
     } else {
-    auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES>;
+    constexpr bool CAN_PERSIST = FACT_WM * FACT_WN <= 4;      // the persistent form exists for 4-wave configurations
+    auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES, false>;
+    auto kern_p = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES, CAN_PERSIST>;
+    const bool persist = CAN_PERSIST && args.persist_items > 0;
+    if (args.persist_items > 0 && !CAN_PERSIST) return hipErrorInvalidConfiguration;     // (the host side never asks for it)
     constexpr int lds = lds_total(FACT_BM, FACT_BN, FACT_WM, FACT_WN, FACT_BK, FACT_STAGES);
     static std::atomic<bool> attr_set[64];         // (two host threads may make a kernel's first launch at once: setting the limit twice is harmless)
     int dev = 0;
@@ -25,13 +29,19 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
     if (!attr_set[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
+        if (CAN_PERSIST) {
+            e = hipFuncSetAttribute((const void *)kern_p, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+        }
         attr_set[dev].store(true, std::memory_order_release);
     }
     const int tiles = args.tiles_m * args.tiles_n;
     const int grid_x = args.tail_g > 1 ? args.tail_first + (tiles - args.tail_first) * args.tail_g : tiles;
     dim3 grid((unsigned)grid_x, 1, (unsigned)grid_z);
+    if (args.persist_items > 0) grid = dim3((unsigned)args.persist_grid, 1, 1);
     dim3 block(FACT_WM * FACT_WN * 64, 1, 1);
-    hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
+    if (persist) hipLaunchKernelGGL(kern_p, grid, block, lds, stream, args);
+    else hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
     return hipGetLastError();
     }
 }
