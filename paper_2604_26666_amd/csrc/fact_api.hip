@@ -758,6 +758,6 @@ int fact_registry_size(void)
 
 const char *fact_last_error(void) { return g_last_error; }
 
-int fact_version(void) { return 200; }
+int fact_version(void) { return 201; }
 
 }  // extern "C"
