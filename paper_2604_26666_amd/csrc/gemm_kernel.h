@@ -12,7 +12,8 @@
 //                  fragments of each 32-deep sub-step are read from LDS into a second register
 //                  set while the MFMAs of the previous sub-step run; one barrier per K step.
 //   grid level   : 2-D data-parallel tiling with an XCD-aware tile order; grid.z is the
-//                  batch index or the split-K range.
+//                  batch index or the split-K range; a tail split for a partly filled last
+//                  round; a persistent instantiation whose work-groups walk several tiles.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -1423,8 +1424,8 @@ gemm_kernel(const GemmArgs p)
     // and then raise a flag; the last one waits for the flags and adds the partial tiles, in
     // ascending K-range order, to its own sums as it reads them back in the epilogue.  The order is
     // fixed, so the result is bit-reproducible.  Producers never wait and are dispatched before the
-    // work-group that waits for them; the wait is bounded all the same (a time-out is counted
-    // behind the flags and the tile is finished with what has arrived).
+    // work-group that waits for them; the wait is bounded all the same (what a wait that gives
+    // up does is described below).
     // The partners may sit on different XCDs, whose L2 caches are not coherent with each other.
     // Partial tiles and flags therefore move with system-scope accesses (write-through stores,
     // cache-bypassing loads): a cache-wide write-back and invalidate around the hand-over, which is
