@@ -52,7 +52,7 @@ struct GemmArgs {
     int tiles_m, tiles_n;
     int group_m;            // tile rows walked together (L2 reuse)
     int vec_store;          // 1: C / residual / bias allow 16-byte vector access
-    int pf_sa, pf_sb;       // L2 prefetch: work-groups that share an A row-panel / a B column-panel (0: off)
+    int pf_sa, pf_sb;       // L2 prefetch: work-groups that share an A row-panel / a B column-panel (0: off; else a power of two)
     int pf_dist;            // L2 prefetch: K steps ahead of the step being loaded into LDS (>= 1)
     // Tail split (the last, partly filled round of tiles): work-groups [0, tail_first) own one tile
     // each; the remaining tiles are shared by tail_g work-groups each, one K range apiece.
@@ -1028,32 +1028,51 @@ gemm_kernel(const GemmArgs p)
     bool pf_up = false;
     {
         constexpr int HT = NWAVES * 32;                   // threads per wave half
+        constexpr int HT_LOG2 = NWAVES == 4 ? 7 : 8;
+        static_assert((1 << HT_LOG2) == HT, "4 or 8 waves");
         const int hx = tid & (HT - 1);                    // index within the wave half
-        // the lines of a share are spread evenly over the half's threads, so that every wave's
-        // load touches about the same number of lines
-        auto pick = [&](int lines, int &li) { const int str = lines < HT ? HT / lines : 1; li = hx / str; return hx % str == 0 && li < lines; };
+        // The sharer counts are powers of two (the host sees to that), so a share is L >> k lines of a
+        // slab of L lines.  They are spread over the half's threads at a power-of-two stride, so that
+        // every wave's load touches about the same number of lines; all of it in shifts (this runs
+        // once per tile, on one wave per SIMD: the divisions it used to take were a third of the
+        // 1.6 us between a work-group's start and its first load).
+        auto pick = [&](auto l_tag, int k, int &li) __attribute__((always_inline)) {
+            constexpr int L = decltype(l_tag)::value;
+            constexpr int LC = L <= 16 ? 4 : L <= 32 ? 5 : L <= 64 ? 6 : L <= 128 ? 7 : 8;       // ceil(log2 L)
+            static_assert(L >= 16 && L <= 256, "slab lines");
+            const int sl = HT_LOG2 + k - LC;
+            const int sh = sl > 0 ? sl : 0;
+            li = hx >> sh;
+            return (hx & ((1 << sh) - 1)) == 0 && li < (L >> k);
+        };
         int li = 0;
         if (pf_is_a) {
             if (p.pf_sa > 0) {
-                const int la = BM / p.pf_sa;
-                if (pick(la, li)) pf_voff = (uint32_t)((int64_t)((tn % p.pf_sa) * la + li) * p.lda * 2) + kOffBias;
+                const int ka = __builtin_ctz((unsigned)p.pf_sa);
+                if (pick(std::integral_constant<int, BM>{}, ka, li))
+                    pf_voff = (uint32_t)((int64_t)((tn & (p.pf_sa - 1)) * (BM >> ka) + li) * p.lda * 2) + kOffBias;
             }
             pf_step = ROWB;
         } else if (p.pf_sb > 0) {
-            const int share = (tm % p.group_m) % p.pf_sb;
+            const int kb = __builtin_ctz((unsigned)p.pf_sb);
+            const int share = (tm % p.group_m) & (p.pf_sb - 1);
             if constexpr (TRANS_B) {
-                int lb = BN / p.pf_sb, row0 = share * lb;
+                bool mine;
+                int row0;
                 if (gated) {                              // shares alternate between the gate and the up rows
-                    const int sh = p.pf_sb > 1 ? p.pf_sb / 2 : 1;
-                    lb = (BN / 2) / sh; row0 = (p.pf_sb > 1 ? share >> 1 : 0) * lb; pf_up = (share & 1) != 0;
+                    const int ks = kb > 0 ? kb - 1 : 0;
+                    mine = pick(std::integral_constant<int, BN / 2>{}, ks, li);
+                    row0 = (kb > 0 ? share >> 1 : 0) * ((BN / 2) >> ks); pf_up = (share & 1) != 0;
+                } else {
+                    mine = pick(std::integral_constant<int, BN>{}, kb, li);
+                    row0 = share * (BN >> kb);
                 }
-                if (pick(lb, li)) pf_voff = (uint32_t)((int64_t)(row0 + li) * p.ldb * 2) + kOffBias;
+                if (mine) pf_voff = (uint32_t)((int64_t)(row0 + li) * p.ldb * 2) + kOffBias;
                 pf_step = ROWB;
             } else {
                 constexpr int LPR = BN / 64;              // 128-byte lines per K-row of the slab
-                const int lb = BN / p.pf_sb;
-                if (pick(lb, li)) {
-                    const int line = share * lb + li;
+                if (pick(std::integral_constant<int, BN>{}, kb, li)) {
+                    const int line = share * (BN >> kb) + li;
                     const int kr = line / LPR, col = (line % LPR) * 64;
                     if (col < p.N - n0) pf_voff = (uint32_t)(((int64_t)kr * p.ldb + col) * 2) + kOffBias;
                 }
@@ -1357,12 +1376,23 @@ gemm_kernel(const GemmArgs p)
     // prologue's loads and the first of those are touched here, ahead of the loads (older than
     // them, so the wait counts are unaffected).
     for (int x = STAGES - 1; x < p.pf_dist; ++x) prefetch_step(x);
-    static_for<STAGES - 1>([&](auto s_) __attribute__((always_inline)) {
-        constexpr int s = decltype(s_)::value;
-        const StepCtx c = step_ctx(s, s);
-        static_for<LOADS>([&](auto i_) __attribute__((always_inline)) { issue_one(c, i_); });
-        prefetch_step(s + p.pf_dist);
-    });
+    if (ksteps >= STAGES) {
+        // every step of the prologue is a whole step inside the K range: the steady form of the loads
+        // (offsets already in registers) instead of some fifteen instructions of range arithmetic per load
+        static_for<STAGES - 1>([&](auto s_) __attribute__((always_inline)) {
+            constexpr int s = decltype(s_)::value;
+            const Steady c = steady_at(s);
+            static_for<LOADS>([&](auto i_) __attribute__((always_inline)) { issue_steady(c, smem + s * STAGE, i_); });
+            prefetch_steady(s + p.pf_dist);
+        });
+    } else {
+        static_for<STAGES - 1>([&](auto s_) __attribute__((always_inline)) {
+            constexpr int s = decltype(s_)::value;
+            const StepCtx c = step_ctx(s, s);
+            static_for<LOADS>([&](auto i_) __attribute__((always_inline)) { issue_one(c, i_); });
+            prefetch_step(s + p.pf_dist);
+        });
+    }
     // The previous tile's register epilogue, while this tile's first stages are on their way.  Its
     // loads and stores are younger than those stages' loads, and the wait counts of the K loop
     // assume that nothing else is outstanding: wait for all of it (the stores have left within
