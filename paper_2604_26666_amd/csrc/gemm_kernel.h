@@ -300,7 +300,8 @@ gemm_kernel(const GemmArgs p)
     // ---- what the epilogue needs of its tile ------------------------------------------------
     // A work-group may walk several tiles (persistent launch).  The epilogue of a tile runs when the
     // next tile's first operand stages have been requested, so it must not look at anything the
-    // loop below derives for the tile in hand: these variables are set when a tile's K loop ends.
+    // loop below derives for the tile in hand: these variables are set by hand_over() in the loop
+    // (before the tile's K loop in a persistent work-group, after it in an ordinary one).
     int e_tm = 0, e_tn = 0, e_z = 0;                  // tile coordinates, batch entry or K range
     bool e_in_regs = false;                           // it takes the register path
     bool e_in_tail = false, tail_gave_up = false;     // tail split: a shared tile; its collecting wait gave up
