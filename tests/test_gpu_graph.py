@@ -78,6 +78,36 @@ def test_gemm_graph_replay(cfg, split):
     check.assert_close(_bits(C), ref.gemm_epilogue(sets[1][0], sets[1][1], True, bias=sets[1][2], act=fact.ACT_GELU_TANH), what="after the replays")
 
 
+def test_persistent_gemm_graph_replay():
+    # A persistent launch reads its parameters from the kernel-argument segment once per tile; a graph keeps
+    # its own copy of that segment.  600 tiles of 128 x 128 on 512 resident work-groups: two rounds, the second ragged.
+    cfg, M, N, K = 3, 24 * 128, 25 * 128, 264
+    before = fact.fact_tune_persistent(1)
+    try:
+        assert fact.fact_persistent_grid(1, M, N, K, 1, fact.ACT_NONE, cfg) > 0
+        sets = [(wl.normal((M, K), 1.0, f"gp.A{i}"), wl.normal((N, K), 0.05, f"gp.W{i}"), wl.normal((N,), 1.0, f"gp.b{i}")) for i in range(2)]
+        A, W, b = (torch.empty_like(x).cuda() for x in sets[0])
+        C = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
+        ep = fact.Epilogue(bias=b)
+
+        def launch():
+            fact.binding.check(fact.fact_gemm_ex(1, M, N, K, A, K, 0, W, K, 0, 1, C, N, 0, ep, cfg, 1, 0, None, 0))
+
+        def refresh(i):
+            for dst, src in zip((A, W, b), sets[i]):
+                dst.copy_(src)
+
+        def eager():
+            launch()
+            return _bits(C)
+
+        _replays(launch, eager, len(sets), refresh, C)
+        rows = np.arange(0, M, 131)
+        check.assert_close(_bits(C)[rows], ref.gemm_epilogue(sets[1][0], sets[1][1], True, bias=sets[1][2], rows=rows), what="after the replays")
+    finally:
+        fact.fact_tune_persistent(before)
+
+
 def test_attention_and_block_graph_replay():
     from test_gpu_block import make_block
     p, t, X0 = make_block("llama", 2, 200, 256, 4, 2, 64, 512)
