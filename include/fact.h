@@ -120,9 +120,11 @@ int fact_gemm_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
  * Large-K GEMM (Section 5.1, Problem 6; Section 5.2.3): K is cut into split_k
  * contiguous ranges, each range's product is written as an fp32 partial into the
  * workspace (fp32 because reduced precision is not enough there, Section 5.2.3), and a
- * second kernel adds the partials in fp32 in a fixed order (the ranges in eight consecutive
- * groups, ascending inside a group, then the eight group sums in ascending order), applies
- * the epilogue and rounds once.  split_k == 0 lets the table choose; split_k == 1 (or a
+ * second kernel adds the partials in fp32 in a fixed order (the ranges in W consecutive
+ * groups of ceil(split_k / W), ascending inside a group, then the W group sums in ascending
+ * order; W is 1, 2, 4 or 8, the least that puts some 2048 waves to work on the M x N output
+ * with at least four ranges each: a function of M, N and split_k alone), applies the epilogue
+ * and rounds once.  split_k == 0 lets the table choose; split_k == 1 (or a
  * choice of 1) runs the plain kernel and needs no workspace.  Bit-reproducible: the
  * order of additions is fixed.
  * ws: device pointer, 16-byte aligned, at least

@@ -6,17 +6,20 @@ namespace fact {
 
 // ---- split-K reduction -----------------------------------------------------------------
 // P holds `splits` fp32 partial products [M][N].  A lane owns 4 consecutive output columns of
-// one row; the eight waves of a work-group own the same 64 such column groups and an eighth of
-// the K ranges each (consecutive ranges, added in ascending order); the eight sums are then
-// added in ascending order by the first wave, which applies the epilogue and rounds once.
-// The order of additions is fixed, so the result is bit-reproducible.  (One wave per column
-// group adding all ranges in turn was bound by its trips to memory: 8.5 us for the 17 MB of
-// 64 ranges of a 256 x 256 output, whatever the number of loads in flight per wave.)  The
-// paper's counterpart is the fix-up step of its Stream-K schedule (Section 5.2.3).
-constexpr int kReduceWaves = 8;
+// one row; the W waves of a work-group own the same 64 such column groups and a W-th of the K
+// ranges each (consecutive ranges, added in ascending order); the W sums are then added in
+// ascending order by the first wave, which applies the epilogue and rounds once.  W depends on
+// the problem's M, N and number of ranges only (reduce_waves below), so the order of additions is
+// fixed for a given problem and the result is bit-reproducible.  Many ranges of a small output want W = 8 (one wave
+// per column group adding all ranges in turn was bound by its trips to memory: 8.5 us for the
+// 17 MB of 64 ranges of a 256 x 256 output, whatever the number of loads in flight per wave);
+// few ranges of a large output want W = 1 (with W = 8 six of the eight waves idled and every
+// 64 column groups paid two barriers: 61 us for 2 ranges of a 256 x 8192 output).  The paper's
+// counterpart is the fix-up step of its Stream-K schedule (Section 5.2.3).
+template <int kReduceWaves>
 __global__ void __launch_bounds__(64 * kReduceWaves) splitk_reduce_kernel(const GemmArgs p)
 {
-    __shared__ float part[kReduceWaves - 1][2][4][64];        // sums of waves 1..: [wave-1][gate|up][column][lane]
+    __shared__ float part[kReduceWaves > 1 ? kReduceWaves - 1 : 1][2][4][64];        // sums of waves 1..: [wave-1][gate|up][column][lane]
     const bool gated = p.act == ACT_SILU_GATE;
     const int nout = gated ? (p.N >> 1) : p.N;
     const int groups = (nout + 3) >> 2;
@@ -71,11 +74,13 @@ __global__ void __launch_bounds__(64 * kReduceWaves) splitk_reduce_kernel(const 
                         if (gated) u[e] += src[s0 * plane + nout + e];
                     }
         }
-        if (wave > 0) {
+        if (kReduceWaves > 1) {
+            if (wave > 0) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { part[wave - 1][0][e][lane] = v[e]; part[wave - 1][1][e][lane] = u[e]; }
+                for (int e = 0; e < 4; ++e) { part[wave - 1][0][e][lane] = v[e]; part[wave - 1][1][e][lane] = u[e]; }
+            }
+            __syncthreads();
         }
-        __syncthreads();
         if (wave == 0 && live) {
 #pragma unroll
             for (int w = 0; w < kReduceWaves - 1; ++w)
@@ -109,8 +114,17 @@ __global__ void __launch_bounds__(64 * kReduceWaves) splitk_reduce_kernel(const 
                 }
             }
         }
-        __syncthreads();                                       // the waves' sums are read before the next round overwrites them
+        if (kReduceWaves > 1) __syncthreads();                 // the waves' sums are read before the next round overwrites them
     }
+}
+
+// Waves that share a column group's K ranges: as many (1, 2, 4 or 8) as it takes to have some 2048 waves
+// at work, each with at least four ranges.  A function of the problem alone (M, N, split factor).
+static int reduce_waves(int splits, int64_t blocks)
+{
+    int w = 1;
+    while (w < 8 && blocks * w < 2048 && splits >= 8 * w) w *= 2;
+    return w;
 }
 
 hipError_t launch_splitk_reduce(const GemmArgs &args, hipStream_t stream)
@@ -120,7 +134,12 @@ hipError_t launch_splitk_reduce(const GemmArgs &args, hipStream_t stream)
     // 64 column groups per work-group: even a 256 x 256 output spreads over all CUs
     int64_t blocks = (total + 63) / 64;
     if (blocks > 256 * 256) blocks = 256 * 256;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(64 * kReduceWaves), 0, stream, args);
+    switch (reduce_waves(args.splits, (total + 63) / 64)) {
+    case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, dim3((unsigned)blocks), dim3(512), 0, stream, args); break;
+    case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, args); break;
+    case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, dim3((unsigned)blocks), dim3(128), 0, stream, args); break;
+    default: hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3((unsigned)blocks), dim3(64), 0, stream, args); break;
+    }
     return hipGetLastError();
 }
 
