@@ -706,7 +706,7 @@ gemm_kernel(const GemmArgs p)
             float v[EPI_U][8], u[EPI_U][8];
             u32x4_t rb[EPI_U], bb[EPI_U];
             int mm[EPI_U], nn[EPI_U];
-            bool live[EPI_U], vec[EPI_U];
+            bool live[EPI_U], vec[EPI_U], whole[EPI_U];       // whole: all 8 columns inside C, whatever their alignment
 #pragma unroll
             for (int j = 0; j < EPI_U; ++j) {
                 const int idx = base + 64 * j;
@@ -714,7 +714,8 @@ gemm_kernel(const GemmArgs p)
                 mm[j] = m_wave + pass * EPI_ROWS + row;
                 nn[j] = n_wave + c8 * 8;
                 live[j] = idx < total && mm[j] < p.M && nn[j] < nout;
-                vec[j] = live[j] && p.vec_store && (nn[j] + 7 < nout);
+                whole[j] = live[j] && (nn[j] + 7 < nout);
+                vec[j] = whole[j] && p.vec_store;
                 if (idx < total) {
                     const char *src = region + row * EPI_PITCH + c8 * 32;
                     const f32x4_t x0 = *(const f32x4_t *)src, x1 = *(const f32x4_t *)(src + 16);
@@ -777,6 +778,9 @@ gemm_kernel(const GemmArgs p)
                     if (vec[j]) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bb[j][e] >> 16); }
+                    } else if (whole[j]) {                       // (unaligned rows, e.g. an odd leading dimension: element accesses, no guards)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) z[e] += (float)p.bias[n + e];
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; ++e)
@@ -793,9 +797,14 @@ gemm_kernel(const GemmArgs p)
                         for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
                     } else {
                         const __bf16 *rp = R + (int64_t)m * p.ldr + n;
+                        if (whole[j]) {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (n + e < nout) z[e] += (float)rp[e];
+                            for (int e = 0; e < 8; ++e) z[e] += (float)rp[e];
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (n + e < nout) z[e] += (float)rp[e];
+                        }
                     }
                 }
                 if (tail_gave_up) {
@@ -807,6 +816,9 @@ gemm_kernel(const GemmArgs p)
                     if (vec[j]) {
                         *(f32x4_t *)cf = f32x4_t{z[0], z[1], z[2], z[3]};
                         *(f32x4_t *)(cf + 4) = f32x4_t{z[4], z[5], z[6], z[7]};
+                    } else if (whole[j]) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) cf[e] = z[e];
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; ++e)
@@ -820,6 +832,10 @@ gemm_kernel(const GemmArgs p)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(z[2 * e]) | (f32_to_bf16_bits(z[2 * e + 1]) << 16);
                     *(u32x4_t *)cp = o;
+                } else if (whole[j]) {
+                    uint16_t *cs = (uint16_t *)cp;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) cs[e] = (uint16_t)f32_to_bf16_bits(z[e]);
                 } else {
                     uint16_t *cs = (uint16_t *)cp;
 #pragma unroll
