@@ -777,6 +777,6 @@ int fact_registry_size(void)
 
 const char *fact_last_error(void) { return g_last_error; }
 
-int fact_version(void) { return 201; }
+int fact_version(void) { return 202; }
 
 }  // extern "C"
