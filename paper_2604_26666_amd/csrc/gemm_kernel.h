@@ -308,6 +308,13 @@ gemm_kernel(const GemmArgs p)
     int e_tail_seg = 0, e_tail_tile = 0;              // tail split: K range number, tile number within the tail
     constexpr int TILE_FLOATS = BM * BN;
     constexpr int kSysScope = 17;                    // cache-policy bits sc0 | sc1 of buffer loads / stores
+    // The 16-byte stores of finished C tiles: written through the XCD's L2 (sc0 | sc1) as non-temporal
+    // data (nt).  C is not read again by this launch, and lines left dirty in the eight L2s have to be
+    // written back before the launch can end.  Same-box A/B against plain stores, operands from the
+    // memory-side cache / rotated out of it: 8192 x 2304 x 768 + bias 37.5 -> 36.6 / 48.1 -> 40.2 us,
+    // 8192 x 3072 x 768 + bias + GELU 45.3 -> 41.6 / 48.0 -> 41.7 us, 128 x 512^3 43.5 -> 42.5 / 51.5 -> 48.5 us,
+    // 8192^3 713 -> 708 us; no shape slower.  (Write-through alone: better from the cache, worse from HBM.)
+    constexpr int kStoreThrough = 19;
 
     // ---- epilogue ---------------------------------------------------------------------------
     // Accumulator tile (mt, nt), lane (r16, q): output row mt*16 + r16, output columns
@@ -522,7 +529,7 @@ gemm_kernel(const GemmArgs p)
                     o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
                 }
                 // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
-                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + j * step_c, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + j * step_c, 0, kStoreThrough);
             }
             vo += FU * step_c; vr += FU * step_r; src += FU * RPB * EPI_PITCH;
         }
@@ -630,7 +637,7 @@ gemm_kernel(const GemmArgs p)
                     o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
                 }
                 // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
-                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + pr * 64, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + pr * 64, 0, kStoreThrough);
             });
         });
     };
