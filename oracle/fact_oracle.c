@@ -26,6 +26,13 @@
  * with numpy fp64 operations; this file supplies only the contraction, the
  * bf16 <-> fp64 conversions and the single final rounding.
  *
+ * A second input format, IEEE binary16 ("fp16", the precision the paper's own
+ * kernels compute in: Listing 1; Sections 5.2.3 - 5.2.5), goes through the same
+ * contraction: orc_gemm_f64_f16 differs from orc_gemm_f64 only in how a 16-bit
+ * pattern is widened.  A product of two binary16 values has at most 22
+ * significant bits and lies between 2^-48 and 2^32, so it is exact in fp64 too.
+ * Its pins are in tests/test_oracle_pins_f16.py.
+ *
  * Pins (tests/test_oracle_pins.py): identity and permutation matrices, K = 1
  * outer products on rounding ties, exact small-integer inputs, all-ones closed
  * forms, exact rational brute force on tiny shapes, an exactly rounded sum
@@ -87,6 +94,65 @@ void orc_bf16_to_f64_array(const uint16_t *in, double *out, int64_t n)
     for (int64_t i = 0; i < n; ++i) out[i] = widen(in[i]);
 }
 
+/* ---- IEEE binary16 <-> fp64 --------------------------------------------- */
+
+/* binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.  Exponent field 0:
+ * subnormal, value = fraction * 2^-24; field 31: infinity or NaN; otherwise
+ * (1024 + fraction) * 2^(field - 25).  Every case is exact in fp64. */
+static inline double widen_f16(uint16_t h)
+{
+    const int field = (h >> 10) & 31;
+    const int frac = h & 1023;
+    double v;
+    if (field == 0) v = ldexp((double)frac, -24);
+    else if (field == 31) v = frac ? NAN : INFINITY;
+    else v = ldexp((double)(1024 + frac), field - 25);
+    return (h & 0x8000) ? -v : v;
+}
+
+double orc_f16_to_f64(uint16_t h) { return widen_f16(h); }
+
+/* Round an fp64 value to the nearest binary16, ties to even, in ONE rounding
+ * (the same scheme as orc_bf16_from_f64): normal range 2^-14 .. below 2^16,
+ * quantum 2^(exponent - 10); subnormal quantum 2^-24; a result that rounds up
+ * to 2^16 is infinity. */
+uint16_t orc_f16_from_f64(double x)
+{
+    if (isnan(x)) return 0x7E00;                       /* canonical quiet NaN */
+    uint16_t sign = signbit(x) ? 0x8000 : 0;
+    double ax = fabs(x);
+    if (isinf(ax)) return sign | 0x7C00;
+    if (ax == 0.0) return sign;
+
+    int e;
+    (void)frexp(ax, &e);
+    int exp2 = e - 1;               /* ax in [2^exp2, 2^(exp2+1)) */
+    if (exp2 < -14) exp2 = -14;     /* subnormal range shares quantum 2^-24 */
+    int qexp = exp2 - 10;
+    double q = nearbyint(ldexp(ax, -qexp));   /* exact scaling, one rounding */
+    double r = ldexp(q, qexp);                /* exact */
+    if (r >= 65536.0) return sign | 0x7C00;            /* rounded up past max */
+    if (r < ldexp(1.0, -14)) return sign | (uint16_t)q;   /* subnormal: q quanta of 2^-24 (0 .. 1023) */
+    int e2;
+    (void)frexp(r, &e2);
+    int E = e2 - 1;                 /* r in [2^E, 2^(E+1)), -14 <= E <= 15 */
+    int frac = (int)ldexp(r, 10 - E) - 1024;  /* exact integer in 0 .. 1023 */
+    return sign | (uint16_t)(((E + 15) << 10) | frac);
+}
+
+void orc_f16_from_f64_array(const double *in, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_f16_from_f64(in[i]);
+}
+
+void orc_f16_to_f64_array(const uint16_t *in, double *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = widen_f16(in[i]);
+}
+
+/* A 16-bit pattern of either format, widened exactly. */
+static inline double widen_as(uint16_t h, int f16) { return f16 ? widen_f16(h) : widen(h); }
+
 /* ---- the contraction ----------------------------------------------------- */
 
 /*
@@ -102,13 +168,15 @@ void orc_bf16_to_f64_array(const uint16_t *in, double *out, int64_t n)
  * k loop is outside the j loop so that memory is walked along rows of B;
  * each acc[r][j] still receives its terms in the order k = 0, 1, ..., K-1.
  *
- * Returns 0, or -1 on a bad argument.  bound may be NULL.
+ * Returns 0, or -1 on a bad argument.  bound may be NULL.  f16 selects how the
+ * 16-bit patterns of A and B are widened (0: bf16, 1: binary16); nothing else
+ * depends on it.
  */
-int orc_gemm_f64(int64_t M, int64_t N, int64_t K,
-                 const uint16_t *A, int64_t lda,
-                 const uint16_t *B, int64_t ldb, int trans_b,
-                 const int64_t *rows, int64_t nrows,
-                 double *acc, double *bound)
+static inline int gemm_f64_as(int f16, int64_t M, int64_t N, int64_t K,
+                              const uint16_t *A, int64_t lda,
+                              const uint16_t *B, int64_t ldb, int trans_b,
+                              const int64_t *rows, int64_t nrows,
+                              double *acc, double *bound)
 {
     if (M <= 0 || N <= 0 || K <= 0 || !A || !B || !acc || nrows < 0) return -1;
     if (lda < K) return -1;
@@ -131,12 +199,12 @@ int orc_gemm_f64(int64_t M, int64_t N, int64_t K,
 
         if (!trans_b) {
             for (int64_t k = 0; k < K; ++k) {
-                const double aik = widen(a[k]);
+                const double aik = widen_as(a[k], f16);
                 const uint16_t *b = B + k * ldb;
-                for (int64_t j = 0; j < N; ++j) c[j] += aik * widen(b[j]);
+                for (int64_t j = 0; j < N; ++j) c[j] += aik * widen_as(b[j], f16);
                 if (d) {
                     const double abs_aik = fabs(aik);
-                    for (int64_t j = 0; j < N; ++j) d[j] += abs_aik * fabs(widen(b[j]));
+                    for (int64_t j = 0; j < N; ++j) d[j] += abs_aik * fabs(widen_as(b[j], f16));
                 }
             }
         } else {
@@ -144,7 +212,7 @@ int orc_gemm_f64(int64_t M, int64_t N, int64_t K,
                 const uint16_t *w = B + j * ldb;
                 double s = 0.0, t = 0.0;
                 for (int64_t k = 0; k < K; ++k) {
-                    const double p = widen(a[k]) * widen(w[k]);
+                    const double p = widen_as(a[k], f16) * widen_as(w[k], f16);
                     s += p;
                     t += fabs(p);       /* |a||b| = |ab| exactly: p is exact */
                 }
@@ -154,6 +222,26 @@ int orc_gemm_f64(int64_t M, int64_t N, int64_t K,
         }
     }
     return 0;
+}
+
+/* bf16 inputs */
+int orc_gemm_f64(int64_t M, int64_t N, int64_t K,
+                 const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb, int trans_b,
+                 const int64_t *rows, int64_t nrows,
+                 double *acc, double *bound)
+{
+    return gemm_f64_as(0, M, N, K, A, lda, B, ldb, trans_b, rows, nrows, acc, bound);
+}
+
+/* binary16 inputs */
+int orc_gemm_f64_f16(int64_t M, int64_t N, int64_t K,
+                     const uint16_t *A, int64_t lda,
+                     const uint16_t *B, int64_t ldb, int trans_b,
+                     const int64_t *rows, int64_t nrows,
+                     double *acc, double *bound)
+{
+    return gemm_f64_as(1, M, N, K, A, lda, B, ldb, trans_b, rows, nrows, acc, bound);
 }
 
 /* Number of threads the parallel loop above will use (for reporting). */

@@ -1,4 +1,4 @@
-"""Reference results for bf16 GEMM + fused epilogue, in fp64.  TEST INFRASTRUCTURE ONLY.
+"""Reference results for bf16 (or fp16) GEMM + fused epilogue, in fp64.  TEST INFRASTRUCTURE ONLY.
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import
 this module.  It shares nothing with the HIP path and imports nothing from the
@@ -23,6 +23,10 @@ bf16 (the paper uses tf32/fp16); accumulation here is fp64.
 
 The contraction and the bf16 conversions are in fact_oracle.c; the epilogue is
 written out below with numpy fp64 operations.
+
+fmt="f16" everywhere below means that every 16-bit pattern (A, B, bias,
+residual, the output) is IEEE binary16, the precision of the paper's own kernels
+(Listing 1; Sections 5.2.3 - 5.2.5), instead of bf16; nothing else changes.
 """
 import ctypes
 import os
@@ -57,6 +61,16 @@ def lib():
         L.orc_bf16_from_f64_array.restype = None
         L.orc_bf16_to_f64_array.argtypes = [p, p, i64]
         L.orc_bf16_to_f64_array.restype = None
+        L.orc_gemm_f64_f16.argtypes = L.orc_gemm_f64.argtypes
+        L.orc_gemm_f64_f16.restype = ctypes.c_int
+        L.orc_f16_from_f64.argtypes = [ctypes.c_double]
+        L.orc_f16_from_f64.restype = ctypes.c_uint16
+        L.orc_f16_to_f64.argtypes = [ctypes.c_uint16]
+        L.orc_f16_to_f64.restype = ctypes.c_double
+        L.orc_f16_from_f64_array.argtypes = [p, p, i64]
+        L.orc_f16_from_f64_array.restype = None
+        L.orc_f16_to_f64_array.argtypes = [p, p, i64]
+        L.orc_f16_to_f64_array.restype = None
         L.orc_num_threads.argtypes = []
         L.orc_num_threads.restype = ctypes.c_int
         _lib = L
@@ -69,25 +83,34 @@ def num_threads():
 
 # ---- bf16 bit patterns ------------------------------------------------------
 
-def as_bits(x):
-    """View a bf16 array (numpy uint16, or a CPU torch.bfloat16 tensor) as numpy uint16."""
+def _check_fmt(fmt):
+    if fmt not in ("bf16", "f16"):
+        raise ValueError(f"unknown 16-bit format {fmt!r}")
+    return fmt
+
+
+def as_bits(x, fmt="bf16"):
+    """View a 16-bit float array (numpy uint16, or a CPU torch tensor of the format's dtype) as numpy uint16."""
+    _check_fmt(fmt)
     if isinstance(x, np.ndarray):
         if x.dtype != np.uint16:
-            raise TypeError("bf16 data must be given as uint16 bit patterns")
+            raise TypeError("16-bit float data must be given as uint16 bit patterns")
         return x
     import torch  # only to unwrap a tensor; no torch arithmetic is used here
     if isinstance(x, torch.Tensor):
-        if x.dtype != torch.bfloat16 or x.device.type != "cpu":
-            raise TypeError("expected a CPU bfloat16 tensor")
+        want = torch.bfloat16 if fmt == "bf16" else torch.float16
+        if x.dtype != want or x.device.type != "cpu":
+            raise TypeError(f"expected a CPU {want} tensor")
         return x.view(torch.int16).numpy().view(np.uint16)
     raise TypeError(type(x))
 
 
-def widen(bits):
-    """bf16 bit patterns -> fp64 values (exact)."""
-    b = np.ascontiguousarray(as_bits(bits))
+def widen(bits, fmt="bf16"):
+    """16-bit patterns -> fp64 values (exact)."""
+    b = np.ascontiguousarray(as_bits(bits, fmt))
     out = np.empty(b.shape, dtype=np.float64)
-    lib().orc_bf16_to_f64_array(b.ctypes.data, out.ctypes.data, b.size)
+    f = lib().orc_bf16_to_f64_array if _check_fmt(fmt) == "bf16" else lib().orc_f16_to_f64_array
+    f(b.ctypes.data, out.ctypes.data, b.size)
     return out
 
 
@@ -97,6 +120,18 @@ def round_bf16(z):
     out = np.empty(z.shape, dtype=np.uint16)
     lib().orc_bf16_from_f64_array(z.ctypes.data, out.ctypes.data, z.size)
     return out
+
+
+def round_f16(z):
+    """fp64 values -> binary16 bit patterns, round to nearest, ties to even, one rounding."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    out = np.empty(z.shape, dtype=np.uint16)
+    lib().orc_f16_from_f64_array(z.ctypes.data, out.ctypes.data, z.size)
+    return out
+
+
+def round_to(z, fmt="bf16"):
+    return round_bf16(z) if _check_fmt(fmt) == "bf16" else round_f16(z)
 
 
 def _ld(a):
@@ -112,15 +147,15 @@ def _ld(a):
 
 # ---- the contraction --------------------------------------------------------
 
-def gemm(A, B, trans_b=False, rows=None):
+def gemm(A, B, trans_b=False, rows=None, fmt="bf16"):
     """acc[r][j] = sum_k A[rows[r]][k] * B[k][j] and bound = sum_k |a||b|, both fp64.
 
     A is [M, K].  B is [K, N] (trans_b False) or [N, K] (trans_b True).  rows is
     an optional 1-D list of row indices; default all rows.  Returns (acc, bound),
     each [len(rows), N].
     """
-    A = as_bits(A)
-    B = as_bits(B)
+    A = as_bits(A, fmt)
+    B = as_bits(B, fmt)
     M, K = A.shape
     if trans_b:
         N, Kb = B.shape
@@ -135,9 +170,10 @@ def gemm(A, B, trans_b=False, rows=None):
         nrows, rows_ptr = rows_arr.size, rows_arr.ctypes.data
     acc = np.empty((nrows, N), dtype=np.float64)
     bound = np.empty((nrows, N), dtype=np.float64)
-    rc = lib().orc_gemm_f64(M, N, K, A.ctypes.data, _ld(A), B.ctypes.data, _ld(B),
-                            1 if trans_b else 0, rows_ptr, nrows,
-                            acc.ctypes.data, bound.ctypes.data)
+    f = lib().orc_gemm_f64 if _check_fmt(fmt) == "bf16" else lib().orc_gemm_f64_f16
+    rc = f(M, N, K, A.ctypes.data, _ld(A), B.ctypes.data, _ld(B),
+          1 if trans_b else 0, rows_ptr, nrows,
+          acc.ctypes.data, bound.ctypes.data)
     if rc != 0:
         raise ValueError("orc_gemm_f64 rejected its arguments")
     return acc, bound
@@ -164,11 +200,12 @@ def silu(z):
 class Ref:
     z: np.ndarray        # fp64 result before the final rounding, [nrows, Nout]
     bound: np.ndarray    # fp64 magnitude bound the tolerance scales with, same shape
-    bits: np.ndarray     # uint16: RNE_bf16(z)
+    bits: np.ndarray     # uint16: RNE(z) in the output format
     rows: np.ndarray     # which rows of the full output these are
+    fmt: str = "bf16"    # the 16-bit format of bits
 
 
-def gemm_epilogue(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE, rows=None):
+def gemm_epilogue(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE, rows=None, fmt="bf16"):
     """One fused GEMM: acc -> +bias -> act -> +residual -> bf16.
 
     With ACT_SILU_GATE, B must be [2I, K] with trans_b True: rows 0..I-1 are the
@@ -180,8 +217,8 @@ def gemm_epilogue(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE, r
     |residual|; for the gated product the product rule with |SiLU'| <= 1.1:
     1.1 bound_g |u| + |SiLU(g)| bound_u.
     """
-    acc, bnd = gemm(A, B, trans_b, rows)
-    M = as_bits(A).shape[0]
+    acc, bnd = gemm(A, B, trans_b, rows, fmt)
+    M = as_bits(A, fmt).shape[0]
     rows_arr = np.arange(M, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
 
     if act == ACT_SILU_GATE:
@@ -199,7 +236,7 @@ def gemm_epilogue(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE, r
         z = acc
         bound = bnd
         if bias is not None:
-            b = widen(bias).reshape(1, -1)
+            b = widen(bias, fmt).reshape(1, -1)
             if b.shape[1] != z.shape[1]:
                 raise ValueError("bias length")
             z = z + b
@@ -210,10 +247,10 @@ def gemm_epilogue(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE, r
             raise ValueError("unknown activation")
 
     if residual is not None:
-        r = widen(np.ascontiguousarray(as_bits(residual)[rows_arr, : z.shape[1]]))
+        r = widen(np.ascontiguousarray(as_bits(residual, fmt)[rows_arr, : z.shape[1]]), fmt)
         z = z + r
         bound = bound + np.abs(r)
-    return Ref(z=z, bound=bound, bits=round_bf16(z), rows=rows_arr)
+    return Ref(z=z, bound=bound, bits=round_to(z, fmt), rows=rows_arr, fmt=fmt)
 
 
 def block_mlp(X, W1, W1u, b1, act, W2, b2, R, rows=None, H_bits=None):
