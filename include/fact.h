@@ -66,7 +66,7 @@ typedef enum fact_act {
 
 /*
  * Fused epilogue, applied in registers in this order:
- *     z = acc + bias[n];  z = act(z);  z = z + residual[m][n];  C[m][n] = bf16(z)
+ *     z = acc + bias[n];  z = act(z);  z = z + residual[m][n];  C[m][n] = bf16(z)   (fp16(z) with f16 = 1)
  * bias     : bf16[Nout] device pointer or NULL.
  * residual : bf16[M][ldr] device pointer or NULL; ldr in elements, >= Nout.
  * act      : a fact_act.  With FACT_ACT_SILU_GATE the GEMM's B must be given with
@@ -89,6 +89,14 @@ typedef struct fact_epilogue {
                                epilogue writes the fp32 result, with K split (fact_gemm_splitk / fact_gemm_ex and
                                a workspace of fact_gemm_f32out_workspace_bytes()) the reduction pass does.
                                Shapes or pointers that only the guarded fallback kernel serves: FACT_ERR_UNSUPPORTED. */
+    int32_t f16;            /* 1: A, B, bias, residual and C (unless out_f32) hold IEEE binary16 instead of bf16: the
+                               precision the paper's own kernels compute in ("fp16 with fp32 accumulator", Listing 1;
+                               Sections 5.2.3 - 5.2.5).  Same kernels with the fp16 matrix instruction, fp32
+                               accumulation, one rounding to nearest even at the store (overflow gives infinity);
+                               same layouts, alignment rules, tile table and error codes.  Taken by fact_gemm,
+                               fact_gemm_batched, fact_gemm_splitk(_static) and fact_gemm_ex; the block entry
+                               points (fact_block_mlp, fact_attention, fact_block_forward) compute in bf16 only.
+                               0 (and a NULL epilogue): bf16.  Other values: FACT_ERR_EPILOGUE. */
 } fact_epilogue;
 
 /* ---- entry points --------------------------------------------------------------------- */

@@ -98,16 +98,26 @@ void orc_bf16_to_f64_array(const uint16_t *in, double *out, int64_t n)
 
 /* binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.  Exponent field 0:
  * subnormal, value = fraction * 2^-24; field 31: infinity or NaN; otherwise
- * (1024 + fraction) * 2^(field - 25).  Every case is exact in fp64. */
+ * (1024 + fraction) * 2^(field - 25).  Every case is exact in binary32, which
+ * is built bit by bit here (the contraction calls this once per term), then in
+ * fp64. */
 static inline double widen_f16(uint16_t h)
 {
-    const int field = (h >> 10) & 31;
-    const int frac = h & 1023;
-    double v;
-    if (field == 0) v = ldexp((double)frac, -24);
-    else if (field == 31) v = frac ? NAN : INFINITY;
-    else v = ldexp((double)(1024 + frac), field - 25);
-    return (h & 0x8000) ? -v : v;
+    const uint32_t sign = (uint32_t)(h & 0x8000) << 16;
+    const uint32_t field = (h >> 10) & 31, frac = h & 1023;
+    uint32_t u;
+    float f;
+    if (field == 0) {                       /* fraction * 2^-24: at most 10 bits, exact in binary32 */
+        f = (float)frac * 0x1p-24f;
+        memcpy(&u, &f, sizeof u);
+        u |= sign;
+    } else if (field == 31) {               /* infinity (fraction 0) or NaN */
+        u = sign | 0x7F800000u | (frac << 13);
+    } else {                                /* the binary32 with the same value: exponent bias 127 - 15, fraction moved up 13 bits */
+        u = sign | ((field + 112) << 23) | (frac << 13);
+    }
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
 }
 
 double orc_f16_to_f64(uint16_t h) { return widen_f16(h); }

@@ -30,7 +30,7 @@ class FactError(RuntimeError):
 
 class _CEpilogue(ctypes.Structure):
     _fields_ = [("bias", _ptr), ("residual", _ptr), ("ldr", _i64), ("stride_r", _i64), ("act", ctypes.c_int32),
-                ("out_f32", ctypes.c_int32)]
+                ("out_f32", ctypes.c_int32), ("f16", ctypes.c_int32)]
 
 
 class _CBlock(ctypes.Structure):
@@ -64,11 +64,12 @@ class Block:
 class Epilogue:
     """Mirror of the C struct fact_epilogue."""
 
-    def __init__(self, bias=None, residual=None, ldr=0, stride_r=0, act=ACT_NONE, out_f32=0):
+    def __init__(self, bias=None, residual=None, ldr=0, stride_r=0, act=ACT_NONE, out_f32=0, f16=0):
         self.bias, self.residual, self.ldr, self.stride_r, self.act, self.out_f32 = bias, residual, ldr, stride_r, act, out_f32
+        self.f16 = f16
 
     def _c(self):
-        return _CEpilogue(_addr(self.bias), _addr(self.residual), int(self.ldr), int(self.stride_r), int(self.act), int(self.out_f32))
+        return _CEpilogue(_addr(self.bias), _addr(self.residual), int(self.ldr), int(self.stride_r), int(self.act), int(self.out_f32), int(self.f16))
 
 
 _lib = None

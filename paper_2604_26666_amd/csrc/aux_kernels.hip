@@ -4,6 +4,10 @@
 
 namespace fact {
 
+// 16-bit pattern <-> fp32 in the launch's format (these kernels are bound by memory traffic: a run-time choice)
+__device__ __forceinline__ float in16_rt(int f16, uint32_t bits) { return f16 ? f16_bits_to_f32(bits) : bf16_bits_to_f32(bits); }
+__device__ __forceinline__ uint32_t out16_rt(int f16, float x) { return f16 ? f32_to_f16_bits(x) : f32_to_bf16_bits(x); }
+
 // ---- split-K reduction -----------------------------------------------------------------
 // P holds `splits` fp32 partial products [M][N].  A lane owns 4 consecutive output columns of
 // one row; the W waves of a work-group own the same 64 such column groups and a W-th of the K
@@ -90,9 +94,9 @@ __global__ void __launch_bounds__(64 * kReduceWaves) splitk_reduce_kernel(const 
                 if (n + e >= nout) continue;
                 float zv = v[e];
                 if (gated) zv = silu(zv) * u[e];
-                if (p.bias) zv += (float)p.bias[n + e];
+                if (p.bias) zv += in16_rt(p.f16, ((const uint16_t *)p.bias)[n + e]);
                 if (p.act == ACT_GELU_TANH) zv = gelu_tanh(zv);
-                if (p.res) zv += (float)p.res[(int64_t)m * p.ldr + n + e];
+                if (p.res) zv += in16_rt(p.f16, ((const uint16_t *)p.res)[(int64_t)m * p.ldr + n + e]);
                 v[e] = zv;
             }
             if (p.out_f32) {                                   // fp32 output: no rounding at all
@@ -106,11 +110,11 @@ __global__ void __launch_bounds__(64 * kReduceWaves) splitk_reduce_kernel(const 
             } else {
                 __bf16 *cp = p.C + (int64_t)m * p.ldc + n;
                 if (full && p.vec_store) {
-                    *(u32x2_t *)cp = pack4_bf16(v[0], v[1], v[2], v[3]);
+                    *(u32x2_t *)cp = u32x2_t{out16_rt(p.f16, v[0]) | (out16_rt(p.f16, v[1]) << 16), out16_rt(p.f16, v[2]) | (out16_rt(p.f16, v[3]) << 16)};
                 } else {
                     uint16_t *cs = (uint16_t *)cp;
                     for (int e = 0; e < 4; ++e)
-                        if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(v[e]);
+                        if (n + e < nout) cs[e] = (uint16_t)out16_rt(p.f16, v[e]);
                 }
             }
         }
@@ -164,20 +168,20 @@ __global__ void __launch_bounds__(256) fallback_gemm_kernel(const GemmArgs p)
         const uint16_t *w = B + (int64_t)n * p.ldb;
         const uint16_t *wu = gated ? (const uint16_t *)(p.B_up + z * p.stride_b) + (int64_t)n * p.ldb : nullptr;
         for (int k = 0; k < p.K; ++k) {
-            const float a = bf16_bits_to_f32(A[k]);
-            acc = __builtin_fmaf(a, bf16_bits_to_f32(w[k]), acc);
-            if (gated) acc_up = __builtin_fmaf(a, bf16_bits_to_f32(wu[k]), acc_up);
+            const float a = in16_rt(p.f16, A[k]);
+            acc = __builtin_fmaf(a, in16_rt(p.f16, w[k]), acc);
+            if (gated) acc_up = __builtin_fmaf(a, in16_rt(p.f16, wu[k]), acc_up);
         }
     } else {
         for (int k = 0; k < p.K; ++k)
-            acc = __builtin_fmaf(bf16_bits_to_f32(A[k]), bf16_bits_to_f32(B[(int64_t)k * p.ldb + n]), acc);
+            acc = __builtin_fmaf(in16_rt(p.f16, A[k]), in16_rt(p.f16, B[(int64_t)k * p.ldb + n]), acc);
     }
     float zv = acc;
     if (gated) zv = silu(zv) * acc_up;
-    if (p.bias) zv += (float)p.bias[n];
+    if (p.bias) zv += in16_rt(p.f16, ((const uint16_t *)p.bias)[n]);
     if (p.act == ACT_GELU_TANH) zv = gelu_tanh(zv);
-    if (p.res) zv += (float)(p.res + z * p.stride_r)[(int64_t)m * p.ldr + n];
-    ((uint16_t *)(p.C + z * p.stride_c))[(int64_t)m * p.ldc + n] = (uint16_t)f32_to_bf16_bits(zv);
+    if (p.res) zv += in16_rt(p.f16, ((const uint16_t *)(p.res + z * p.stride_r))[(int64_t)m * p.ldr + n]);
+    ((uint16_t *)(p.C + z * p.stride_c))[(int64_t)m * p.ldc + n] = (uint16_t)out16_rt(p.f16, zv);
 }
 
 hipError_t launch_fallback_gemm(const GemmArgs &args, bool trans_b, int grid_z, hipStream_t stream)

@@ -217,6 +217,7 @@ static int validate(const Problem &q)
                           (uintptr_t)q.ep.residual | (uintptr_t)q.B_up;
     if (two & 1u) return FACT_ERR_ALIGN;
     if (q.ep.out_f32 != 0 && q.ep.out_f32 != 1) return FACT_ERR_EPILOGUE;
+    if (q.ep.f16 != 0 && q.ep.f16 != 1) return FACT_ERR_EPILOGUE;
     if (q.ep.out_f32 && ((uintptr_t)q.C & 3u)) return FACT_ERR_ALIGN;
     return FACT_OK;
 }
@@ -323,6 +324,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     // 16-byte vector access to C / residual / bias in the epilogue
     a.out_f32 = out_f32 ? 1 : 0;
     a.c_f32 = c_f32 ? 1 : 0;
+    a.f16 = q.ep.f16;
     // (an fp32 row of 8 columns is two 16-byte pieces: ldc and the batch stride in multiples of 4)
     a.vec_store = (nout % 8 == 0) && q.ldc % (c_f32 ? 4 : 8) == 0 && aligned16(q.C) && q.stride_c % (c_f32 ? 4 : 8) == 0 &&
                   (!q.ep.bias || aligned16(q.ep.bias)) &&
@@ -411,7 +413,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
     }
     // Persistent launch: more work items than resident work-groups, K whole, no tail split.
     a.persist_items = 0; a.persist_z = 1; a.persist_grid = 0;
-    if (a.tail_g <= 1 && a.splits <= 1) {
+    if (a.tail_g <= 1 && a.splits <= 1 && !a.f16) {       // (the persistent form is instantiated for bf16 only)
         const int grid = persistent_grid(c, tiles_m * tiles_n * q.batch);
         if (grid > 0) { a.persist_items = (int)(tiles_m * tiles_n * q.batch); a.persist_z = (int)q.batch; a.persist_grid = grid; }
     }

@@ -58,6 +58,7 @@ struct GemmArgs {
     // each; the remaining tiles are shared by tail_g work-groups each, one K range apiece.
     int out_f32;            // fp32 output (written by the reduce pass; the main kernel then always stores partials)
     int c_f32;              // C holds fp32 and this kernel's epilogue writes it, unrounded (K not split)
+    int f16;                // 1: A, B, bias, residual and a 16-bit C are IEEE binary16 (else bf16)
     int tail_first;         // number of tiles computed whole (== tiles_m * tiles_n when tail_g <= 1)
     int tail_g;             // K ranges per tail tile (0 or 1: off)
     float *tail_ws;         // fp32 partial accumulators, (tail_g - 1) per tail tile
@@ -124,6 +125,30 @@ __device__ __forceinline__ u32x2_t pack4_bf16(float a, float b, float c, float d
     r.x = f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
     r.y = f32_to_bf16_bits(c) | (f32_to_bf16_bits(d) << 16);
     return r;
+}
+
+// The two 16-bit formats a launch may compute in.  F16 = false: bf16 (the workload definition's); F16 = true: IEEE
+// binary16, the precision of the paper's own kernels (Listing 1; Sections 5.2.3 - 5.2.5).  Either way the
+// accumulator is fp32 and the epilogue rounds once, to nearest even.
+typedef __bf16 pk_bf16_t __attribute__((ext_vector_type(2)));
+typedef _Float16 pk_f16_t __attribute__((ext_vector_type(2)));
+typedef float pk_f32_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h16) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h16); }
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float x) { return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)x); }
+template <bool F16> __device__ __forceinline__ float in16(uint32_t bits)
+{
+    if constexpr (F16) return f16_bits_to_f32(bits);
+    else return bf16_bits_to_f32(bits);
+}
+template <bool F16> __device__ __forceinline__ uint32_t out16(float x)
+{
+    if constexpr (F16) return f32_to_f16_bits(x);
+    else return f32_to_bf16_bits(x);
+}
+template <bool F16> __device__ __forceinline__ uint32_t pack2(pk_f32_t f2)       // two values rounded to nearest even, low half first
+{
+    if constexpr (F16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, pk_f16_t));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, pk_bf16_t));
 }
 
 // Work-group id -> tile coordinates.  Consecutive work-group ids go to different
@@ -226,6 +251,11 @@ template <int T> struct AccTile;
             asm volatile("v_mfma_f32_16x16x32_bf16 a[" #R0 ":" #R3 "], %0, %1, a[" #R0 ":" #R3 "]"                               \
                          : : "v"(b), "v"(a) : "a" #R0, "a" #R1, "a" #R2, "a" #R3);                                               \
         }                                                                                                                        \
+        static __device__ __forceinline__ void mfma_f16(const bf16x8_t &b, const bf16x8_t &a)   /* the same registers holding binary16 */ \
+        {                                                                                                                        \
+            asm volatile("v_mfma_f32_16x16x32_f16 a[" #R0 ":" #R3 "], %0, %1, a[" #R0 ":" #R3 "]"                                \
+                         : : "v"(b), "v"(a) : "a" #R0, "a" #R1, "a" #R2, "a" #R3);                                               \
+        }                                                                                                                        \
         static __device__ __forceinline__ void zero()                                                                            \
         {                                                                                                                        \
             asm volatile("v_accvgpr_write_b32 a" #R0 ", 0\n\tv_accvgpr_write_b32 a" #R1 ", 0\n\t"                                \
@@ -270,7 +300,8 @@ __device__ __forceinline__ GemmArgs fresh_args()
 
 // PERSIST: the work-group walks several work items (persistent launch; 4-wave configurations only).  The
 // ordinary kernel is a separate instantiation in which the loop below is gone at compile time.
-template <int BM, int BN, int WGM, int WGN, bool TRANS_B, int BK, int STAGES, bool PERSIST>
+// F16: the operands, bias, residual and the 16-bit output are IEEE binary16 instead of bf16.
+template <int BM, int BN, int WGM, int WGN, bool TRANS_B, int BK, int STAGES, bool PERSIST, bool F16 = false>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_kernel(const GemmArgs p)
 {
@@ -366,7 +397,6 @@ gemm_kernel(const GemmArgs p)
     const __amdgpu_buffer_rsrc_t rsrc_part = __builtin_amdgcn_make_buffer_rsrc(      // this tile's partials
         (void *)wave_uniform((const char *)(e_in_tail ? p.tail_ws + (int64_t)e_tail_tile * tail_parts * TILE_FLOATS : nullptr)), 0,
         (uint32_t)(tail_parts * TILE_FLOATS * 4), kBufferFlags);
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
     auto fast_pass = [&](int pass, auto gated_tag) __attribute__((always_inline)) {
         constexpr bool GATED = decltype(gated_tag)::value;
@@ -385,7 +415,7 @@ gemm_kernel(const GemmArgs p)
         if (p.bias) {
             const u32x4_t b4 = *(const u32x4_t *)(p.bias + n);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+            for (int e = 0; e < 4; ++e) { bv[2 * e] = in16<F16>(b4[e] & 0xFFFFu); bv[2 * e + 1] = in16<F16>(b4[e] >> 16); }
         }
         const int act = p.act;
 #pragma unroll
@@ -426,7 +456,7 @@ gemm_kernel(const GemmArgs p)
                     }
                     if (R) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += in16<F16>(rb[j][e] & 0xFFFFu); z[2 * e + 1] += in16<F16>(rb[j][e] >> 16); }
                     }
                     if (tail_gave_up) {
 #pragma unroll
@@ -442,7 +472,7 @@ gemm_kernel(const GemmArgs p)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
-                        o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                        o[e] = pack2<F16>(f2);     // round to nearest even
                     }
                     *(u32x4_t *)(C + (int64_t)(m_wave + pass * EPI_ROWS + row[j]) * p.ldc + n) = o;
                 }
@@ -482,7 +512,7 @@ gemm_kernel(const GemmArgs p)
         if (p.bias) {
             const u32x4_t b4 = *(const u32x4_t *)(p.bias + n_wave + c8 * 8);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { bv[2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+            for (int e = 0; e < 4; ++e) { bv[2 * e] = in16<F16>(b4[e] & 0xFFFFu); bv[2 * e + 1] = in16<F16>(b4[e] >> 16); }
         }
         const bool gelu = p.act == ACT_GELU_TANH, has_res = R != nullptr;
         const int64_t row0 = m_wave + pass * EPI_ROWS;
@@ -520,13 +550,13 @@ gemm_kernel(const GemmArgs p)
                 }
                 if (has_res) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                    for (int e = 0; e < 4; ++e) { z[2 * e] += in16<F16>(rb[j][e] & 0xFFFFu); z[2 * e + 1] += in16<F16>(rb[j][e] >> 16); }
                 }
                 u32x4_t o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
-                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                    o[e] = pack2<F16>(f2);     // round to nearest even
                 }
                 // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
                 __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + j * step_c, 0, kStoreThrough);
@@ -578,7 +608,7 @@ gemm_kernel(const GemmArgs p)
                 if constexpr (LEAN) bp[pr] = b4;
                 else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { bv[pr][2 * e] = bf16_bits_to_f32(b4[e] & 0xFFFFu); bv[pr][2 * e + 1] = bf16_bits_to_f32(b4[e] >> 16); }
+                    for (int e = 0; e < 4; ++e) { bv[pr][2 * e] = in16<F16>(b4[e] & 0xFFFFu); bv[pr][2 * e + 1] = in16<F16>(b4[e] >> 16); }
                 }
             }
         }
@@ -615,7 +645,7 @@ gemm_kernel(const GemmArgs p)
                 if constexpr (BIAS) {
                     if constexpr (LEAN) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bp[pr][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bp[pr][e] >> 16); }
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += in16<F16>(bp[pr][e] & 0xFFFFu); z[2 * e + 1] += in16<F16>(bp[pr][e] >> 16); }
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) z[e] += bv[pr][e];
@@ -628,13 +658,13 @@ gemm_kernel(const GemmArgs p)
                 if constexpr (RES) {
                     const u32x4_t r4 = rb[LEAN ? 0 : (mt & 1)][pr];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(r4[e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(r4[e] >> 16); }
+                    for (int e = 0; e < 4; ++e) { z[2 * e] += in16<F16>(r4[e] & 0xFFFFu); z[2 * e + 1] += in16<F16>(r4[e] >> 16); }
                 }
                 u32x4_t o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const f32x2_t f2 = {z[2 * e], z[2 * e + 1]};
-                    o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));     // round to nearest even
+                    o[e] = pack2<F16>(f2);     // round to nearest even
                 }
                 // (scalar offset operand: the constant 0, see the note at the partial-tile stores below)
                 __builtin_amdgcn_raw_buffer_store_b128(o, rsrc_c, vo + pr * 64, 0, kStoreThrough);
@@ -796,7 +826,7 @@ gemm_kernel(const GemmArgs p)
                 if (p.bias) {
                     if (vec[j]) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(bb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(bb[j][e] >> 16); }
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += in16<F16>(bb[j][e] & 0xFFFFu); z[2 * e + 1] += in16<F16>(bb[j][e] >> 16); }
                     } else if (whole[j]) {                       // (unaligned rows, e.g. an odd leading dimension: element accesses, no guards)
 #pragma unroll
                         for (int e = 0; e < 8; ++e) z[e] += (float)p.bias[n + e];
@@ -813,7 +843,7 @@ gemm_kernel(const GemmArgs p)
                 if (R) {
                     if (vec[j]) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) { z[2 * e] += bf16_bits_to_f32(rb[j][e] & 0xFFFFu); z[2 * e + 1] += bf16_bits_to_f32(rb[j][e] >> 16); }
+                        for (int e = 0; e < 4; ++e) { z[2 * e] += in16<F16>(rb[j][e] & 0xFFFFu); z[2 * e + 1] += in16<F16>(rb[j][e] >> 16); }
                     } else {
                         const __bf16 *rp = R + (int64_t)m * p.ldr + n;
                         if (whole[j]) {
@@ -849,17 +879,17 @@ gemm_kernel(const GemmArgs p)
                 if (vec[j]) {
                     u32x4_t o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(z[2 * e]) | (f32_to_bf16_bits(z[2 * e + 1]) << 16);
+                    for (int e = 0; e < 4; ++e) o[e] = out16<F16>(z[2 * e]) | (out16<F16>(z[2 * e + 1]) << 16);
                     *(u32x4_t *)cp = o;
                 } else if (whole[j]) {
                     uint16_t *cs = (uint16_t *)cp;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) cs[e] = (uint16_t)f32_to_bf16_bits(z[e]);
+                    for (int e = 0; e < 8; ++e) cs[e] = (uint16_t)out16<F16>(z[e]);
                 } else {
                     uint16_t *cs = (uint16_t *)cp;
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        if (n + e < nout) cs[e] = (uint16_t)f32_to_bf16_bits(z[e]);
+                        if (n + e < nout) cs[e] = (uint16_t)out16<F16>(z[e]);
                 }
             }
         }
@@ -1346,7 +1376,8 @@ gemm_kernel(const GemmArgs p)
         constexpr int u = decltype(u_)::value, idx = decltype(idx_)::value;     // compile-time: they name the accumulator's registers
         constexpr int kk = u / PH, h = u % PH;
         constexpr int nt = idx / MTH, x = (nt & 1) ? MTH - 1 - idx % MTH : idx % MTH;
-        AccTile<(h * MTH + x) * NT + nt>::mfma(bf[kk & 1][nt], af[u & 1][x]);
+        if constexpr (F16) AccTile<(h * MTH + x) * NT + nt>::mfma_f16(bf[kk & 1][nt], af[u & 1][x]);
+        else AccTile<(h * MTH + x) * NT + nt>::mfma(bf[kk & 1][nt], af[u & 1][x]);
     };
 
     // ---- main loop -----------------------------------------------------------------------

@@ -18,8 +18,9 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
     constexpr bool CAN_PERSIST = FACT_WM * FACT_WN <= 4;      // the persistent form exists for 4-wave configurations
     auto kern = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES, false>;
     auto kern_p = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES, CAN_PERSIST>;
+    auto kern_h = gemm_kernel<FACT_BM, FACT_BN, FACT_WM, FACT_WN, TRANS_B, FACT_BK, FACT_STAGES, false, true>;      // binary16 operands (ordinary launches only)
     const bool persist = CAN_PERSIST && args.persist_items > 0;
-    if (args.persist_items > 0 && !CAN_PERSIST) return hipErrorInvalidConfiguration;     // (the host side never asks for it)
+    if (args.persist_items > 0 && (!CAN_PERSIST || args.f16)) return hipErrorInvalidConfiguration;     // (the host side never asks for it)
     constexpr int lds = lds_total(FACT_BM, FACT_BN, FACT_WM, FACT_WN, FACT_BK, FACT_STAGES);
     static std::atomic<bool> attr_set[64];         // (two host threads may make a kernel's first launch at once: setting the limit twice is harmless)
     int dev = 0;
@@ -33,6 +34,8 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
             e = hipFuncSetAttribute((const void *)kern_p, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
             if (e != hipSuccess) return e;
         }
+        e = hipFuncSetAttribute((const void *)kern_h, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
         attr_set[dev].store(true, std::memory_order_release);
     }
     const int tiles = args.tiles_m * args.tiles_n;
@@ -40,7 +43,8 @@ static hipError_t launch_one(const GemmArgs &args, int grid_z, hipStream_t strea
     dim3 grid((unsigned)grid_x, 1, (unsigned)grid_z);
     if (args.persist_items > 0) grid = dim3((unsigned)args.persist_grid, 1, 1);
     dim3 block(FACT_WM * FACT_WN * 64, 1, 1);
-    if (persist) hipLaunchKernelGGL(kern_p, grid, block, lds, stream, args);
+    if (args.f16) hipLaunchKernelGGL(kern_h, grid, block, lds, stream, args);
+    else if (persist) hipLaunchKernelGGL(kern_p, grid, block, lds, stream, args);
     else hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
     return hipGetLastError();
     }

@@ -47,6 +47,19 @@ def small_int(shape, lo, hi, name):
     return x.to(torch.float32).to(torch.bfloat16)
 
 
+def normal_f16(shape, std, name):
+    """fp32 normal with the given standard deviation, converted to IEEE binary16 (torch.float16)."""
+    x = torch.randn(shape, generator=_generator(name), dtype=torch.float32) * float(std)
+    return x.to(torch.float16)
+
+
+def small_int_f16(shape, lo, hi, name):
+    """Integers in [lo, hi], exactly representable in binary16 (|v| <= 2048)."""
+    assert -2048 <= lo <= hi <= 2048
+    x = torch.randint(lo, hi + 1, shape, generator=_generator(name), dtype=torch.int32)
+    return x.to(torch.float32).to(torch.float16)
+
+
 def permutation(n, name):
     return torch.randperm(n, generator=_generator(name))
 
@@ -60,7 +73,7 @@ def choice_rows(M, count, name, edges=()):
 
 
 def bits(t):
-    """uint16 numpy view of a CPU bfloat16 tensor."""
+    """uint16 numpy view of a CPU bfloat16 (or float16) tensor."""
     return t.view(torch.int16).numpy().view(np.uint16)
 
 
@@ -80,6 +93,13 @@ def config2(n=8192):
     """Square GEMM, inputs ~ N(0,1), fused bias ~ N(0,1)."""
     return {"A": normal((n, n), 1.0, "c2.A"), "B": normal((n, n), 1.0, "c2.B"),
             "bias": normal((n,), 1.0, "c2.bias")}
+
+
+def config2_f16(n=8192):
+    """The square GEMM of config2 with every tensor in binary16 (the paper's own precision; same seeds'
+    fp32 draws, rounded to fp16 instead of bf16)."""
+    return {"A": normal_f16((n, n), 1.0, "c2.A"), "B": normal_f16((n, n), 1.0, "c2.B"),
+            "bias": normal_f16((n,), 1.0, "c2.bias")}
 
 
 def config3a(batch=128, n=512):
