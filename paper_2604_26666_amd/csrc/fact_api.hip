@@ -247,6 +247,7 @@ static TailPlan tail_plan(const ConfigDesc &c, int64_t tiles, int64_t K, int g)
     const int64_t slots = (int64_t)kNumCU * wgs_per_cu(c);
     const int64_t ksteps = (K + 63) / 64;
     if (g < 2 || ksteps / g < 4) return t;            // too little K per range to be worth a hand-over
+    if (!c.has_prefetch()) return t;                  // (no sink behind the ring: the collector has nowhere to pass its verdict)
     t.first = tiles / slots * slots;
     t.rem = tiles - t.first;
     if (t.rem == 0) { t.first = 0; return t; }
@@ -392,7 +393,7 @@ static int run(const Problem &q, int cfg_id, int split, int group_m, bool allow_
         // no gain or a small loss for K = 768, for half-empty grids and for split-K ranges.
         const int64_t wgs = a.tail_g > 1 ? a.tail_first + (tiles_m * tiles_n - a.tail_first) * a.tail_g : grid;
         const bool one_round_long_k = pl.split <= 1 && wgs >= 3 * kNumCU / 4 && q.K >= 2048;
-        if (soff_ok) {
+        if (soff_ok && c.has_prefetch()) {
             // (a round and a half of whole-K tiles counts as many: 8192 x 2304 x 768 on 384 tiles of 256 x 192,
             // operands from HBM, 48.0 -> 42.9 us with the prefetch, 37.4 -> 36.9 us from the memory-side cache)
             if (grid >= 2 * kNumCU || (a.splits <= 1 && grid >= 3 * kNumCU / 2) || one_round_long_k) {
@@ -781,6 +782,6 @@ int fact_registry_size(void)
 
 const char *fact_last_error(void) { return g_last_error; }
 
-int fact_version(void) { return 203; }
+int fact_version(void) { return 204; }
 
 }  // extern "C"

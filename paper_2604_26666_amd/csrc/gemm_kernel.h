@@ -192,17 +192,33 @@ constexpr bool plain_b_supported(int bn) { return 64 % (bn / 8) == 0; }
 // Epilogue staging geometry (shared with the host side, which sizes the dynamic LDS): each wave
 // transposes its accumulators through an fp32 region of epi_rows rows with this pitch.
 constexpr int epi_pitch(int wtn) { return wtn * 4 + 16; }
-constexpr int epi_rows(int wtm, int wtn, int nwaves) { return (wtm >= 64 && nwaves * 64 * epi_pitch(wtn) <= 144 * 1024) ? 64 : 32; }
+// Half a compute unit's LDS: a configuration that stays within it runs two work-groups per compute unit (its registers
+// permitting), one's K loop under the other's prologue and epilogue.  Nothing optional may be what pushes a
+// configuration over that line: the epilogue then stages 32 rows per pass instead of 64, and a ring of exactly this size
+// does without the L2 prefetch and its sink (has_prefetch).
+constexpr int kHalfLds = 80 * 1024;
+constexpr int ring_bytes(int bm, int bn, int bk, int stages) { return stages * (bm + bn) * bk * 2; }
+constexpr int epi_rows(int wtm, int wtn, int nwaves, int ring)
+{
+    const int r64 = nwaves * 64 * epi_pitch(wtn);
+    return (wtm >= 64 && r64 <= 144 * 1024 && !(ring <= kHalfLds && r64 > kHalfLds)) ? 64 : 32;
+}
 constexpr int lds_bytes(int bm, int bn, int wgm, int wgn, int bk, int stages)
 {
-    const int ring = stages * (bm + bn) * bk * 2;
-    const int epi = wgm * wgn * epi_rows(bm / wgm, bn / wgn, wgm * wgn) * epi_pitch(bn / wgn);
+    const int ring = ring_bytes(bm, bn, bk, stages);
+    const int epi = wgm * wgn * epi_rows(bm / wgm, bn / wgn, wgm * wgn, ring) * epi_pitch(bn / wgn);
     return ring > epi ? ring : epi;
 }
-// plus a small sink for the L2 prefetch loads (256 bytes per wave) behind it
+// The L2 prefetch loads land in a small sink behind the operand ring (256 bytes per wave); the collecting work-group of a
+// tail split also passes its verdict through a word of it.
+constexpr bool has_prefetch(int bm, int bn, int wgm, int wgn, int bk, int stages)
+{
+    const int b = lds_bytes(bm, bn, wgm, wgn, bk, stages);
+    return !(b <= kHalfLds && b + wgm * wgn * 256 > kHalfLds);
+}
 constexpr int lds_total(int bm, int bn, int wgm, int wgn, int bk, int stages)
 {
-    return lds_bytes(bm, bn, wgm, wgn, bk, stages) + wgm * wgn * 256;
+    return lds_bytes(bm, bn, wgm, wgn, bk, stages) + (has_prefetch(bm, bn, wgm, wgn, bk, stages) ? wgm * wgn * 256 : 0);
 }
 
 // Wait until at most N of this wave's global->LDS loads are outstanding and all its LDS
@@ -359,7 +375,7 @@ gemm_kernel(const GemmArgs p)
     // Region row pitch = row bytes + 16, which spreads the 16 rows a write instruction touches
     // over all banks.  Only the wave itself reads what it wrote: no work-group barrier inside.
     constexpr int EPI_PITCH = epi_pitch(WTN);
-    constexpr int EPI_ROWS = epi_rows(WTM, WTN, NWAVES);
+    constexpr int EPI_ROWS = epi_rows(WTM, WTN, NWAVES, ring_bytes(BM, BN, BK, STAGES));
     constexpr int EPI_TR = EPI_ROWS / 16;                       // tile-rows per pass
     constexpr int EPI_REGION = EPI_ROWS * EPI_PITCH;
     static_assert(lds_total(BM, BN, WGM, WGN, BK, STAGES) <= 160 * 1024 && NWAVES * EPI_REGION <= lds_bytes(BM, BN, WGM, WGN, BK, STAGES) && WTM % EPI_ROWS == 0, "LDS budget");
@@ -1150,7 +1166,9 @@ gemm_kernel(const GemmArgs p)
         (void *)wave_uniform(pf_is_a ? base_a : (pf_up ? base_b_up : base_b)), 0, wave_uniform(pf_is_a ? nrec_a : nrec_b), kBufferFlags);
     char *pf_sink = smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES) + wave * 256;
     const int pf_step_u = (int)wave_uniform(pf_step);          // the same in every lane: a scalar offset, no per-lane loop
+    constexpr bool PF = has_prefetch(BM, BN, WGM, WGN, BK, STAGES);      // (without it there is no sink: nothing below may be issued)
     auto prefetch_step = [&](int step) __attribute__((always_inline)) {
+        if constexpr (!PF) return;
         const uint32_t off = step < ksteps - 1 ? 0u : kOobOffset;
         const int st = step < ksteps - 1 ? step : 0;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_pf, FACT_LDS_PTR(pf_sink), 4, pf_voff | off, st * pf_step_u, 0, 0);
@@ -1159,6 +1177,7 @@ gemm_kernel(const GemmArgs p)
     // range is clamped to the last one (a line touched twice costs an L2 hit; lines past a K range
     // or a matrix edge are outside the descriptor and touch nothing).
     auto prefetch_steady = [&](int step) __attribute__((always_inline)) {
+        if constexpr (!PF) return;
         const int st = step < ksteps - 1 ? step : ksteps - 1;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_pf, FACT_LDS_PTR(pf_sink), 4, pf_voff, st * pf_step_u, 0, 0);
     };
@@ -1399,7 +1418,7 @@ gemm_kernel(const GemmArgs p)
     // a scheduling fence after every MFMA to keep every memory instruction where it was put.
     // every step's loads are followed by one prefetch load; a wave may leave outstanding the
     // newest STAGES-2 such groups and the prefetch behind the group it waits for
-    constexpr int WAIT_N = (STAGES - 2) * (LOADS + 1) + 1;
+    constexpr int WAIT_N = (STAGES - 2) * (LOADS + (PF ? 1 : 0)) + (PF ? 1 : 0);
     // The address unit is shared by the CU's waves and takes one wave-wide load per 16 cycles, so a
     // step's loads are spread evenly: over the first 3/4 of the step's MFMAs with a two-slot
     // ring (they must have landed by its end), over nearly all of it with a deeper ring.
@@ -1447,7 +1466,8 @@ gemm_kernel(const GemmArgs p)
     // The prefetch behind the loads of step x covers step x + pf_dist; the steps between the
     // prologue's loads and the first of those are touched here, ahead of the loads (older than
     // them, so the wait counts are unaffected).
-    for (int x = STAGES - 1; x < p.pf_dist; ++x) prefetch_step(x);
+    if constexpr (PF)
+        for (int x = STAGES - 1; x < p.pf_dist; ++x) prefetch_step(x);
     if (ksteps >= STAGES) {
         // every step of the prologue is a whole step inside the K range: the steady form of the loads
         // (offsets already in registers) instead of some fifteen instructions of range arithmetic per load
@@ -1539,7 +1559,7 @@ gemm_kernel(const GemmArgs p)
     // which fact_tail_timeouts reads.  (Every thread learns of it through a word of the first
     // wave's prefetch sink: the operand stages may still be read by slower waves.)
     tail_gave_up = false;
-    if (in_tail && !tail_producer) {
+    if (PF && in_tail && !tail_producer) {          // (the host never splits the tail of a configuration without a sink)
         unsigned long long *flags = p_launch.tail_flags + (int64_t)tail_tile * tail_parts;
         volatile int *verdict = (volatile int *)(smem + lds_bytes(BM, BN, WGM, WGN, BK, STAGES));
         const int tid = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) + wave * 64;      // (derived anew: not kept across the K loop)

@@ -18,6 +18,7 @@ struct ConfigDesc {
     // operand ring, or the epilogue's per-wave fp32 staging regions if those are larger
     int lds_bytes() const { return fact::lds_total(bm, bn, wm, wn, bk, stages); }
     int threads() const { return wm * wn * 64; }
+    bool has_prefetch() const { return fact::has_prefetch(bm, bn, wm, wn, bk, stages); }      // and with it the sink a tail split's collector needs
     bool gate_capable() const { return true; }      // every wave tile has an even number of MFMA tiles along N
     bool serves(int trans_b) const { return trans_b || plain_b_supported(bn); }      // 192-wide tiles: B as [N][K] only
 };
