@@ -184,6 +184,14 @@ def main():
         out["attention"] = workbench.time_attention(args.steps, args.warmup)
         out["blocks"] = workbench.time_blocks()
         out["paper_shapes"] = workbench.time_all(args.steps, args.warmup, names=["p1.", "p3.", "p6.", "pb.", "pc."])
+        # the headline workload in the paper's own precision (IEEE binary16 in and out, fp32 accumulation)
+        h = wl.config2_f16(n)
+        Ah, Bh, bh = h["A"].cuda(), h["B"].cuda(), h["bias"].cuda()
+        Ch = torch.empty(n, n, dtype=torch.float16, device="cuda")
+        eph = fact.Epilogue(bias=bh, f16=1)
+        ms16 = time_calls(lambda: fact.binding.check(fact.fact_gemm(n, n, n, Ah, n, Bh, n, 0, Ch, n, eph)), args.steps, args.warmup, 50.0)
+        out["fp16"] = {f"square{n}+bias": {"ms": round(ms16, 5), "tflops": round(flops / (ms16 * 1e-3) / 1e12, 2),
+                                           "pct_mfma_peak": round(100.0 * flops / (ms16 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)}}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
