@@ -139,3 +139,27 @@ def test_new_entry_points_validate_on_the_host_before_any_gpu_call():
     assert fact.fact_block_forward(fact.Block(2, 128, 256, 4, 2, 64, 512, 1, fact.ACT_SILU_GATE, **w), p, p, p, n, 0) == -5
     assert fact.fact_gemm_f32out_workspace_bytes(256, 256, 4096, 1) == 0          # K whole: the main kernel writes fp32 itself
     assert fact.fact_gemm_f32out_workspace_bytes(256, 256, 4096, 4) == 4 * 256 * 256 * 4
+
+
+def test_two_per_compute_unit_configuration_and_fp16_field_host_logic():
+    """Configuration 15 (128 x 192, 2 stages) takes exactly half a compute unit's LDS, so two of its
+    work-groups share one; it has no prefetch sink, hence no tail split.  The f16 field is validated
+    before anything touches the GPU."""
+    n = fact.fact_num_configs()
+    assert n >= 16
+    bm, bn, wm, wn, lds = fact.fact_config_info(15)
+    assert (bm, bn, wm, wn) == (128, 192, 2, 2) and lds == 80 * 1024 and 2 * lds <= 160 * 1024
+    bm14, bn14, _, _, lds14 = fact.fact_config_info(14)                 # the same tile on 3 stages, with the sink
+    assert (bm14, bn14) == (128, 192) and lds14 == 3 * (128 + 192) * 128 + 4 * 256
+    # every other configuration either fits twice with its sink or does not fit twice at all
+    for c in range(n):
+        l = fact.fact_config_info(c)[4]
+        assert l <= 160 * 1024 and (l <= 80 * 1024 or l > 80 * 1024 + 2048 or c == 15), (c, l)
+    p = 4096                                   # a non-NULL, 16-byte aligned number; never dereferenced
+    # (832 tiles: a partly filled last round on 256 or 512 slots)  a tail split cannot use configuration 15;
+    # the same request on configuration 14 only lacks a workspace
+    ep = fact.Epilogue()
+    assert fact.fact_gemm_ex(1, 8192, 2496, 4096, p, 4096, 0, p, 4096, 0, 1, p, 2496, 0, ep, 15, -2, 4, None, 0, 0) == -7
+    assert fact.fact_gemm_ex(1, 8192, 2496, 4096, p, 4096, 0, p, 4096, 0, 1, p, 2496, 0, ep, 14, -2, 4, None, 0, 0) == -6
+    assert fact.fact_gemm(64, 64, 64, p, 64, p, 64, 0, p, 64, fact.Epilogue(f16=2), 0) == -5
+    assert fact.fact_gemm(64, 64, 64, p, 64, p, 64, 0, p, 64, fact.Epilogue(f16=-1), 0) == -5
