@@ -94,8 +94,9 @@ typedef struct fact_epilogue {
                                Sections 5.2.3 - 5.2.5).  Same kernels with the fp16 matrix instruction, fp32
                                accumulation, one rounding to nearest even at the store (overflow gives infinity);
                                same layouts, alignment rules, tile table and error codes.  Taken by fact_gemm,
-                               fact_gemm_batched, fact_gemm_splitk(_static) and fact_gemm_ex; the block entry
-                               points (fact_block_mlp, fact_attention, fact_block_forward) compute in bf16 only.
+                               fact_gemm_batched, fact_gemm_splitk(_static) and fact_gemm_ex (and fact_block_mlp_f16
+                               is fact_block_mlp with it); fact_attention, fact_norm, fact_rope and
+                               fact_block_forward compute in bf16 only.
                                0 (and a NULL epilogue): bf16.  Other values: FACT_ERR_EPILOGUE. */
 } fact_epilogue;
 
@@ -196,6 +197,14 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
                    const void *X, const void *W1, const void *W1u, const void *b1, int act,
                    const void *W2, const void *b2, const void *R,
                    void *H, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/* The same block with every 16-bit tensor (X, the weights and biases, R, H, Y) in IEEE binary16, the
+ * precision the paper runs its two blocks in (Sections 5.2.4 and 5.2.5: fp16 compute, fp32 accumulator).
+ * Same arguments, workspace size, launches and error codes as fact_block_mlp. */
+int fact_block_mlp_f16(int64_t T, int64_t d_model, int64_t d_ff,
+                       const void *X, const void *W1, const void *W1u, const void *b1, int act,
+                       const void *W2, const void *b2, const void *R,
+                       void *H, void *Y, void *ws, size_t ws_bytes, void *stream);
 
 size_t fact_block_mlp_workspace_bytes(int64_t T, int64_t d_model, int64_t d_ff, int act);
 

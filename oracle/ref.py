@@ -253,32 +253,32 @@ def gemm_epilogue(A, B, trans_b=False, bias=None, residual=None, act=ACT_NONE, r
     return Ref(z=z, bound=bound, bits=round_to(z, fmt), rows=rows_arr, fmt=fmt)
 
 
-def block_mlp(X, W1, W1u, b1, act, W2, b2, R, rows=None, H_bits=None):
+def block_mlp(X, W1, W1u, b1, act, W2, b2, R, rows=None, H_bits=None, fmt="bf16"):
     """Two-GEMM feed-forward block (Sections 5.2.4 and 5.2.5).
 
-    H = act(X W1^T + b1), rounded to bf16 because it is stored as bf16 between
-    the two GEMMs;  Y = H W2^T + b2 + R.  W1 is [d_ff, d]; with ACT_SILU_GATE W1
+    H = act(X W1^T + b1), rounded to the 16-bit format (bf16, or binary16 with
+    fmt="f16") because it is stored in it between the two GEMMs;  Y = H W2^T + b2 + R.  W1 is [d_ff, d]; with ACT_SILU_GATE W1
     is the gate weight and W1u the up weight, each [d_ff, d].  W2 is [d, d_ff].
 
     If H_bits is given (the bf16 H another implementation produced, all rows),
     the second stage consumes it instead of the oracle's own H: the stage-wise
     strict check.  Returns (ref_H, ref_Y).
     """
-    W1 = as_bits(W1)
+    W1 = as_bits(W1, fmt)
     if act == ACT_SILU_GATE:
-        W = np.concatenate([W1, as_bits(W1u)], axis=0)
-        ref_h = gemm_epilogue(X, W, True, None, None, ACT_SILU_GATE, rows)
+        W = np.concatenate([W1, as_bits(W1u, fmt)], axis=0)
+        ref_h = gemm_epilogue(X, W, True, None, None, ACT_SILU_GATE, rows, fmt)
     else:
-        ref_h = gemm_epilogue(X, W1, True, b1, None, act, rows)
+        ref_h = gemm_epilogue(X, W1, True, b1, None, act, rows, fmt)
     if H_bits is None:
         H = ref_h.bits
-        ref_y = gemm_epilogue(H, W2, True, b2, None, ACT_NONE, None)
+        ref_y = gemm_epilogue(H, W2, True, b2, None, ACT_NONE, None, fmt)
         if R is not None:
-            r = widen(np.ascontiguousarray(as_bits(R)[ref_h.rows, : ref_y.z.shape[1]]))
+            r = widen(np.ascontiguousarray(as_bits(R, fmt)[ref_h.rows, : ref_y.z.shape[1]]), fmt)
             z = ref_y.z + r
-            ref_y = Ref(z=z, bound=ref_y.bound + np.abs(r), bits=round_bf16(z), rows=ref_h.rows)
+            ref_y = Ref(z=z, bound=ref_y.bound + np.abs(r), bits=round_to(z, fmt), rows=ref_h.rows, fmt=fmt)
         else:
-            ref_y = Ref(z=ref_y.z, bound=ref_y.bound, bits=ref_y.bits, rows=ref_h.rows)
+            ref_y = Ref(z=ref_y.z, bound=ref_y.bound, bits=ref_y.bits, rows=ref_h.rows, fmt=fmt)
     else:
-        ref_y = gemm_epilogue(as_bits(H_bits), W2, True, b2, R, ACT_NONE, ref_h.rows)
+        ref_y = gemm_epilogue(as_bits(H_bits, fmt), W2, True, b2, R, ACT_NONE, ref_h.rows, fmt)
     return ref_h, ref_y

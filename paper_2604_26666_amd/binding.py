@@ -99,6 +99,7 @@ def lib():
         L.fact_gemm_f32out_workspace_bytes.restype = _size
         L.fact_block_mlp.argtypes = [_i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr, _int, _ptr, _ptr, _ptr,
                                      _ptr, _ptr, _ptr, _size, _ptr]
+        L.fact_block_mlp_f16.argtypes = L.fact_block_mlp.argtypes
         L.fact_block_mlp_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
         L.fact_block_mlp_workspace_bytes.restype = _size
         L.fact_gemm_ex.argtypes = [_i64, _i64, _i64, _i64, _ptr, _i64, _i64, _ptr, _i64, _i64, _int,
@@ -147,7 +148,7 @@ def lib():
         L.fact_registry_clear.restype = None
         L.fact_registry_size.argtypes = []
         L.fact_registry_size.restype = _int
-        for name in ("fact_gemm", "fact_gemm_batched", "fact_gemm_splitk", "fact_block_mlp", "fact_gemm_ex",
+        for name in ("fact_gemm", "fact_gemm_batched", "fact_gemm_splitk", "fact_block_mlp", "fact_block_mlp_f16", "fact_gemm_ex",
                      "fact_num_configs", "fact_config_info", "fact_select_config", "fact_version"):
             getattr(L, name).restype = _int
         _lib = L
@@ -221,6 +222,12 @@ def fact_block_mlp(T, d_model, d_ff, X, W1, W1u, b1, act, W2, b2, R, H, Y, ws, w
     return lib().fact_block_mlp(T, d_model, d_ff, _addr(X), _addr(W1), _addr(W1u), _addr(b1), int(act),
                                 _addr(W2), _addr(b2), _addr(R), _addr(H), _addr(Y), _addr(ws), int(ws_bytes),
                                 _stream(stream))
+
+
+def fact_block_mlp_f16(T, d_model, d_ff, X, W1, W1u, b1, act, W2, b2, R, H, Y, ws, ws_bytes, stream=None):
+    return lib().fact_block_mlp_f16(T, d_model, d_ff, _addr(X), _addr(W1), _addr(W1u), _addr(b1), int(act),
+                                    _addr(W2), _addr(b2), _addr(R), _addr(H), _addr(Y), _addr(ws), int(ws_bytes),
+                                    _stream(stream))
 
 
 def fact_block_mlp_workspace_bytes(T, d_model, d_ff, act):

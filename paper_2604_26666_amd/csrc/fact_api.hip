@@ -549,10 +549,10 @@ size_t fact_block_mlp_workspace_bytes(int64_t T, int64_t d_model, int64_t d_ff, 
     return b1 > b2 ? b1 : b2;
 }
 
-int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
-                   const void *X, const void *W1, const void *W1u, const void *b1, int act,
-                   const void *W2, const void *b2, const void *R,
-                   void *H, void *Y, void *ws, size_t ws_bytes, void *stream)
+static int block_mlp_impl(int f16, int64_t T, int64_t d_model, int64_t d_ff,
+                          const void *X, const void *W1, const void *W1u, const void *b1, int act,
+                          const void *W2, const void *b2, const void *R,
+                          void *H, void *Y, void *ws, size_t ws_bytes, void *stream)
 {
     if (!X || !W1 || !W2 || !H || !Y) return FACT_ERR_NULL;
     if (act != FACT_ACT_NONE && act != FACT_ACT_GELU_TANH && act != FACT_ACT_SILU_GATE) return FACT_ERR_EPILOGUE;
@@ -567,6 +567,7 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
     std::memset(&e1, 0, sizeof e1);
     e1.bias = b1;
     e1.act = act;
+    e1.f16 = f16;
     Problem q1{1, T, gated ? 2 * d_ff : d_ff, d_model, X, d_model, 0, W1, d_model, 0, 1,
                gated ? W1u : nullptr, H, d_ff, 0, e1};
     // GEMM 2: Y = H W2^T + b2 + R  (may split K = d_ff when the table says so and ws allows)
@@ -576,6 +577,7 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
     e2.residual = R;
     e2.ldr = d_model;
     e2.act = FACT_ACT_NONE;
+    e2.f16 = f16;
     Problem q2{1, T, d_model, d_ff, H, d_ff, 0, W2, d_ff, 0, 1, nullptr, Y, d_model, 0, e2};
     // everything either launch could refuse is checked before the first one: on error nothing runs
     int rc = validate(q1);
@@ -589,6 +591,22 @@ int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
     rc = run(q1, -1, p1.split < -1 ? 0 : 1, 0, p1.split < -1, ws, ws_bytes, (hipStream_t)stream);
     if (rc != FACT_OK) return rc;
     return run(q2, -1, 0, 0, need > 0, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int fact_block_mlp(int64_t T, int64_t d_model, int64_t d_ff,
+                   const void *X, const void *W1, const void *W1u, const void *b1, int act,
+                   const void *W2, const void *b2, const void *R,
+                   void *H, void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return block_mlp_impl(0, T, d_model, d_ff, X, W1, W1u, b1, act, W2, b2, R, H, Y, ws, ws_bytes, stream);
+}
+
+int fact_block_mlp_f16(int64_t T, int64_t d_model, int64_t d_ff,
+                       const void *X, const void *W1, const void *W1u, const void *b1, int act,
+                       const void *W2, const void *b2, const void *R,
+                       void *H, void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return block_mlp_impl(1, T, d_model, d_ff, X, W1, W1u, b1, act, W2, b2, R, H, Y, ws, ws_bytes, stream);
 }
 
 int fact_num_configs(void) { return kNumConfigs; }

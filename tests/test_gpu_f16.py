@@ -243,3 +243,58 @@ def test_square_8192_bias_fp16_one_row_of_every_eight():
         r = ref.gemm_epilogue(c["A"], c["B"], False, bias=c["bias"], rows=part, fmt="f16")
         s = check.assert_close(got, r, rows="full", what=f"fp16 8192^3 rows {part[0]}..")
         assert s["bits_equal_frac"] > 0.9, s         # fp32 accumulation moves few results across a rounding boundary
+
+
+# ---- the two-GEMM block in fp16 ---------------------------------------------------------------
+
+@pytest.mark.parametrize("kind", ["gelu", "swiglu"])
+def test_block_mlp_fp16_reduced(kind):
+    T, d, dff = 520, 256, 768
+    X = wl.normal_f16((T, d), 1.0, "hm.X")
+    W1 = wl.normal_f16((dff, d), 0.05, "hm.W1")
+    Wu = wl.normal_f16((dff, d), 0.05, "hm.Wu")
+    b1 = wl.normal_f16((dff,), 0.05, "hm.b1")
+    W2 = wl.normal_f16((d, dff), 0.05, "hm.W2")
+    b2 = wl.normal_f16((d,), 0.05, "hm.b2")
+    R = wl.normal_f16((T, d), 1.0, "hm.R")
+    gated = kind == "swiglu"
+    act = fact.ACT_SILU_GATE if gated else fact.ACT_GELU_TANH
+    Hd, Yd = poisoned(T, dff), poisoned(T, d)
+    need = fact.fact_block_mlp_workspace_bytes(T, d, dff, act)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    rc = fact.fact_block_mlp_f16(T, d, dff, X.cuda(), W1.cuda(), Wu.cuda() if gated else None,
+                                 None if gated else b1.cuda(), act, W2.cuda(), None if gated else b2.cuda(),
+                                 R.cuda(), Hd, Yd, ws, need)
+    fact.binding.check(rc, "fact_block_mlp_f16")
+    torch.cuda.synchronize()
+    Hg, Yg = wl.bits(Hd.cpu().contiguous()), wl.bits(Yd.cpu().contiguous())
+    args = (X, W1, Wu if gated else None, None if gated else b1, act, W2, None if gated else b2, R)
+    h, y = ref.block_mlp(*args, fmt="f16")
+    check.assert_close(Hg, h, what="fp16 H")
+    check.assert_close(Yg, y, what="fp16 Y end to end")
+    _, y2 = ref.block_mlp(*args, H_bits=Hg, fmt="f16")                   # the oracle's second GEMM fed the GPU's H bits
+    s = check.assert_close(Yg, y2, what="fp16 Y stage-wise")
+    assert s["bits_equal_frac"] >= 0.97, s
+
+
+def test_block_mlp_fp16_paper_gpt_shape_sampled_rows():
+    # the MLP of the paper's GPT block (Section 5.2.4: 768 -> 3072 -> 768, GELU) at 8192 tokens, in its precision
+    T, d, dff = 8192, 768, 3072
+    X = wl.normal_f16((T, d), 1.0, "hp.X")
+    W1 = wl.normal_f16((dff, d), 0.02, "hp.W1")
+    b1 = wl.normal_f16((dff,), 0.02, "hp.b1")
+    W2 = wl.normal_f16((d, dff), 0.02, "hp.W2")
+    b2 = wl.normal_f16((d,), 0.02, "hp.b2")
+    R = wl.normal_f16((T, d), 1.0, "hp.R")
+    Hd = torch.empty(T, dff, dtype=torch.float16, device="cuda")
+    Yd = torch.empty(T, d, dtype=torch.float16, device="cuda")
+    need = fact.fact_block_mlp_workspace_bytes(T, d, dff, fact.ACT_GELU_TANH)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    fact.binding.check(fact.fact_block_mlp_f16(T, d, dff, X.cuda(), W1.cuda(), None, b1.cuda(), fact.ACT_GELU_TANH, W2.cuda(), b2.cuda(),
+                                               R.cuda(), Hd, Yd, ws, need))
+    torch.cuda.synchronize()
+    Hg, Yg = wl.bits(Hd.cpu().contiguous()), wl.bits(Yd.cpu().contiguous())
+    rows = wl.choice_rows(T, 200, "hp.rows", edges=(0, 127, 128, 255, 256, T - 1))
+    h, y = ref.block_mlp(X, W1, None, b1, fact.ACT_GELU_TANH, W2, b2, R, rows=rows, H_bits=Hg, fmt="f16")
+    check.assert_close(Hg, h, rows="full", what="fp16 GPT MLP H")
+    check.assert_close(Yg, y, rows="full", what="fp16 GPT MLP Y")

@@ -254,3 +254,44 @@ def test_check_uses_the_format_of_the_reference():
     near[0, 0] = 0x3C01
     s = check.compare(near, r)
     assert abs(s["max_err_ulp"] - 1.0) < 1e-12
+
+
+# ---- the two-GEMM block in fp16 ---------------------------------------------------------------
+
+def test_block_mlp_stores_h_in_binary16_between_the_two_gemms():
+    # X W1^T = 1 + 2^-10 and 1 + 2^-11 + 2^-13: the first is a binary16 number (bf16 would make it 1),
+    # the second rounds to 1 + 2^-10 in binary16 (above the tie); Y = 4 H + R shows which H was used
+    X = h(np.array([[1.0, 2.0 ** -10], [1.0, 2.0 ** -11 + 2.0 ** -13]]))
+    W1 = h(np.array([[1.0, 1.0]]))
+    W2 = h(np.array([[4.0], [0.5]]))
+    R = h(np.array([[0.0, 1.0], [2.0, 0.0]]))
+    rh, ry = ref.block_mlp(X, W1, None, None, ref.ACT_NONE, W2, None, R, fmt="f16")
+    assert [int(b) for b in rh.bits.ravel()] == [0x3C01, 0x3C01] and rh.fmt == "f16" and ry.fmt == "f16"
+    hv = 1.0 + 2.0 ** -10
+    assert (ry.z == np.array([[4 * hv, 0.5 * hv + 1.0], [4 * hv + 2.0, 0.5 * hv]])).all()
+    # rows: the second stage follows the first stage's row subset, the residual too
+    rh1, ry1 = ref.block_mlp(X, W1, None, None, ref.ACT_NONE, W2, None, R, rows=[1], fmt="f16")
+    assert (ry1.z == ry.z[[1]]).all() and (ry1.bits == ry.bits[[1]]).all() and (rh1.bits == rh.bits[[1]]).all()
+
+
+def test_block_mlp_fp16_against_a_numpy_composition():
+    g = np.random.default_rng(29)
+    T, d, dff = 12, 16, 40
+    f16 = lambda a: a.astype(np.float16)
+    X, W1, W1u, W2 = f16(g.standard_normal((T, d))), f16(g.standard_normal((dff, d)) * 0.3), f16(g.standard_normal((dff, d)) * 0.3), f16(g.standard_normal((d, dff)) * 0.3)
+    b1, b2, R = f16(g.standard_normal(dff) * 0.1), f16(g.standard_normal(d) * 0.1), f16(g.standard_normal((T, d)))
+    u = lambda a: a.view(np.uint16)
+    d64 = lambda a: a.astype(np.float64)
+    # GELU block with biases and residual
+    rh, ry = ref.block_mlp(u(X), u(W1), None, u(b1), ref.ACT_GELU_TANH, u(W2), u(b2), u(R), fmt="f16")
+    z1 = d64(X) @ d64(W1).T + d64(b1)
+    hz = 0.5 * z1 * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (z1 + 0.044715 * z1 ** 3)))
+    assert np.allclose(rh.z, hz, rtol=1e-13, atol=1e-14)
+    H = d64(rh.z.astype(np.float16))                      # numpy's own fp64 -> binary16 rounding of the oracle's H
+    assert (u(rh.z.astype(np.float16)) == rh.bits).all()
+    assert np.allclose(ry.z, H @ d64(W2).T + d64(b2) + d64(R), rtol=1e-13, atol=1e-13)
+    # gated block
+    rh, ry = ref.block_mlp(u(X), u(W1), u(W1u), None, ref.ACT_SILU_GATE, u(W2), None, None, fmt="f16")
+    gz, uz = d64(X) @ d64(W1).T, d64(X) @ d64(W1u).T
+    assert np.allclose(rh.z, gz / (1.0 + np.exp(-gz)) * uz, rtol=1e-13, atol=1e-14)
+    assert np.allclose(ry.z, d64(rh.z.astype(np.float16)) @ d64(W2).T, rtol=1e-13, atol=1e-13)
