@@ -800,6 +800,6 @@ int fact_registry_size(void)
 
 const char *fact_last_error(void) { return g_last_error; }
 
-int fact_version(void) { return 204; }
+int fact_version(void) { return 205; }
 
 }  // extern "C"

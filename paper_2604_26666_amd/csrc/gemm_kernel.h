@@ -1420,10 +1420,15 @@ gemm_kernel(const GemmArgs p)
     // newest STAGES-2 such groups and the prefetch behind the group it waits for
     constexpr int WAIT_N = (STAGES - 2) * (LOADS + (PF ? 1 : 0)) + (PF ? 1 : 0);
     // The address unit is shared by the CU's waves and takes one wave-wide load per 16 cycles, so a
-    // step's loads are spread evenly: over the first 3/4 of the step's MFMAs with a two-slot
-    // ring (they must have landed by its end), over nearly all of it with a deeper ring.
+    // step's loads are spread evenly: over the first half of the step's MFMAs with a two-slot
+    // ring (they must have landed by its end: a step of such a ring lasts about as long as the loads'
+    // latency, so the last load's issue time adds to it), over nearly all of it with a deeper ring.
+    // Same-box A/B of the two-slot span, 3/4 -> 1/2: 2048 x 6144 x 4096 on 256 x 192 tiles 72.6 -> 70.3 us
+    // (operands from HBM 79.7 -> 76.6), 8192^3 from HBM 713.7 -> 700.8 us, from the memory-side cache
+    // unchanged; 3/8 and 1/4 are slower again (address-unit contention stalls the matrix pipe).  Deeper
+    // rings: 15/16, 3/4 and 1/2 measure the same or worse in that order.
     constexpr int TG = U * NMFMA;                        // MFMAs (= gaps) per K step
-    constexpr int LOAD_SPAN = STAGES > 2 ? (TG * 15) / 16 : (TG * 3) / 4;
+    constexpr int LOAD_SPAN = STAGES > 2 ? (TG * 15) / 16 : TG / 2;
     auto load_gap = [](int l) constexpr { const int g = 1 + (l * LOAD_SPAN) / LOADS; return g < TG ? g : TG - 1; };
     constexpr int SPAN = (NMFMA * 7) / 8 > 0 ? (NMFMA * 7) / 8 : 1;
     Steady sc = steady_at(STAGES - 1);
