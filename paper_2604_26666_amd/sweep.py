@@ -19,8 +19,9 @@ know the oracle.)
 
 Run on a machine with the GPU:  python -m paper_2604_26666_amd.sweep [case-prefix ...]
 Then rebuild the library (python -m paper_2604_26666_amd.build): it compiles csrc/tile_table.inc,
-which this tool regenerates from the registry file.  The raw per-candidate log goes to
-gpurun_out/sweep_log.json (not kept in the repository).
+which this tool regenerates from the registry file.  The raw per-candidate log goes to the file
+the environment variable FACT_SWEEP_LOG names (default: fact_sweep_log.json in the system's
+temporary directory; it is not kept in the repository).
 """
 import json
 import os
@@ -34,7 +35,7 @@ from . import workbench as wb
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-RAW_LOG = os.path.join(ROOT, "gpurun_out", "sweep_log.json")
+RAW_LOG = os.environ.get("FACT_SWEEP_LOG") or os.path.join(__import__("tempfile").gettempdir(), "fact_sweep_log.json")
 CONFIG_GUARDED = -2
 
 
@@ -168,7 +169,7 @@ def main(argv):
     merged = registry.merge(old, new)
     registry.write(merged)
     registry.write_table_inc(merged)
-    os.makedirs(os.path.dirname(RAW_LOG), exist_ok=True)
+    os.makedirs(os.path.dirname(os.path.abspath(RAW_LOG)), exist_ok=True)
     prev = {}
     if os.path.exists(RAW_LOG):
         try:
