@@ -7,7 +7,8 @@
  * the two-GEMM feed-forward patterns with fused activation epilogues (Section
  * 5.2.4 "MLP with GELU", Section 5.2.5 "SwiGLU MLP"), with reduced-precision
  * inputs and an fp32 accumulator (Listing 1: reduced-precision inputs with fp32
- * accumulator).  Here the inputs and outputs are bf16.
+ * accumulator).  Here the inputs and outputs are bf16, or IEEE binary16 - the
+ * paper's own precision - when fact_epilogue.f16 is set.
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller.  The library
